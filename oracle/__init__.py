@@ -1,0 +1,176 @@
+"""ctypes loader for the SASQ CPU oracle (oracle/sasq_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: importable from tests/, from __graft_entry__.smoke()
+and from bench.py's cpu_baseline leg.  The HIP library and its Python binding
+never import this package, and this package never imports them.
+
+All 16-bit float tensors cross this interface as numpy uint16 bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sasq_oracle.c")
+_LIB = os.path.join(_HERE, "libsasq_oracle.so")
+
+DT = {"f16": 0, "bf16": 1}
+WF = {"int8": 0, "int4": 1}
+NO_ROUND, NO_CLAMP, STE_ON_V = 1, 2, 4
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, OpenMP over rows, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+               "-shared", "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        L.sasq_oracle_scale_sgd.restype = ctypes.c_float
+        L.sasq_oracle_scale_sgd.argtypes = [ctypes.c_float] * 3
+        L.sasq_oracle_inv_scale.restype = ctypes.c_float
+        L.sasq_oracle_inv_scale.argtypes = [ctypes.c_float]
+        L.sasq_oracle_threads.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _u16(a: np.ndarray) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint16, a.dtype
+    return a
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with status {rc}")
+
+
+def threads() -> int:
+    return int(lib().sasq_oracle_threads())
+
+
+def decode16(bits: np.ndarray, dtype: str) -> np.ndarray:
+    bits = _u16(bits)
+    out = np.empty(bits.shape, dtype=np.float64)
+    lib().sasq_oracle_decode16(_p(bits), _p(out), ctypes.c_int64(bits.size), DT[dtype])
+    return out
+
+
+def encode16(vals: np.ndarray, dtype: str) -> np.ndarray:
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    out = np.empty(vals.shape, dtype=np.uint16)
+    lib().sasq_oracle_encode16(_p(vals), _p(out), ctypes.c_int64(vals.size), DT[dtype])
+    return out
+
+
+def inv_scale(s: float) -> np.float32:
+    return np.float32(lib().sasq_oracle_inv_scale(ctypes.c_float(float(s))))
+
+
+def fakequant_fwd(x: np.ndarray, s: float, bits: int, dtype: str, flags: int = 0
+                  ) -> Tuple[np.ndarray, np.ndarray]:
+    """Returns (y bits uint16 [rows, cols], codes int8 [rows, cols])."""
+    x = _u16(x)
+    rows, cols = (x.shape if x.ndim == 2 else (1, x.size))
+    y = np.empty(x.shape, dtype=np.uint16)
+    codes = np.empty(x.shape, dtype=np.int8)
+    rc = lib().sasq_oracle_fakequant_fwd(_p(x), ctypes.c_float(float(s)), _p(y), _p(codes),
+                                         ctypes.c_int64(rows), ctypes.c_int64(cols),
+                                         int(bits), DT[dtype], int(flags))
+    _check(rc, "fakequant_fwd")
+    return y, codes
+
+
+def fakequant_bwd(x: np.ndarray, dy: np.ndarray, s: float, bits: int, dtype: str, flags: int = 0,
+                  want_dx: bool = True):
+    """Returns dict(dx=uint16 bits, ds=np.float32, ds64=float, sum_abs=float)."""
+    x, dy = _u16(x), _u16(dy)
+    assert x.shape == dy.shape
+    rows, cols = (x.shape if x.ndim == 2 else (1, x.size))
+    dx = np.empty(x.shape, dtype=np.uint16) if want_dx else None
+    ds = ctypes.c_float(0.0)
+    ds64 = ctypes.c_double(0.0)
+    sabs = ctypes.c_double(0.0)
+    rc = lib().sasq_oracle_fakequant_bwd(_p(x), _p(dy), ctypes.c_float(float(s)), _p(dx),
+                                         ctypes.byref(ds), ctypes.byref(ds64), ctypes.byref(sabs),
+                                         ctypes.c_int64(rows), ctypes.c_int64(cols),
+                                         int(bits), DT[dtype], int(flags))
+    _check(rc, "fakequant_bwd")
+    return {"dx": dx, "ds": np.float32(ds.value), "ds64": float(ds64.value),
+            "sum_abs": float(sabs.value)}
+
+
+def static_linear(x: np.ndarray, s: float, wq: np.ndarray, s_w: np.ndarray,
+                  bias: Optional[np.ndarray], a_bits: int, w_fmt: str, dtype: str,
+                  want_y: bool = True, want_acc: bool = True, want_xq: bool = True):
+    """x: [M,K] uint16 bits; wq: [N,K] int8 or [N,K/2] uint8 (packed int4).
+    Returns dict(y=uint16 [M,N], acc=int32 [M,N], xq=int8 [M,K])."""
+    x = _u16(x)
+    M, K = x.shape
+    wq = np.ascontiguousarray(wq)
+    assert wq.dtype in (np.int8, np.uint8)
+    N = wq.shape[0]
+    assert wq.shape[1] == (K if w_fmt == "int8" else K // 2), (wq.shape, K, w_fmt)
+    s_w = np.ascontiguousarray(s_w, dtype=np.float32)
+    assert s_w.shape == (N,)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+        assert bias.shape == (N,)
+    y = np.empty((M, N), dtype=np.uint16) if want_y else None
+    acc = np.empty((M, N), dtype=np.int32) if want_acc else None
+    xq = np.empty((M, K), dtype=np.int8) if want_xq else None
+    rc = lib().sasq_oracle_static_linear(_p(x), ctypes.c_float(float(s)), _p(wq), _p(s_w), _p(bias),
+                                         _p(y), _p(acc), _p(xq), ctypes.c_int64(M),
+                                         ctypes.c_int64(N), ctypes.c_int64(K), int(a_bits),
+                                         WF[w_fmt], DT[dtype])
+    _check(rc, "static_linear")
+    return {"y": y, "acc": acc, "xq": xq}
+
+
+def quantize_weight(w: np.ndarray, w_fmt: str) -> Tuple[np.ndarray, np.ndarray]:
+    """w: fp32 [N,K] -> (wq int8 [N,K] | uint8 [N,K/2], s_w fp32 [N])."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    N, K = w.shape
+    if w_fmt == "int8":
+        wq = np.empty((N, K), dtype=np.int8)
+    else:
+        wq = np.zeros((N, K // 2), dtype=np.uint8)
+    s_w = np.empty((N,), dtype=np.float32)
+    rc = lib().sasq_oracle_quantize_weight(_p(w), _p(wq), _p(s_w), ctypes.c_int64(N),
+                                           ctypes.c_int64(K), WF[w_fmt])
+    _check(rc, "quantize_weight")
+    return wq, s_w
+
+
+def absmax_scale(x: np.ndarray, bits: int, dtype: str) -> np.float32:
+    x = _u16(x)
+    s = ctypes.c_float(0.0)
+    rc = lib().sasq_oracle_absmax_scale(_p(x), ctypes.byref(s), ctypes.c_int64(x.size),
+                                        int(bits), DT[dtype])
+    _check(rc, "absmax_scale")
+    return np.float32(s.value)
+
+
+def scale_sgd(s: float, ds: float, lr: float) -> np.float32:
+    return np.float32(lib().sasq_oracle_scale_sgd(ctypes.c_float(float(s)), ctypes.c_float(float(ds)),
+                                                  ctypes.c_float(float(lr))))
