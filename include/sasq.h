@@ -1,0 +1,166 @@
+/*
+ * sasq.h -- C ABI of the SASQ hot-path library for AMD MI355X (gfx950).
+ *
+ * SASQ (Static Activation Scaling for Quantization-aware training) trains nothing but the
+ * activation quantization factors of an LLM's linear layers and then runs those layers with
+ * the trained factors held fixed.  This library is the data-parallel hot path of that method:
+ *
+ *   training:   x' = fakequant(x; s)                     sasq_fakequant_fwd
+ *               dx, ds = backward(x, dy; s)              sasq_fakequant_bwd
+ *               s <- s - lr * ds                         sasq_scale_sgd
+ *   inference:  Y = s * (q(X) . Wq^T) * s_w (+ bias)     sasq_static_linear
+ *   set-up:     Wq, s_w from frozen fp32 weights         sasq_quantize_weight
+ *               s0 = max|X| / (2^(bits-1) - 1)           sasq_absmax_scale
+ *
+ * Conventions shared by every entry point
+ *   - Every data pointer is DEVICE memory owned by the caller (the library never allocates,
+ *     frees or keeps a pointer).  Scalars that are trained or produced on the device (s, ds)
+ *     are device pointers too, so a training step needs no host synchronisation.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work on that stream and return; outputs are valid once the stream has drained.
+ *   - Matrices are dense row-major.  An activation matrix is [tokens, channels] (Sec. 2, Fig. 2).
+ *   - 16-bit tensors are IEEE binary16 (SASQ_F16) or bfloat16 (SASQ_BF16).
+ *   - Base pointers of 16-bit and weight tensors must be 16-byte aligned (SASQ_ERR_ALIGN).
+ *   - Return value: a sasq_status.  Arguments are validated on the host before anything is
+ *     launched; on error nothing has been enqueued.  The library never throws or aborts.
+ *   - NOT validated (device-resident, checking would need a sync): *s finite and non-zero,
+ *     inputs free of NaN.  Behaviour for such values is unspecified (but in-bounds).
+ *   - Workspaces come from sasq_workspace_init(): a workspace is caller-owned device memory
+ *     that must have been passed ONCE to sasq_workspace_init before its first use, may be reused
+ *     by any number of later calls, and must not be used by two calls that can overlap in time.
+ *
+ * Numerical contract (the paper gives real-number formulas; these make them bit-level)
+ *   - round(x/s) is round-half-to-even of the exact product x * inv_s, inv_s = fl32(1/s).
+ *   - the straight-through clamp indicator is taken on the rounded value, bounds inclusive.
+ *   - dequantisation is one fp32 multiply then one round-to-nearest-even to the 16-bit type.
+ */
+#ifndef SASQ_H
+#define SASQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SASQ_OK = 0,
+    SASQ_ERR_NULL = 1,         /* a required pointer is NULL                               */
+    SASQ_ERR_SHAPE = 2,        /* a size is <= 0, too large, or violates a stated multiple */
+    SASQ_ERR_ALIGN = 3,        /* a base pointer is not 16-byte aligned                    */
+    SASQ_ERR_UNSUPPORTED = 4,  /* unknown enum value or bits outside [2, 8]                */
+    SASQ_ERR_WORKSPACE = 5,    /* workspace NULL or smaller than the matching query        */
+    SASQ_ERR_LAUNCH = 6        /* the HIP runtime reported an error at launch              */
+} sasq_status;
+
+typedef enum { SASQ_F16 = 0, SASQ_BF16 = 1 } sasq_dtype;            /* activation / output type */
+typedef enum { SASQ_W_INT8 = 0, SASQ_W_INT4_PACKED = 1 } sasq_wfmt; /* frozen weight storage    */
+
+/* Human-readable name of a status code (static storage, host pointer). */
+const char* sasq_status_string(int status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int sasq_version(void);
+
+/*
+ * Prepare a workspace for use by the calls below (zero-fills its control words on `stream`).
+ * Call once per workspace allocation, before the first call that uses it.
+ */
+int sasq_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Fake quantization, forward (Sec. 4.2 "fake quantization operators"; Sec. 3, Eq. 1;
+ * dequantisation X' = S_x * X_int, Sec. 4.3, Eq. 5):
+ *     q = clamp(round(x / s), -2^(bits-1), 2^(bits-1) - 1),   y = s * q.
+ *   x      [rows, cols] device, 16-bit `dt`, read only
+ *   s      device, one fp32: the per-tensor activation quantization factor
+ *   y      [rows, cols] device, 16-bit `dt`, written (may alias x)
+ *   codes  [rows, cols] device int8 or NULL: the integer codes q (for inspection and tests)
+ *   bits   2..8
+ */
+int sasq_fakequant_fwd(const void* x, const float* s, void* y, int8_t* codes,
+                       int64_t rows, int64_t cols, int bits, sasq_dtype dt, void* stream);
+
+/* Bytes of workspace sasq_fakequant_bwd needs for this shape (pure function, host only). */
+size_t sasq_fakequant_bwd_workspace(int64_t rows, int64_t cols);
+
+/*
+ * Fake quantization, backward with the straight-through estimator (Sec. 4.2, Eq. 4: the
+ * gradient of round is 1, the gradient of clamp is 1 inside the range and 0 outside), and the
+ * gradient of the scale, the only trained parameter (Sec. 4.2), by the chain rule:
+ *     m  = 1 if -2^(bits-1) <= round(x/s) <= 2^(bits-1)-1 else 0
+ *     dx = dy * m
+ *     ds = sum over all elements of dy * (q - m * x/s)         (overwritten, not accumulated)
+ *   x, dy  [rows, cols] device, 16-bit `dt`, read only
+ *   s      device fp32 scalar
+ *   dx     [rows, cols] device, 16-bit `dt`, written (may alias dy), or NULL to skip it
+ *   ds     device fp32 scalar, written.  The reduction order is fixed: repeated calls with the
+ *          same inputs give bit-identical results.
+ *   workspace  >= sasq_fakequant_bwd_workspace(rows, cols) bytes, initialised once
+ */
+int sasq_fakequant_bwd(const void* x, const void* dy, const float* s, void* dx, float* ds,
+                       int64_t rows, int64_t cols, int bits, sasq_dtype dt,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One plain SGD step on the scale (the optimiser state of SASQ is the scale alone, Sec. 4.2;
+ * the paper's own runs use AdamW, Sec. 5.1):  *s = fl32(*s - fl32(lr * *ds)).
+ */
+int sasq_scale_sgd(float* s, const float* ds, float lr, void* stream);
+
+/* Bytes of workspace sasq_static_linear needs (pure function, host only; may be 0). */
+size_t sasq_static_linear_workspace(int64_t M, int64_t N, int64_t K, sasq_wfmt wf);
+
+/*
+ * Static-inference quantized linear (Sec. 3, Eq. 2: Y = S_x * (X_int . W_int) * S_w, integer
+ * product first, inverse quantization after; bias not quantized).  The activation scale is a
+ * fixed input: nothing is reduced over X at run time (static quantization, Sec. 3; Sec. 4.5).
+ *     xq[m,k]  = clamp(round(X[m,k] / s), -2^(a_bits-1), 2^(a_bits-1) - 1)
+ *     acc[m,n] = sum_k xq[m,k] * Wq[n,k]                      (exact, int32)
+ *     Y[m,n]   = fl32(fl32(acc[m,n]) * fl32(s * s_w[n])) (+ bias[n])  -> 16-bit `dt`
+ *   x        [M, K] device 16-bit `dt`
+ *   s        device fp32 scalar
+ *   wq       [N, K] device int8 (SASQ_W_INT8), or [N, K/2] bytes (SASQ_W_INT4_PACKED): element k
+ *            even in the low nibble, k odd in the high nibble, two's complement, range [-8, 7]
+ *   s_w      [N] device fp32, one factor per output channel
+ *   bias     [N] device fp32 or NULL
+ *   y        [M, N] device 16-bit `dt`, written
+ *   acc_out  [M, N] device int32 or NULL; xq_out [M, K] device int8 or NULL (inspection/tests;
+ *            requesting either selects a slower code path)
+ *   K        multiple of 2 for int4.  Any M, N, K > 0 is accepted; the MFMA path is taken when
+ *            K is a multiple of 64, other shapes use a scalar kernel.
+ *   M*K, N*K, M*N must each be < 2^40; |acc| cannot overflow for K <= 131071.
+ *   workspace  >= sasq_static_linear_workspace(M, N, K, wf) bytes (NULL allowed when that is 0)
+ */
+int sasq_static_linear(const void* x, const float* s, const void* wq, const float* s_w,
+                       const float* bias, void* y, int32_t* acc_out, int8_t* xq_out,
+                       int64_t M, int64_t N, int64_t K, int a_bits, sasq_wfmt wf, sasq_dtype dt,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Quantize frozen weights, symmetric, one factor per output channel (Sec. 3, Eq. 1 applied to
+ * each row of W[N,K]; "the quantization granularity of weights is always per-channel", Sec. 5.1):
+ *     s_w[n]  = fl32(max_k |W[n,k]| / Qp)     (1 if the row is all zero),  Qp = 127 or 7
+ *     Wq[n,k] = clamp(round(W[n,k] / s_w[n]), -Qp-1, Qp)     (same rounding rule as activations)
+ *   w    [N, K] device fp32;  wq: [N, K] int8 or [N, K/2] packed int4 (K even);  s_w [N] fp32
+ */
+int sasq_quantize_weight(const float* w, void* wq, float* s_w, int64_t N, int64_t K,
+                         sasq_wfmt wf, void* stream);
+
+/* Bytes of workspace sasq_absmax_scale needs (pure function, host only). */
+size_t sasq_absmax_scale_workspace(int64_t rows, int64_t cols);
+
+/*
+ * Initial (post-training) scale of an activation tensor (Sec. 3, Eq. 1, right half; Sec. 4.1):
+ *     *s = fl32(max|x| / (2^(bits-1) - 1)).
+ * This is the dynamic-quantization reduction that static inference avoids; it is used once,
+ * to initialise s before training.
+ */
+int sasq_absmax_scale(const void* x, float* s, int64_t rows, int64_t cols, int bits,
+                      sasq_dtype dt, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SASQ_H */

@@ -1,0 +1,177 @@
+"""ctypes binding of libsasq.so: one Python function per C entry point of include/sasq.h.
+
+Only argument marshalling happens here (device pointers, sizes, the current HIP stream taken
+from PyTorch); every step of the path runs in the library's kernels.  Tensors must be device
+tensors, contiguous, of the dtypes the header states.  A non-zero status raises SasqError.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libsasq.so")
+
+SASQ_F16, SASQ_BF16 = 0, 1
+SASQ_W_INT8, SASQ_W_INT4_PACKED = 0, 1
+
+_DT = {torch.float16: SASQ_F16, torch.bfloat16: SASQ_BF16}
+
+
+class SasqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib().sasq_status_string(status).decode() if _LIB is not None else str(status)
+        super().__init__(f"{where}: {msg}")
+
+
+_LIB = None
+
+
+def _lib() -> ctypes.CDLL:
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2512_14481_amd.build` "
+                "(there is no CPU fallback for the SASQ kernels)")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, i32, vp, sz, f32 = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float
+        L.sasq_status_string.restype = ctypes.c_char_p
+        L.sasq_status_string.argtypes = [i32]
+        L.sasq_version.restype = i32
+        L.sasq_workspace_init.argtypes = [vp, sz, vp]
+        L.sasq_fakequant_fwd.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp]
+        L.sasq_fakequant_bwd_workspace.restype = sz
+        L.sasq_fakequant_bwd_workspace.argtypes = [i64, i64]
+        L.sasq_fakequant_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, sz, vp]
+        L.sasq_scale_sgd.argtypes = [vp, vp, f32, vp]
+        L.sasq_static_linear_workspace.restype = sz
+        L.sasq_static_linear_workspace.argtypes = [i64, i64, i64, i32]
+        L.sasq_static_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, sz, vp]
+        L.sasq_quantize_weight.argtypes = [vp, vp, vp, i64, i64, i32, vp]
+        L.sasq_absmax_scale_workspace.restype = sz
+        L.sasq_absmax_scale_workspace.argtypes = [i64, i64]
+        L.sasq_absmax_scale.argtypes = [vp, vp, i64, i64, i32, i32, vp, sz, vp]
+        _LIB = L
+    return _LIB
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("SASQ entry points take device tensors")
+    if not t.is_contiguous():
+        raise ValueError("SASQ entry points take contiguous tensors")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise SasqError(rc, where)
+
+
+def _want(t: Optional[torch.Tensor], dtype, name: str):
+    if t is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype not in _DT:
+        raise TypeError(f"activation dtype must be float16 or bfloat16, got {t.dtype}")
+    return _DT[t.dtype]
+
+
+def sasq_version() -> int:
+    return int(_lib().sasq_version())
+
+
+def sasq_workspace_init(workspace: torch.Tensor) -> None:
+    _check(_lib().sasq_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
+           "sasq_workspace_init")
+
+
+def new_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    """Allocate (with PyTorch) and initialise a workspace of at least nbytes."""
+    ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+    sasq_workspace_init(ws)
+    return ws
+
+
+def sasq_fakequant_fwd(x: torch.Tensor, s: torch.Tensor, y: torch.Tensor,
+                       codes: Optional[torch.Tensor] = None, bits: int = 8) -> None:
+    _want(s, torch.float32, "s"); _want(codes, torch.int8, "codes")
+    if y.dtype != x.dtype or y.shape != x.shape:
+        raise ValueError("y must match x")
+    rows, cols = (x.shape[0], x.numel() // max(x.shape[0], 1)) if x.dim() >= 1 else (1, 1)
+    _check(_lib().sasq_fakequant_fwd(_ptr(x), _ptr(s), _ptr(y), _ptr(codes), rows, cols, bits, _dt(x), _stream()),
+           "sasq_fakequant_fwd")
+
+
+def sasq_fakequant_bwd_workspace(rows: int, cols: int) -> int:
+    return int(_lib().sasq_fakequant_bwd_workspace(rows, cols))
+
+
+def sasq_fakequant_bwd(x: torch.Tensor, dy: torch.Tensor, s: torch.Tensor, dx: Optional[torch.Tensor],
+                       ds: torch.Tensor, workspace: torch.Tensor, bits: int = 8) -> None:
+    _want(s, torch.float32, "s"); _want(ds, torch.float32, "ds")
+    if dy.dtype != x.dtype or dy.shape != x.shape or (dx is not None and (dx.dtype != x.dtype or dx.shape != x.shape)):
+        raise ValueError("dy and dx must match x")
+    rows, cols = x.shape[0], x.numel() // max(x.shape[0], 1)
+    _check(_lib().sasq_fakequant_bwd(_ptr(x), _ptr(dy), _ptr(s), _ptr(dx), _ptr(ds), rows, cols, bits, _dt(x),
+                                     _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
+           "sasq_fakequant_bwd")
+
+
+def sasq_scale_sgd(s: torch.Tensor, ds: torch.Tensor, lr: float) -> None:
+    _want(s, torch.float32, "s"); _want(ds, torch.float32, "ds")
+    _check(_lib().sasq_scale_sgd(_ptr(s), _ptr(ds), ctypes.c_float(lr), _stream()), "sasq_scale_sgd")
+
+
+def sasq_static_linear_workspace(M: int, N: int, K: int, wf: int) -> int:
+    return int(_lib().sasq_static_linear_workspace(M, N, K, wf))
+
+
+def sasq_static_linear(x: torch.Tensor, s: torch.Tensor, wq: torch.Tensor, s_w: torch.Tensor,
+                       bias: Optional[torch.Tensor], y: torch.Tensor, wf: int = SASQ_W_INT8,
+                       workspace: Optional[torch.Tensor] = None, acc_out: Optional[torch.Tensor] = None,
+                       xq_out: Optional[torch.Tensor] = None, a_bits: int = 8) -> None:
+    _want(s, torch.float32, "s"); _want(s_w, torch.float32, "s_w"); _want(bias, torch.float32, "bias")
+    _want(acc_out, torch.int32, "acc_out"); _want(xq_out, torch.int8, "xq_out")
+    if wq.dtype not in (torch.int8, torch.uint8):
+        raise TypeError("wq must be int8 (or uint8 bytes for packed int4)")
+    M, K = x.shape
+    N = wq.shape[0]
+    if wq.shape[1] != (K if wf == SASQ_W_INT8 else K // 2) or tuple(y.shape) != (M, N) or y.dtype != x.dtype:
+        raise ValueError("shape mismatch between x, wq and y")
+    if s_w.numel() != N or (bias is not None and bias.numel() != N):
+        raise ValueError("s_w / bias must have N elements")
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib().sasq_static_linear(_ptr(x), _ptr(s), _ptr(wq), _ptr(s_w), _ptr(bias), _ptr(y), _ptr(acc_out),
+                                     _ptr(xq_out), M, N, K, a_bits, wf, _dt(x), _ptr(workspace), wsb, _stream()),
+           "sasq_static_linear")
+
+
+def sasq_quantize_weight(w: torch.Tensor, wq: torch.Tensor, s_w: torch.Tensor, wf: int = SASQ_W_INT8) -> None:
+    _want(w, torch.float32, "w"); _want(s_w, torch.float32, "s_w")
+    N, K = w.shape
+    _check(_lib().sasq_quantize_weight(_ptr(w), _ptr(wq), _ptr(s_w), N, K, wf, _stream()), "sasq_quantize_weight")
+
+
+def sasq_absmax_scale_workspace(rows: int, cols: int) -> int:
+    return int(_lib().sasq_absmax_scale_workspace(rows, cols))
+
+
+def sasq_absmax_scale(x: torch.Tensor, s: torch.Tensor, workspace: torch.Tensor, bits: int = 8) -> None:
+    _want(s, torch.float32, "s")
+    rows, cols = x.shape[0], x.numel() // max(x.shape[0], 1)
+    _check(_lib().sasq_absmax_scale(_ptr(x), _ptr(s), rows, cols, bits, _dt(x), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _stream()), "sasq_absmax_scale")

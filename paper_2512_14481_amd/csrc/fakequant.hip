@@ -1,0 +1,253 @@
+// Fake-quant forward / backward kernels (HBM-bound streaming kernels) and their C entry points.
+//
+// Forward  (Sec. 4.2; Sec. 3, Eq. 1; Sec. 4.3, Eq. 5):  y = s * clamp(round(x/s), Qn, Qp)
+// Backward (Sec. 4.2, Eq. 4 + chain rule):               dx = dy * m,  ds = sum dy * (q - m*x/s)
+//
+// Both treat the [rows, cols] tensor as a flat array: each lane moves 8 elements per 128-bit
+// access, a block covers kUnroll such accesses per lane back to back so enough bytes are in
+// flight to cover HBM latency, and a scalar tail handles the last (n mod 8) elements.
+#include "sasq_device.h"
+
+namespace sasq {
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;                       // 128-bit accesses in flight per lane per stream
+constexpr int kMaxReduceBlocks = 4096;           // upper bound on partials in the workspace
+
+template <int DT, bool CODES>
+__global__ __launch_bounds__(kThreads) void fakequant_fwd_kernel(
+    const u32x4* __restrict__ x, const float* __restrict__ s_ptr, u32x4* __restrict__ y,
+    u32x2* __restrict__ codes, int64_t nvec, int64_t n, int bits)
+{
+    using S = Store16<DT>;
+    const QConst k = make_qconst(*s_ptr, bits);
+    const int64_t stride = (int64_t)gridDim.x * kThreads * kUnroll;
+    for (int64_t base = (int64_t)blockIdx.x * kThreads * kUnroll; base < nvec; base += stride) {
+        u32x4 in[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            int64_t i = base + u * kThreads + threadIdx.x;
+            if (i < nvec) in[u] = __builtin_nontemporal_load(&x[i]);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            int64_t i = base + u * kThreads + threadIdx.x;
+            if (i >= nvec) continue;
+            u32x4 out;
+            uint32_t cw[2];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                QElem a = quantize(S::lo(in[u][w]), k);
+                QElem b = quantize(S::hi(in[u][w]), k);
+                out[w] = S::pack(codef_of(a) * k.s, codef_of(b) * k.s);
+                if (CODES) {
+                    uint32_t two = __builtin_amdgcn_perm(__float_as_uint(b.c), __float_as_uint(a.c), 0x0c0c0400u);
+                    if (w & 1) cw[w >> 1] |= two << 16; else cw[w >> 1] = two;
+                }
+            }
+            __builtin_nontemporal_store(out, &y[i]);
+            if (CODES) { u32x2 c = {cw[0], cw[1]}; codes[i] = c; }
+        }
+    }
+    // scalar tail: elements [8*nvec, n)
+    if (blockIdx.x == 0 && threadIdx.x < (unsigned)(n - nvec * 8)) {
+        int64_t i = nvec * 8 + threadIdx.x;
+        const uint16_t* xs = reinterpret_cast<const uint16_t*>(x);
+        uint16_t* ys = reinterpret_cast<uint16_t*>(y);
+        QElem e = quantize(S::one(xs[i]), k);
+        ys[i] = S::enc(codef_of(e) * k.s);
+        if (CODES) reinterpret_cast<int8_t*>(codes)[i] = (int8_t)code_of(e);
+    }
+}
+
+// Per-element backward term.  For an unclipped element q == round(p), and fma(-x, inv_s, q)
+// is the exact difference q - p rounded once; for a clipped one the term is q itself.
+__device__ __forceinline__ float ds_term(float x, float g, const QConst& k, bool& keep)
+{
+    QElem e = quantize(x, k);
+    keep = unclipped(e);
+    float q = codef_of(e);
+    float u = __builtin_fmaf(-x, k.inv_s, q);
+    return g * (keep ? u : q);
+}
+
+template <int DT, bool WRITE_DX>
+__global__ __launch_bounds__(kThreads) void fakequant_bwd_kernel(
+    const u32x4* __restrict__ x, const u32x4* __restrict__ dy, const float* __restrict__ s_ptr,
+    u32x4* __restrict__ dx, float* __restrict__ ds, uint32_t* __restrict__ ws_head,
+    double* __restrict__ partials, int64_t nvec, int64_t n, int bits)
+{
+    using S = Store16<DT>;
+    const QConst k = make_qconst(*s_ptr, bits);
+    double acc = 0.0;
+    const int64_t stride = (int64_t)gridDim.x * kThreads * kUnroll;
+    for (int64_t base = (int64_t)blockIdx.x * kThreads * kUnroll; base < nvec; base += stride) {
+        u32x4 xin[kUnroll], gin[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            int64_t i = base + u * kThreads + threadIdx.x;
+            if (i < nvec) {
+                xin[u] = __builtin_nontemporal_load(&x[i]);
+                gin[u] = __builtin_nontemporal_load(&dy[i]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            int64_t i = base + u * kThreads + threadIdx.x;
+            if (i >= nvec) continue;
+            u32x4 out;
+            float part = 0.0f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                bool ka, kb;
+                float ta = ds_term(S::lo(xin[u][w]), S::lo(gin[u][w]), k, ka);
+                float tb = ds_term(S::hi(xin[u][w]), S::hi(gin[u][w]), k, kb);
+                part += ta;
+                part += tb;
+                out[w] = gin[u][w] & ((ka ? 0x0000FFFFu : 0u) | (kb ? 0xFFFF0000u : 0u));
+            }
+            acc += (double)part;               // 8 terms in fp32, everything above in fp64
+            if (WRITE_DX) __builtin_nontemporal_store(out, &dx[i]);
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (unsigned)(n - nvec * 8)) {
+        int64_t i = nvec * 8 + threadIdx.x;
+        const uint16_t* xs = reinterpret_cast<const uint16_t*>(x);
+        const uint16_t* gs = reinterpret_cast<const uint16_t*>(dy);
+        bool keep;
+        float t = ds_term(S::one(xs[i]), S::one(gs[i]), k, keep);
+        acc += (double)t;
+        if (WRITE_DX) reinterpret_cast<uint16_t*>(dx)[i] = keep ? gs[i] : (uint16_t)0;
+    }
+
+    // block partial: lanes -> wave (shuffles) -> block (LDS), fixed order
+    __shared__ double wave_part[kThreads / kWave];
+    __shared__ bool is_last;
+    double w = wave_sum(acc);
+    const int lane = threadIdx.x % kWave, wid = threadIdx.x / kWave;
+    if (lane == 0) wave_part[wid] = w;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double b = 0.0;
+#pragma unroll
+        for (int i = 0; i < kThreads / kWave; ++i) b += wave_part[i];
+        __hip_atomic_store(&partials[blockIdx.x], b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();
+        uint32_t ticket = atomicAdd(&ws_head[0], 1u);
+        is_last = (ticket == kTicketBase + gridDim.x - 1);
+        if (ticket - kTicketBase >= gridDim.x)      // workspace was never initialised: fail loudly
+            *ds = __uint_as_float(0x7FC00000u);
+    }
+    __syncthreads();
+    if (!is_last) return;
+
+    // deterministic second pass by the last block to arrive: fixed strided order, fp64
+    __threadfence();
+    double t = 0.0;
+    for (int i = threadIdx.x; i < (int)gridDim.x; i += kThreads)
+        t += __hip_atomic_load(&partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __shared__ double tree[kThreads];
+    tree[threadIdx.x] = t;
+    __syncthreads();
+    for (int off = kThreads / 2; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) tree[threadIdx.x] += tree[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        *ds = (float)tree[0];
+        __hip_atomic_store(&ws_head[0], kTicketBase, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+__global__ void scale_sgd_kernel(float* s, const float* ds, float lr)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        float step = lr * *ds;
+        *s = *s - step;
+    }
+}
+
+static int grid_for(int64_t nvec, int max_blocks)
+{
+    int64_t per_block = (int64_t)kThreads * kUnroll;
+    int64_t need = (nvec + per_block - 1) / per_block;
+    if (need < 1) need = 1;
+    return (int)(need < max_blocks ? need : max_blocks);
+}
+
+static int check_shape(int64_t rows, int64_t cols, int bits, int dt)
+{
+    if (rows <= 0 || cols <= 0) return SASQ_ERR_SHAPE;
+    if (rows > (INT64_C(1) << 40) / cols) return SASQ_ERR_SHAPE;
+    if (bits < 2 || bits > 8) return SASQ_ERR_UNSUPPORTED;
+    if (dt != SASQ_F16 && dt != SASQ_BF16) return SASQ_ERR_UNSUPPORTED;
+    return SASQ_OK;
+}
+
+}  // namespace sasq
+
+using namespace sasq;
+
+extern "C" int sasq_fakequant_fwd(const void* x, const float* s, void* y, int8_t* codes,
+                                  int64_t rows, int64_t cols, int bits, sasq_dtype dt, void* stream)
+{
+    if (!x || !s || !y) return SASQ_ERR_NULL;
+    int rc = check_shape(rows, cols, bits, (int)dt);
+    if (rc) return rc;
+    if (!aligned16(x) || !aligned16(y) || (codes && (reinterpret_cast<uintptr_t>(codes) & 7u))) return SASQ_ERR_ALIGN;
+    const int64_t n = rows * cols, nvec = n / 8;
+    const int grid = grid_for(nvec, 1 << 20);
+    hipStream_t st = as_stream(stream);
+    auto X = static_cast<const u32x4*>(x);
+    auto Y = static_cast<u32x4*>(y);
+    auto C = reinterpret_cast<u32x2*>(codes);
+    if (dt == SASQ_F16) {
+        if (codes) fakequant_fwd_kernel<SASQ_F16, true><<<grid, kThreads, 0, st>>>(X, s, Y, C, nvec, n, bits);
+        else       fakequant_fwd_kernel<SASQ_F16, false><<<grid, kThreads, 0, st>>>(X, s, Y, C, nvec, n, bits);
+    } else {
+        if (codes) fakequant_fwd_kernel<SASQ_BF16, true><<<grid, kThreads, 0, st>>>(X, s, Y, C, nvec, n, bits);
+        else       fakequant_fwd_kernel<SASQ_BF16, false><<<grid, kThreads, 0, st>>>(X, s, Y, C, nvec, n, bits);
+    }
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+extern "C" size_t sasq_fakequant_bwd_workspace(int64_t rows, int64_t cols)
+{
+    (void)rows; (void)cols;
+    return kWsHeaderBytes + sizeof(double) * kMaxReduceBlocks;
+}
+
+extern "C" int sasq_fakequant_bwd(const void* x, const void* dy, const float* s, void* dx, float* ds,
+                                  int64_t rows, int64_t cols, int bits, sasq_dtype dt,
+                                  void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !dy || !s || !ds) return SASQ_ERR_NULL;
+    int rc = check_shape(rows, cols, bits, (int)dt);
+    if (rc) return rc;
+    if (!aligned16(x) || !aligned16(dy) || (dx && !aligned16(dx))) return SASQ_ERR_ALIGN;
+    if (!workspace || workspace_bytes < sasq_fakequant_bwd_workspace(rows, cols)) return SASQ_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SASQ_ERR_ALIGN;
+    const int64_t n = rows * cols, nvec = n / 8;
+    const int grid = grid_for(nvec, kMaxReduceBlocks);
+    hipStream_t st = as_stream(stream);
+    auto X = static_cast<const u32x4*>(x);
+    auto G = static_cast<const u32x4*>(dy);
+    auto DX = static_cast<u32x4*>(dx);
+    auto head = static_cast<uint32_t*>(workspace);
+    auto parts = reinterpret_cast<double*>(static_cast<char*>(workspace) + kWsHeaderBytes);
+    if (dt == SASQ_F16) {
+        if (dx) fakequant_bwd_kernel<SASQ_F16, true><<<grid, kThreads, 0, st>>>(X, G, s, DX, ds, head, parts, nvec, n, bits);
+        else    fakequant_bwd_kernel<SASQ_F16, false><<<grid, kThreads, 0, st>>>(X, G, s, DX, ds, head, parts, nvec, n, bits);
+    } else {
+        if (dx) fakequant_bwd_kernel<SASQ_BF16, true><<<grid, kThreads, 0, st>>>(X, G, s, DX, ds, head, parts, nvec, n, bits);
+        else    fakequant_bwd_kernel<SASQ_BF16, false><<<grid, kThreads, 0, st>>>(X, G, s, DX, ds, head, parts, nvec, n, bits);
+    }
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+extern "C" int sasq_scale_sgd(float* s, const float* ds, float lr, void* stream)
+{
+    if (!s || !ds) return SASQ_ERR_NULL;
+    scale_sgd_kernel<<<1, 64, 0, as_stream(stream)>>>(s, ds, lr);
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}

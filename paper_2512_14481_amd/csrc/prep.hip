@@ -1,0 +1,188 @@
+// Set-up operations: workspace initialisation, frozen-weight quantization, absmax initial scale.
+#include "sasq_device.h"
+
+namespace sasq {
+
+constexpr int kPrepThreads = 256;
+constexpr int kMaxAbsmaxBlocks = 2048;
+
+__global__ void fill_zero_kernel(uint32_t* p, int64_t nwords)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < nwords) p[i] = 0u;
+}
+
+__device__ __forceinline__ float block_max(float v, float* sh)
+{
+    uint32_t w = wave_max(__float_as_uint(v));      // non-negative floats order like their bits
+    if (threadIdx.x % kWave == 0) sh[threadIdx.x / kWave] = __uint_as_float(w);
+    __syncthreads();
+    float m = sh[0];
+#pragma unroll
+    for (int i = 1; i < kPrepThreads / kWave; ++i) m = fmaxf(m, sh[i]);
+    __syncthreads();
+    return m;
+}
+
+// One block per output channel n (row of W[N,K]): Sec. 3, Eq. 1 applied to the row.
+template <bool INT4>
+__global__ __launch_bounds__(kPrepThreads) void quantize_weight_kernel(
+    const float* __restrict__ w, uint8_t* __restrict__ wq, float* __restrict__ s_w, int64_t K)
+{
+    __shared__ float sh[kPrepThreads / kWave];
+    const int64_t n = blockIdx.x;
+    const float* row = w + n * K;
+    float amax = 0.0f;
+    for (int64_t k = threadIdx.x; k < K; k += kPrepThreads) amax = fmaxf(amax, fabsf(row[k]));
+    amax = block_max(amax, sh);
+    const int bits = INT4 ? 4 : 8;
+    const float Qp = (float)((1 << (bits - 1)) - 1);
+    const float sw = amax == 0.0f ? 1.0f : amax / Qp;
+    if (threadIdx.x == 0) s_w[n] = sw;
+    const QConst kc = make_qconst(sw, bits);
+    if (INT4) {
+        uint8_t* out = wq + n * (K / 2);
+        for (int64_t j = threadIdx.x; j < K / 2; j += kPrepThreads) {
+            int lo = code_of(quantize(row[2 * j], kc));
+            int hi = code_of(quantize(row[2 * j + 1], kc));
+            out[j] = (uint8_t)((lo & 15) | ((hi & 15) << 4));
+        }
+    } else {
+        uint8_t* out = wq + n * K;
+        for (int64_t k = threadIdx.x; k < K; k += kPrepThreads)
+            out[k] = (uint8_t)(code_of(quantize(row[k], kc)) & 0xFF);
+    }
+}
+
+// max |x| over a flat 16-bit tensor: magnitudes of finite values and infinities order like their
+// 15 low bits, so the reduction is an integer max (exact and order-independent).
+template <int DT>
+__global__ __launch_bounds__(kPrepThreads) void absmax_kernel(
+    const uint16_t* __restrict__ x, float* __restrict__ s, uint32_t* __restrict__ ws_head,
+    uint32_t* __restrict__ partials, int64_t n, int bits)
+{
+    using S = Store16<DT>;
+    uint32_t m = 0;
+    const int64_t nvec = n / 8;
+    const u32x4* xv = reinterpret_cast<const u32x4*>(x);
+    for (int64_t i = (int64_t)blockIdx.x * kPrepThreads + threadIdx.x; i < nvec;
+         i += (int64_t)gridDim.x * kPrepThreads) {
+        u32x4 v = xv[i];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            uint32_t lo = v[w] & 0x7FFFu, hi = (v[w] >> 16) & 0x7FFFu;
+            m = lo > m ? lo : m;
+            m = hi > m ? hi : m;
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (unsigned)(n - nvec * 8)) {
+        uint32_t a = x[nvec * 8 + threadIdx.x] & 0x7FFFu;
+        m = a > m ? a : m;
+    }
+    __shared__ uint32_t sh[kPrepThreads / kWave];
+    __shared__ bool is_last;
+    m = wave_max(m);
+    if (threadIdx.x % kWave == 0) sh[threadIdx.x / kWave] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 1; i < kPrepThreads / kWave; ++i) m = sh[i] > m ? sh[i] : m;
+        __hip_atomic_store(&partials[blockIdx.x], m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();
+        uint32_t ticket = atomicAdd(&ws_head[0], 1u);
+        is_last = (ticket == kTicketBase + gridDim.x - 1);
+        if (ticket - kTicketBase >= gridDim.x) *s = __uint_as_float(0x7FC00000u);
+    }
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
+    uint32_t t = 0;
+    for (int i = threadIdx.x; i < (int)gridDim.x; i += kPrepThreads) {
+        uint32_t p = __hip_atomic_load(&partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        t = p > t ? p : t;
+    }
+    t = wave_max(t);
+    __syncthreads();
+    if (threadIdx.x % kWave == 0) sh[threadIdx.x / kWave] = t;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 0; i < kPrepThreads / kWave; ++i) t = sh[i] > t ? sh[i] : t;
+        float amax = S::one((uint16_t)t);
+        *s = amax / (float)((1 << (bits - 1)) - 1);
+        __hip_atomic_store(&ws_head[0], kTicketBase, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+}  // namespace sasq
+
+using namespace sasq;
+
+extern "C" const char* sasq_status_string(int status)
+{
+    switch (status) {
+        case SASQ_OK: return "SASQ_OK";
+        case SASQ_ERR_NULL: return "SASQ_ERR_NULL: a required pointer is NULL";
+        case SASQ_ERR_SHAPE: return "SASQ_ERR_SHAPE: bad size";
+        case SASQ_ERR_ALIGN: return "SASQ_ERR_ALIGN: pointer not 16-byte aligned";
+        case SASQ_ERR_UNSUPPORTED: return "SASQ_ERR_UNSUPPORTED: unknown enum or bits outside [2,8]";
+        case SASQ_ERR_WORKSPACE: return "SASQ_ERR_WORKSPACE: workspace missing or too small";
+        case SASQ_ERR_LAUNCH: return "SASQ_ERR_LAUNCH: HIP launch error";
+        default: return "unknown sasq_status";
+    }
+}
+
+extern "C" int sasq_version(void) { return 100; }
+
+extern "C" int sasq_workspace_init(void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!workspace) return SASQ_ERR_NULL;
+    if (workspace_bytes < kWsHeaderBytes) return SASQ_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SASQ_ERR_ALIGN;
+    const int64_t words = kWsHeaderBytes / 4;
+    fill_zero_kernel<<<1, 64, 0, as_stream(stream)>>>(static_cast<uint32_t*>(workspace), words);
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+extern "C" int sasq_quantize_weight(const float* w, void* wq, float* s_w, int64_t N, int64_t K,
+                                    sasq_wfmt wf, void* stream)
+{
+    if (!w || !wq || !s_w) return SASQ_ERR_NULL;
+    if (N <= 0 || K <= 0 || N > 0x7FFFFFFF || N > (INT64_C(1) << 40) / K) return SASQ_ERR_SHAPE;
+    if (wf != SASQ_W_INT8 && wf != SASQ_W_INT4_PACKED) return SASQ_ERR_UNSUPPORTED;
+    if (wf == SASQ_W_INT4_PACKED && (K & 1)) return SASQ_ERR_SHAPE;
+    if (!aligned16(w) || !aligned16(wq)) return SASQ_ERR_ALIGN;
+    hipStream_t st = as_stream(stream);
+    if (wf == SASQ_W_INT8)
+        quantize_weight_kernel<false><<<(int)N, kPrepThreads, 0, st>>>(w, static_cast<uint8_t*>(wq), s_w, K);
+    else
+        quantize_weight_kernel<true><<<(int)N, kPrepThreads, 0, st>>>(w, static_cast<uint8_t*>(wq), s_w, K);
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+extern "C" size_t sasq_absmax_scale_workspace(int64_t rows, int64_t cols)
+{
+    (void)rows; (void)cols;
+    return kWsHeaderBytes + sizeof(uint32_t) * kMaxAbsmaxBlocks;
+}
+
+extern "C" int sasq_absmax_scale(const void* x, float* s, int64_t rows, int64_t cols, int bits,
+                                 sasq_dtype dt, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !s) return SASQ_ERR_NULL;
+    if (rows <= 0 || cols <= 0 || rows > (INT64_C(1) << 40) / cols) return SASQ_ERR_SHAPE;
+    if (bits < 2 || bits > 8) return SASQ_ERR_UNSUPPORTED;
+    if (dt != SASQ_F16 && dt != SASQ_BF16) return SASQ_ERR_UNSUPPORTED;
+    if (!aligned16(x)) return SASQ_ERR_ALIGN;
+    if (!workspace || workspace_bytes < sasq_absmax_scale_workspace(rows, cols)) return SASQ_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SASQ_ERR_ALIGN;
+    const int64_t n = rows * cols;
+    int64_t need = (n / 8 + kPrepThreads * 4 - 1) / (kPrepThreads * 4);
+    int grid = (int)(need < 1 ? 1 : (need > kMaxAbsmaxBlocks ? kMaxAbsmaxBlocks : need));
+    auto head = static_cast<uint32_t*>(workspace);
+    auto parts = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + kWsHeaderBytes);
+    hipStream_t st = as_stream(stream);
+    if (dt == SASQ_F16)
+        absmax_kernel<SASQ_F16><<<grid, kPrepThreads, 0, st>>>(static_cast<const uint16_t*>(x), s, head, parts, n, bits);
+    else
+        absmax_kernel<SASQ_BF16><<<grid, kPrepThreads, 0, st>>>(static_cast<const uint16_t*>(x), s, head, parts, n, bits);
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}

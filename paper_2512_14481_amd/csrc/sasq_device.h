@@ -1,0 +1,125 @@
+// Device-side building blocks shared by the HIP kernels of the SASQ library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sasq.h"
+
+namespace sasq {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+// 1.5 * 2^23.  For |p| < 2^22, fma(x, inv_s, kMagic) is the exact product x*inv_s rounded ONCE
+// (hardware round-to-nearest-even) to the integer grid, offset by kMagic; in [2^23, 2^24) the
+// fp32 bit pattern is linear in the value, so the low bits carry the signed integer.
+constexpr float kMagic = 12582912.0f;
+constexpr int32_t kMagicBits = 0x4B400000;
+
+// Quantizer constants for one call: Sec. 3, Eq. 1 with S = s and N = bits.
+struct QConst {
+    float inv_s;   // fl32(1/s), one IEEE division
+    float s;
+    float lo;      // kMagic + Qn
+    float hi;      // kMagic + Qp
+};
+
+__device__ __forceinline__ QConst make_qconst(float s, int bits)
+{
+    QConst q;
+    q.s = s;
+    q.inv_s = 1.0f / s;                       // correctly rounded (no fast-math)
+    q.lo = kMagic - (float)(1 << (bits - 1));
+    q.hi = kMagic + (float)((1 << (bits - 1)) - 1);
+    return q;
+}
+
+// One quantized element in the "magic" domain.
+//   f  = round(x*inv_s) + kMagic  (single rounding; saturating garbage far out of range)
+//   c  = clamp(f) = q + kMagic
+struct QElem {
+    float f;
+    float c;
+};
+
+__device__ __forceinline__ QElem quantize(float x, const QConst& k)
+{
+    QElem e;
+    e.f = __builtin_fmaf(x, k.inv_s, kMagic);
+    e.c = __builtin_amdgcn_fmed3f(e.f, k.lo, k.hi);
+    return e;
+}
+
+__device__ __forceinline__ int code_of(const QElem& e) { return __float_as_int(e.c) - kMagicBits; }
+__device__ __forceinline__ float codef_of(const QElem& e) { return e.c - kMagic; }   // exact
+__device__ __forceinline__ bool unclipped(const QElem& e) { return e.f == e.c; }
+
+// ---- 16-bit storage types -------------------------------------------------------------------
+template <int DT> struct Store16;
+
+template <> struct Store16<SASQ_F16> {
+    static __device__ __forceinline__ float lo(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xFFFFu)); }
+    static __device__ __forceinline__ float hi(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)); }
+    static __device__ __forceinline__ float one(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+    static __device__ __forceinline__ uint16_t enc(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
+    static __device__ __forceinline__ uint32_t pack(float a, float b)
+    {
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        h2 v = {(_Float16)a, (_Float16)b};
+        return __builtin_bit_cast(uint32_t, v);
+    }
+};
+
+template <> struct Store16<SASQ_BF16> {
+    static __device__ __forceinline__ float lo(uint32_t w) { return __uint_as_float(w << 16); }
+    static __device__ __forceinline__ float hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+    static __device__ __forceinline__ float one(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+    static __device__ __forceinline__ uint16_t enc(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+    static __device__ __forceinline__ uint32_t pack(float a, float b)
+    {
+        typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+        b2 v = {(__bf16)a, (__bf16)b};
+        return __builtin_bit_cast(uint32_t, v);
+    }
+};
+
+// Pack the low bytes of four "magic domain" floats (their int8 codes) into one dword.
+__device__ __forceinline__ uint32_t pack_codes4(float c0, float c1, float c2, float c3)
+{
+    uint32_t a = __builtin_amdgcn_perm(__float_as_uint(c1), __float_as_uint(c0), 0x0c0c0400u);  // [c0.b0, c1.b0, 0, 0]
+    uint32_t b = __builtin_amdgcn_perm(__float_as_uint(c3), __float_as_uint(c2), 0x04000c0cu);  // [0, 0, c2.b0, c3.b0]
+    return a | b;
+}
+
+// ---- reductions -----------------------------------------------------------------------------
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_max(uint32_t v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        uint32_t o = (uint32_t)__shfl_xor((int)v, off, kWave);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// Workspace header used by the grid-wide reductions: word 0 is the arrival ticket.
+constexpr size_t kWsHeaderBytes = 256;
+constexpr uint32_t kTicketBase = 0;
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace sasq

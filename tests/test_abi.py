@@ -1,0 +1,104 @@
+"""The C-ABI library loads without a GPU, exports every symbol include/sasq.h declares, and
+rejects bad arguments on the host before launching anything (no compute calls here)."""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sasq.h")
+LIB = os.path.join(ROOT, "paper_2512_14481_amd", "libsasq.so")
+
+i64 = ctypes.c_int64
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2512_14481_amd import build
+        build.build(verbose=False)
+    L = ctypes.CDLL(LIB)
+    for f in ("sasq_fakequant_bwd_workspace", "sasq_static_linear_workspace", "sasq_absmax_scale_workspace"):
+        getattr(L, f).restype = ctypes.c_size_t
+    L.sasq_status_string.restype = ctypes.c_char_p
+    return L
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(sasq_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_header_symbols_exported(lib):
+    names = declared_functions()
+    assert {"sasq_fakequant_fwd", "sasq_fakequant_bwd", "sasq_static_linear"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in sasq.h but not exported"
+
+
+def test_binding_has_same_names():
+    from paper_2512_14481_amd import binding
+    for n in declared_functions():
+        if n == "sasq_status_string":
+            continue
+        assert hasattr(binding, n), n
+
+
+def test_status_strings(lib):
+    assert lib.sasq_status_string(0) == b"SASQ_OK"
+    assert all(lib.sasq_status_string(i).startswith(b"SASQ_ERR") for i in range(1, 7))
+    assert lib.sasq_version() >= 100
+
+
+def test_workspace_queries(lib):
+    assert lib.sasq_fakequant_bwd_workspace(i64(4096), i64(4096)) >= 256
+    assert lib.sasq_absmax_scale_workspace(i64(1), i64(1)) >= 256
+    assert lib.sasq_static_linear_workspace(i64(0), i64(4), i64(4), 0) == 0
+    assert lib.sasq_static_linear_workspace(i64(4096), i64(11008), i64(4096), 0) >= 0
+
+
+def test_host_side_validation(lib):
+    P = ctypes.c_void_p
+    good = P(0x1000)          # never dereferenced: every call below fails validation first
+    odd = P(0x1004)
+    fwd = lib.sasq_fakequant_fwd
+    assert fwd(None, good, good, None, i64(4), i64(4), 8, 0, None) == 1
+    assert fwd(good, good, good, None, i64(0), i64(4), 8, 0, None) == 2
+    assert fwd(good, good, good, None, i64(-1), i64(4), 8, 0, None) == 2
+    assert fwd(good, good, good, None, i64(1 << 30), i64(1 << 30), 8, 0, None) == 2
+    assert fwd(odd, good, good, None, i64(4), i64(4), 8, 0, None) == 3
+    assert fwd(good, good, good, None, i64(4), i64(4), 9, 0, None) == 4
+    assert fwd(good, good, good, None, i64(4), i64(4), 1, 0, None) == 4
+    assert fwd(good, good, good, None, i64(4), i64(4), 8, 7, None) == 4
+    bwd = lib.sasq_fakequant_bwd
+    assert bwd(good, None, good, good, good, i64(4), i64(4), 8, 0, good, ctypes.c_size_t(1 << 20), None) == 1
+    assert bwd(good, good, good, good, good, i64(4), i64(4), 8, 0, None, ctypes.c_size_t(0), None) == 5
+    assert bwd(good, good, good, good, good, i64(4), i64(4), 8, 0, good, ctypes.c_size_t(8), None) == 5
+    lin = lib.sasq_static_linear
+    big = ctypes.c_size_t(1 << 40)
+    args = lambda **kw: [kw.get("x", good), good, kw.get("wq", good), good, None, good, None, None,
+                         i64(kw.get("M", 4)), i64(kw.get("N", 4)), i64(kw.get("K", 4)), kw.get("bits", 8),
+                         kw.get("wf", 0), kw.get("dt", 0), kw.get("ws", good), kw.get("wsb", big), None]
+    assert lin(*args(x=None)) == 1
+    assert lin(*args(M=0)) == 2
+    assert lin(*args(K=5, wf=1)) == 2
+    assert lin(*args(K=1 << 20)) == 2
+    assert lin(*args(wf=2)) == 4
+    assert lin(*args(dt=3)) == 4
+    assert lin(*args(bits=0)) == 4
+    assert lin(*args(wq=odd)) == 3
+    assert lin(*args(ws=None, wsb=ctypes.c_size_t(0))) == 5
+    qw = lib.sasq_quantize_weight
+    assert qw(None, good, good, i64(4), i64(4), 0, None) == 1
+    assert qw(good, good, good, i64(4), i64(3), 1, None) == 2
+    assert qw(good, good, good, i64(4), i64(4), 5, None) == 4
+    am = lib.sasq_absmax_scale
+    assert am(good, None, i64(4), i64(4), 8, 0, good, big, None) == 1
+    assert am(good, good, i64(4), i64(4), 8, 0, None, ctypes.c_size_t(0), None) == 5
+    assert lib.sasq_workspace_init(None, ctypes.c_size_t(1024), None) == 1
+    assert lib.sasq_workspace_init(good, ctypes.c_size_t(8), None) == 5
+    assert lib.sasq_scale_sgd(None, good, ctypes.c_float(0.1), None) == 1

@@ -1,0 +1,238 @@
+"""GPU parity: the HIP library (through its C ABI via the ctypes binding) against the CPU oracle,
+element by element, on seeded inputs small enough for the oracle to finish in seconds.
+
+Bars: integer codes, int32 accumulators and dx bit-exact (dx by value for zeros); 16-bit outputs
+within 1e-3 relative (asserted equal by value, which is stricter); ds within 1e-4 relative.
+"""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2512_14481_amd import binding as B
+from paper_2512_14481_amd import workloads as wl
+from tests.gpu_util import (TDT, assert_same_values, dev_scalar, rel_err, to_bits, to_dev, val)
+
+pytestmark = pytest.mark.gpu
+
+SCALE_SET = [0.5, 2.0 ** -7, 0.0123456789, 0.0371, 3.1, -0.043, 1e-4, 97.0, 7.3e-6, 1.7e4]
+
+
+@pytest.fixture(scope="module")
+def ws():
+    return B.new_workspace(1 << 20)
+
+
+def run_fwd(x_bits, s, bits, dtype, want_codes=True):
+    x = to_dev(x_bits, dtype)
+    y = torch.empty_like(x)
+    codes = torch.empty(x.shape, dtype=torch.int8, device="cuda") if want_codes else None
+    B.sasq_fakequant_fwd(x, dev_scalar(s), y, codes, bits)
+    torch.cuda.synchronize()
+    return to_bits(y), (codes.cpu().numpy() if want_codes else None)
+
+
+def run_bwd(x_bits, dy_bits, s, bits, dtype, ws, want_dx=True):
+    x, dy = to_dev(x_bits, dtype), to_dev(dy_bits, dtype)
+    dx = torch.empty_like(x) if want_dx else None
+    ds = torch.full((1,), 12345.0, dtype=torch.float32, device="cuda")
+    B.sasq_fakequant_bwd(x, dy, dev_scalar(s), dx, ds, ws, bits)
+    torch.cuda.synchronize()
+    return (to_bits(dx) if want_dx else None), np.float32(ds.item())
+
+
+# ---------------------------------------------------------------- fake-quant, exhaustive inputs
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("bits", [8, 4, 2])
+def test_fakequant_all_patterns(dtype, bits, ws):
+    """Every finite 16-bit pattern (and +-inf) x a scale set: codes, y, dx, ds."""
+    pats = wl.all_finite_patterns(dtype)
+    x = pats.reshape(-1, 64) if pats.size % 64 == 0 else pats.reshape(1, -1)
+    dy = wl.random_bits(3, f"dy_all_{dtype}", x.shape, dtype)
+    for s in SCALE_SET:
+        s32 = np.float32(s)
+        y_ref, c_ref = oracle.fakequant_fwd(x, s32, bits, dtype)
+        y, c = run_fwd(x, s32, bits, dtype)
+        assert np.array_equal(c, c_ref), f"codes differ at s={s}"
+        assert_same_values(y, y_ref, dtype, f"fwd y s={s}")
+        y2, _ = run_fwd(x, s32, bits, dtype, want_codes=False)
+        assert np.array_equal(y2, y)
+        # backward: drop the infinities from ds (0 * inf style terms are not part of the contract)
+        fin = np.isfinite(val(x, dtype))
+        xb = np.where(fin, x, 0).astype(np.uint16)
+        ref = oracle.fakequant_bwd(xb, dy, s32, bits, dtype)
+        dx, ds = run_bwd(xb, dy, s32, bits, dtype, ws)
+        assert_same_values(dx, ref["dx"], dtype, f"dx s={s}")
+        assert abs(float(ds) - ref["ds64"]) <= 1e-4 * abs(ref["ds64"]) + 1e-7 * ref["sum_abs"], (s, ds, ref["ds64"])
+        dxi, _ = run_bwd(x, dy, s32, bits, dtype, ws)
+        assert_same_values(dxi, oracle.fakequant_bwd(x, dy, s32, bits, dtype)["dx"], dtype, f"dx(inf) s={s}")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_reciprocal_is_correctly_rounded_on_device(dtype, ws):
+    """x = 1, dy = 1: ds = round(inv_s) - inv_s exactly, which exposes every bit of the
+    device's 1/s for |inv_s| < 128."""
+    one = wl.f32_to_storage_bits(np.ones((1, 1), np.float32), dtype)
+    rng = np.random.default_rng(5)
+    for s in np.exp(rng.uniform(np.log(1 / 100), np.log(50.0), 64)).astype(np.float32):
+        inv = np.float32(1.0) / s
+        _, ds = run_bwd(one, one, s, 8, dtype, ws)
+        assert np.float32(ds) == np.float32(np.rint(np.float64(inv)) - np.float64(inv)), (s, inv, ds)
+
+
+# ---------------------------------------------------------------- fake-quant, shapes and tails
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("shape", [(1, 1), (1, 7), (3, 5), (1, 8), (17, 33), (64, 256), (257, 1031),
+                                   (1, 8 * 256 * 4), (1, 8 * 256 * 4 + 1), (513, 4099)])
+def test_fakequant_shapes(dtype, shape, ws):
+    x = wl.random_bits(7, f"x{shape}{dtype}", shape, dtype, gain=3.0)
+    dy = wl.random_bits(7, f"dy{shape}{dtype}", shape, dtype)
+    s0 = oracle.absmax_scale(x, 8, dtype)
+    for s in (s0, np.float32(s0 / 4)):
+        y_ref, c_ref = oracle.fakequant_fwd(x, s, 8, dtype)
+        y, c = run_fwd(x, s, 8, dtype)
+        assert np.array_equal(c, c_ref)
+        assert_same_values(y, y_ref, dtype, "y")
+        ref = oracle.fakequant_bwd(x, dy, s, 8, dtype)
+        dx, ds = run_bwd(x, dy, s, 8, dtype, ws)
+        assert_same_values(dx, ref["dx"], dtype, "dx")
+        assert rel_err(float(ds), ref["ds64"]) <= 1e-4, (ds, ref["ds64"], ref["sum_abs"])
+        _, ds_nodx = run_bwd(x, dy, s, 8, dtype, ws, want_dx=False)
+        assert ds_nodx == ds
+
+
+def test_fakequant_in_place_and_determinism(ws):
+    dtype = "f16"
+    xb = wl.random_bits(8, "inplace", (300, 1000), dtype, gain=2.0)
+    dyb = wl.random_bits(8, "inplace_dy", (300, 1000), dtype)
+    s = np.float32(0.01)
+    y_ref, _ = oracle.fakequant_fwd(xb, s, 8, dtype)
+    x = to_dev(xb, dtype)
+    B.sasq_fakequant_fwd(x, dev_scalar(s), x, None, 8)
+    assert_same_values(to_bits(x), y_ref, dtype, "in-place y")
+    x = to_dev(xb, dtype)
+    seen = set()
+    for _ in range(5):
+        dy = to_dev(dyb, dtype)
+        ds = torch.zeros(1, dtype=torch.float32, device="cuda")
+        B.sasq_fakequant_bwd(x, dy, dev_scalar(s), dy, ds, ws, 8)   # dx aliases dy
+        torch.cuda.synchronize()
+        seen.add((ds.view(torch.int32).item(), to_bits(dy).tobytes()))
+    assert len(seen) == 1, "backward is not bit-reproducible"
+    ref = oracle.fakequant_bwd(xb, dyb, s, 8, dtype)
+    assert_same_values(np.frombuffer(next(iter(seen))[1], dtype=np.uint16).reshape(xb.shape), ref["dx"], dtype, "dx alias")
+
+
+def test_uninitialised_workspace_is_loud():
+    x = to_dev(wl.random_bits(9, "u", (4, 64), "f16"), "f16")
+    junk = torch.full((1 << 16,), 0x5A, dtype=torch.uint8, device="cuda")
+    ds = torch.zeros(1, dtype=torch.float32, device="cuda")
+    B.sasq_fakequant_bwd(x, x, dev_scalar(0.1), None, ds, junk, 8)
+    torch.cuda.synchronize()
+    assert torch.isnan(ds).item()
+
+
+def test_scale_sgd_and_absmax(ws):
+    for dtype in ("f16", "bf16"):
+        for shape in ((1, 3), (64, 256), (129, 1001)):
+            xb = wl.random_bits(10, f"am{shape}{dtype}", shape, dtype, gain=5.0)
+            s = torch.zeros(1, dtype=torch.float32, device="cuda")
+            for bits in (8, 4):
+                B.sasq_absmax_scale(to_dev(xb, dtype), s, ws, bits)
+                assert np.float32(s.item()) == oracle.absmax_scale(xb, bits, dtype)
+    s = dev_scalar(0.5)
+    ds = dev_scalar(126.212890625)
+    B.sasq_scale_sgd(s, ds, 2e-4)
+    assert np.float32(s.item()) == oracle.scale_sgd(0.5, 126.212890625, 2e-4)
+
+
+# ---------------------------------------------------------------- weight quantizer
+@pytest.mark.parametrize("fmt", ["int8", "int4"])
+@pytest.mark.parametrize("shape", [(1, 2), (5, 34), (33, 130), (256, 4096), (7, 11008)])
+def test_quantize_weight(fmt, shape):
+    w = wl.random_f32(11, f"w{shape}", shape, 0.02)
+    if shape[0] > 4:
+        w[3] = 0.0
+    wq_ref, sw_ref = oracle.quantize_weight(w, fmt)
+    wd = torch.from_numpy(w).cuda()
+    N, K = shape
+    wq = torch.zeros((N, K if fmt == "int8" else K // 2), dtype=torch.int8 if fmt == "int8" else torch.uint8, device="cuda")
+    sw = torch.zeros(N, dtype=torch.float32, device="cuda")
+    B.sasq_quantize_weight(wd, wq, sw, B.SASQ_W_INT8 if fmt == "int8" else B.SASQ_W_INT4_PACKED)
+    assert np.array_equal(sw.cpu().numpy(), sw_ref)
+    assert np.array_equal(wq.cpu().numpy(), wq_ref)
+
+
+# ---------------------------------------------------------------- static linear
+def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True):
+    M, K = xb.shape
+    N = wq.shape[0]
+    wf = B.SASQ_W_INT8 if fmt == "int8" else B.SASQ_W_INT4_PACKED
+    x = to_dev(xb, dtype)
+    y = torch.empty((M, N), dtype=TDT[dtype], device="cuda")
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda") if want_debug else None
+    xq = torch.empty((M, K), dtype=torch.int8, device="cuda") if want_debug else None
+    wsl = B.new_workspace(B.sasq_static_linear_workspace(M, N, K, wf))
+    B.sasq_static_linear(x, dev_scalar(s), torch.from_numpy(wq).cuda(), torch.from_numpy(s_w).cuda(),
+                         None if bias is None else torch.from_numpy(bias).cuda(), y, wf, wsl, acc, xq)
+    torch.cuda.synchronize()
+    return to_bits(y), (acc.cpu().numpy() if want_debug else None), (xq.cpu().numpy() if want_debug else None)
+
+
+LINEAR_SHAPES = [
+    (1, 1, 2), (3, 5, 8), (19, 23, 70),              # scalar path: K not a multiple of 128
+    (64, 256, 256),                                   # config 1
+    (1, 1, 128), (33, 47, 128), (256, 256, 128),      # MFMA path: single K step, ragged / exact tile
+    (300, 520, 384), (257, 255, 1024), (512, 768, 512),
+]
+
+
+@pytest.mark.parametrize("dtype,fmt", [("f16", "int8"), ("bf16", "int8"), ("bf16", "int4"), ("f16", "int4")])
+@pytest.mark.parametrize("shape", LINEAR_SHAPES)
+def test_static_linear(shape, dtype, fmt):
+    M, N, K = shape
+    xb = wl.random_bits(12, f"lx{shape}{dtype}", (M, K), dtype, gain=2.0)
+    w = wl.random_f32(12, f"lw{shape}", (N, K), 0.02)
+    wq, s_w = oracle.quantize_weight(w, fmt)
+    bias = wl.random_f32(12, f"lb{shape}", (N,), 0.3)
+    s = np.float32(oracle.absmax_scale(xb, 8, dtype) / 3)
+    for b in (None, bias):
+        ref = oracle.static_linear(xb, s, wq, s_w, b, 8, fmt, dtype)
+        y, acc, xq = run_linear(xb, s, wq, s_w, b, fmt, dtype)
+        assert np.array_equal(xq, ref["xq"]), "activation codes"
+        assert np.array_equal(acc, ref["acc"]), "int32 accumulators"
+        assert_same_values(y, ref["y"], dtype, "Y")
+        y2, _, _ = run_linear(xb, s, wq, s_w, b, fmt, dtype, want_debug=False)
+        assert np.array_equal(y2, y)
+
+
+def test_static_linear_extreme_codes():
+    """All-extreme codes at a long K: signs and int32 headroom through the MFMA path."""
+    K = 28672
+    xv = np.tile(np.array([[-128.0], [127.0], [-128.0]], dtype=np.float32), (1, K))
+    xv[2, ::2] = 127.0
+    xb = wl.f32_to_storage_bits(xv, "bf16")
+    wq = np.stack([np.full(K, -128), np.full(K, 127), np.full(K, -127), np.where(np.arange(K) % 2, 127, -128)]).astype(np.int8)
+    ref = oracle.static_linear(xb, np.float32(1.0), wq, np.ones(4, np.float32), None, 8, "int8", "bf16")
+    y, acc, xq = run_linear(xb, np.float32(1.0), wq, np.ones(4, np.float32), None, "int8", "bf16")
+    assert ref["acc"][0, 0] == 128 * 128 * K
+    assert np.array_equal(acc, ref["acc"]) and np.array_equal(xq, ref["xq"])
+    assert_same_values(y, ref["y"], "bf16", "Y")
+
+
+def test_cross_export_identity():
+    """xq of the linear == codes of fake-quant, and Y ~ fakequant(x) . (Wq*s_w)^T (Eq. 2 <=> Eq. 5)."""
+    dtype = "f16"
+    M, N, K = 96, 80, 256
+    xb = wl.random_bits(13, "cx", (M, K), dtype, gain=2.0)
+    w = wl.random_f32(13, "cw", (N, K), 0.02)
+    wq, s_w = oracle.quantize_weight(w, "int8")
+    s = np.float32(0.05)
+    y, acc, xq = run_linear(xb, s, wq, s_w, None, "int8", dtype)
+    yfq, codes = run_fwd(xb, s, 8, dtype)
+    assert np.array_equal(xq, codes)
+    exact = (codes.astype(np.float64) * float(s)) @ (wq.astype(np.float64) * s_w[:, None].astype(np.float64)).T
+    yv = val(y, dtype)
+    assert (np.abs(yv - exact) <= 2.0 ** -10 * np.abs(exact) + 1e-6).all()
