@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the SASQ hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over the LLaMA-2-7B MLP workload (M = 4096 tokens;
+gate, up: K 4096 -> N 11008; down: K 11008 -> N 4096; fp16 activations, int8 weights): for every
+projection, fake-quant forward, straight-through backward with the grid-wide ds reduction, one SGD
+update of the scale, and the static-inference W8A8 linear.  Inputs are seeded synthetic tensors
+already resident in HBM; weights are quantized once, outside the timed region, by the library.
+
+Prints ONE JSON line.  `value` is the linear-layer integer throughput of the whole step
+(2*M*N*K summed over the projections, divided by the full step time, fake-quant kernels included).
+`roofline` is the static linear alone, timed with HIP events on the launch stream inside the timed
+region; `fakequant` is the fake-quant forward+backward pair against HBM bandwidth; `cpu_baseline`
+is the CPU oracle on a bounded row sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2512_14481_amd import binding as B          # noqa: E402
+from paper_2512_14481_amd import workloads as wl       # noqa: E402
+
+INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8, published
+HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published
+LR = 2e-4
+TDT = {"f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def dev16(bits: np.ndarray, dtype: str) -> torch.Tensor:
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(TDT[dtype])
+
+
+class Projection:
+    def __init__(self, cfg, proj, x, ws_small):
+        self.name, self.x = proj.name, x
+        self.M, self.K, self.N = x.shape[0], x.shape[1], proj.N
+        wf = B.SASQ_W_INT8 if cfg.w_fmt == wl.W_INT8 else B.SASQ_W_INT4_PACKED
+        self.wf = wf
+        w = torch.from_numpy(wl.weight_fp32(cfg, proj.name)).cuda()
+        kq = self.K if wf == B.SASQ_W_INT8 else self.K // 2
+        self.wq = torch.empty((self.N, kq), dtype=torch.int8 if wf == B.SASQ_W_INT8 else torch.uint8, device="cuda")
+        self.s_w = torch.empty(self.N, dtype=torch.float32, device="cuda")
+        B.sasq_quantize_weight(w, self.wq, self.s_w, wf)
+        del w
+        self.dy = dev16(wl.upstream_grad(cfg, proj.name), cfg.dtype)
+        self.s = torch.empty(1, dtype=torch.float32, device="cuda")
+        B.sasq_absmax_scale(x, self.s, ws_small, 8)           # s0 = absmax / 127
+        self.s0 = self.s.clone()
+        self.ds = torch.zeros(1, dtype=torch.float32, device="cuda")
+        self.xhat = torch.empty_like(x)
+        self.dx = torch.empty_like(x)
+        self.y = torch.empty((self.M, self.N), dtype=x.dtype, device="cuda")
+        self.ws_lin = B.new_workspace(B.sasq_static_linear_workspace(self.M, self.N, self.K, wf))
+        self.ops = 2.0 * self.M * self.N * self.K
+        self.fq_bytes = 10.0 * self.M * self.K
+
+
+def step(projs, ws_bwd, ev=None):
+    """One pass of the hot path.  ev: optional dict of event lists for per-call timing."""
+    for p in projs:
+        if ev is not None:
+            e0, e1, e2, e3 = (torch.cuda.Event(enable_timing=True) for _ in range(4))
+            e0.record()
+        B.sasq_fakequant_fwd(p.x, p.s, p.xhat, None, 8)
+        B.sasq_fakequant_bwd(p.x, p.dy, p.s, p.dx, p.ds, ws_bwd, 8)
+        if ev is not None:
+            e1.record()
+        B.sasq_scale_sgd(p.s, p.ds, LR)
+        if ev is not None:
+            e2.record()
+        B.sasq_static_linear(p.x, p.s, p.wq, p.s_w, None, p.y, p.wf, p.ws_lin)
+        if ev is not None:
+            e3.record()
+            ev["fq"].append((e0, e1, p))
+            ev["lin"].append((e2, e3, p))
+
+
+def cpu_baseline(cfg, rows: int):
+    """The CPU oracle, as it stands, on the first `rows` tokens of every projection's input."""
+    import oracle
+    t_total, ops = 0.0, 0.0
+    for proj in cfg.projs:
+        x = wl.activation(cfg, proj.x, rows=rows)
+        dy = wl.upstream_grad(cfg, proj.name, rows=rows)
+        w = wl.weight_fp32(cfg, proj.name)
+        wq, s_w = oracle.quantize_weight(w, cfg.w_fmt)       # set-up, not timed (as on the GPU)
+        s = oracle.absmax_scale(x, 8, cfg.dtype)
+        t0 = time.perf_counter()
+        oracle.fakequant_fwd(x, s, 8, cfg.dtype)
+        b = oracle.fakequant_bwd(x, dy, s, 8, cfg.dtype)
+        s1 = oracle.scale_sgd(s, b["ds"], LR)
+        oracle.static_linear(x, s1, wq, s_w, None, 8, cfg.w_fmt, cfg.dtype, want_acc=False, want_xq=False)
+        t_total += time.perf_counter() - t0
+        ops += 2.0 * rows * proj.N * cfg.K_of(proj)
+    return {"value": ops / t_total / 1e12, "unit": "TOPS", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"first {rows} of {cfg.M} tokens of every projection, whole step "
+                      f"(fake-quant fwd+bwd, SGD, static linear); {t_total:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c3_mlp7b")
+    ap.add_argument("--cpu-rows", type=int, default=1024)
+    ap.add_argument("--no-cpu", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU; --gpus must be 1 (how the path would shard over "
+                 "GPUs is described in DESIGN.md, nothing multi-GPU is implemented)")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+
+    cfg = wl.CONFIGS[a.config]
+    ws_small = B.new_workspace(max(B.sasq_absmax_scale_workspace(1, 1), B.sasq_fakequant_bwd_workspace(1, 1)))
+    acts = {act.name: dev16(wl.activation(cfg, act.name), cfg.dtype) for act in cfg.acts}
+    projs = [Projection(cfg, p, acts[p.x], ws_small) for p in cfg.projs]
+    torch.cuda.synchronize()
+
+    for _ in range(a.warmup):
+        step(projs, ws_small)
+    for p in projs:                                   # every timed run starts from the same scales
+        p.s.copy_(p.s0)
+    torch.cuda.synchronize()
+    ev = {"fq": [], "lin": []}
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step(projs, ws_small, ev)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ms_per_step = dt / a.steps * 1e3
+    total_ops = sum(p.ops for p in projs)
+    lin_ms = [(e0.elapsed_time(e1), p) for e0, e1, p in ev["lin"]]
+    fq_ms = [(e0.elapsed_time(e1), p) for e0, e1, p in ev["fq"]]
+    lin_ops_per_call = total_ops / len(projs)         # the three linears are the same size
+    lin_avg_ms = sum(t for t, _ in lin_ms) / len(lin_ms)
+    lin_tops = lin_ops_per_call / (lin_avg_ms * 1e-3) / 1e12
+    fq_gbps = sum(p.fq_bytes for _, p in fq_ms) / (sum(t for t, _ in fq_ms) * 1e-3) / 1e9
+    per_proj = {}
+    for name in [p.name for p in projs]:
+        tl = [t for t, p in lin_ms if p.name == name]
+        tf = [t for t, p in fq_ms if p.name == name]
+        pp = next(p for p in projs if p.name == name)
+        per_proj[name] = {"linear_us": round(1e3 * sum(tl) / len(tl), 2),
+                          "linear_tops": round(pp.ops / (sum(tl) / len(tl) * 1e-3) / 1e12, 1),
+                          "fakequant_fwd_bwd_us": round(1e3 * sum(tf) / len(tf), 2),
+                          "fakequant_gbps": round(pp.fq_bytes / (sum(tf) / len(tf) * 1e-3) / 1e9, 1)}
+
+    out = {
+        "metric": "static-scale W8A8 linear TOPS (% int8 MFMA peak); fake-quant fwd+bwd GB/s",
+        "value": round(total_ops / (ms_per_step * 1e-3) / 1e12, 2),
+        "unit": "TOPS",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: LLaMA-2-7B MLP, M=4096 tokens, gate/up 4096->11008, down 11008->4096, "
+                               "fp16 activations, int8 per-channel weights, per-tensor static scale; "
+                               "step = fake-quant fwd + STE bwd + ds + SGD + static W8A8 linear per projection"
+                   if cfg.name == "c3_mlp7b" else cfg.name},
+        "roofline": {"bound": "mfma", "kernel": "sasq_static_linear (activation quantize + int8 MFMA GEMM + dequant)",
+                     "achieved": round(lin_tops, 1), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": round(lin_tops / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
+                     "avg_launch_us": round(lin_avg_ms * 1e3, 2)},
+        "fakequant": {"bound": "hbm", "achieved": round(fq_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                      "frac": round(fq_gbps / HBM_PEAK_GBPS, 4),
+                      "bytes_per_element": 10, "note": "fwd (2+2 B/el) + bwd (2+2+2 B/el), events around the pair"},
+        "per_projection": per_proj,
+    }
+    if not a.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(cfg, a.cpu_rows)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

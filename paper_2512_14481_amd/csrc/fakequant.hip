@@ -14,6 +14,26 @@ constexpr int kThreads = 256;
 constexpr int kUnroll = 4;                       // 128-bit accesses in flight per lane per stream
 constexpr int kMaxReduceBlocks = 4096;           // upper bound on partials in the workspace
 
+// Forward on one 8-element vector.
+template <int DT, bool CODES>
+__device__ __forceinline__ void fwd_vec(const u32x4& in, const QConst& k, u32x4& out, u32x2& cw)
+{
+    using S = Store16<DT>;
+    float c[8];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        QElem a = quantize(S::lo(in[w]), k);
+        QElem b = quantize(S::hi(in[w]), k);
+        out[w] = S::pack(codef_of(a) * k.s, codef_of(b) * k.s);
+        c[2 * w] = a.c;
+        c[2 * w + 1] = b.c;
+    }
+    if (CODES) {
+        cw[0] = pack_codes4(c[0], c[1], c[2], c[3]);
+        cw[1] = pack_codes4(c[4], c[5], c[6], c[7]);
+    }
+}
+
 template <int DT, bool CODES>
 __global__ __launch_bounds__(kThreads) void fakequant_fwd_kernel(
     const u32x4* __restrict__ x, const float* __restrict__ s_ptr, u32x4* __restrict__ y,
@@ -21,36 +41,32 @@ __global__ __launch_bounds__(kThreads) void fakequant_fwd_kernel(
 {
     using S = Store16<DT>;
     const QConst k = make_qconst(*s_ptr, bits);
-    const int64_t stride = (int64_t)gridDim.x * kThreads * kUnroll;
-    for (int64_t base = (int64_t)blockIdx.x * kThreads * kUnroll; base < nvec; base += stride) {
+    constexpr int64_t kChunk = (int64_t)kThreads * kUnroll;
+    const int64_t full_end = nvec / kChunk * kChunk;
+    // full chunks: no predication, all kUnroll loads of a lane in flight together
+    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < full_end; base += (int64_t)gridDim.x * kChunk) {
         u32x4 in[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            int64_t i = base + u * kThreads + threadIdx.x;
-            if (i < nvec) in[u] = __builtin_nontemporal_load(&x[i]);
-        }
+        for (int u = 0; u < kUnroll; ++u) in[u] = __builtin_nontemporal_load(&x[base + u * kThreads + threadIdx.x]);
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            int64_t i = base + u * kThreads + threadIdx.x;
-            if (i >= nvec) continue;
             u32x4 out;
-            uint32_t cw[2];
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                QElem a = quantize(S::lo(in[u][w]), k);
-                QElem b = quantize(S::hi(in[u][w]), k);
-                out[w] = S::pack(codef_of(a) * k.s, codef_of(b) * k.s);
-                if (CODES) {
-                    uint32_t two = __builtin_amdgcn_perm(__float_as_uint(b.c), __float_as_uint(a.c), 0x0c0c0400u);
-                    if (w & 1) cw[w >> 1] |= two << 16; else cw[w >> 1] = two;
-                }
-            }
-            __builtin_nontemporal_store(out, &y[i]);
-            if (CODES) { u32x2 c = {cw[0], cw[1]}; codes[i] = c; }
+            u32x2 cw;
+            fwd_vec<DT, CODES>(in[u], k, out, cw);
+            __builtin_nontemporal_store(out, &y[base + u * kThreads + threadIdx.x]);
+            if (CODES) codes[base + u * kThreads + threadIdx.x] = cw;
         }
     }
-    // scalar tail: elements [8*nvec, n)
-    if (blockIdx.x == 0 && threadIdx.x < (unsigned)(n - nvec * 8)) {
+    if (blockIdx.x != 0) return;
+    // remainder: fewer than kChunk vectors, then fewer than 8 scalars
+    for (int64_t i = full_end + threadIdx.x; i < nvec; i += kThreads) {
+        u32x4 out;
+        u32x2 cw;
+        fwd_vec<DT, CODES>(x[i], k, out, cw);
+        y[i] = out;
+        if (CODES) codes[i] = cw;
+    }
+    if (threadIdx.x < (unsigned)(n - nvec * 8)) {
         int64_t i = nvec * 8 + threadIdx.x;
         const uint16_t* xs = reinterpret_cast<const uint16_t*>(x);
         uint16_t* ys = reinterpret_cast<uint16_t*>(y);
@@ -71,53 +87,65 @@ __device__ __forceinline__ float ds_term(float x, float g, const QConst& k, bool
     return g * (keep ? u : q);
 }
 
+// Backward on one 8-element vector: dx bits and the fp32 sum of the 8 ds terms.
+template <int DT>
+__device__ __forceinline__ float bwd_vec(const u32x4& xin, const u32x4& gin, const QConst& k, u32x4& out)
+{
+    using S = Store16<DT>;
+    float part = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        bool ka, kb;
+        float ta = ds_term(S::lo(xin[w]), S::lo(gin[w]), k, ka);
+        float tb = ds_term(S::hi(xin[w]), S::hi(gin[w]), k, kb);
+        part += ta;
+        part += tb;
+        out[w] = gin[w] & ((ka ? 0x0000FFFFu : 0u) | (kb ? 0xFFFF0000u : 0u));
+    }
+    return part;
+}
+
 template <int DT, bool WRITE_DX>
 __global__ __launch_bounds__(kThreads) void fakequant_bwd_kernel(
-    const u32x4* __restrict__ x, const u32x4* __restrict__ dy, const float* __restrict__ s_ptr,
-    u32x4* __restrict__ dx, float* __restrict__ ds, uint32_t* __restrict__ ws_head,
+    const u32x4* __restrict__ x, const u32x4* dy, const float* __restrict__ s_ptr,
+    u32x4* dx, float* __restrict__ ds, uint32_t* __restrict__ ws_head,
     double* __restrict__ partials, int64_t nvec, int64_t n, int bits)
 {
     using S = Store16<DT>;
     const QConst k = make_qconst(*s_ptr, bits);
-    double acc = 0.0;
-    const int64_t stride = (int64_t)gridDim.x * kThreads * kUnroll;
-    for (int64_t base = (int64_t)blockIdx.x * kThreads * kUnroll; base < nvec; base += stride) {
+    double acc = 0.0;       // 8 terms are summed in fp32, everything above that in fp64
+    constexpr int64_t kChunk = (int64_t)kThreads * kUnroll;
+    const int64_t full_end = nvec / kChunk * kChunk;
+    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < full_end; base += (int64_t)gridDim.x * kChunk) {
         u32x4 xin[kUnroll], gin[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            int64_t i = base + u * kThreads + threadIdx.x;
-            if (i < nvec) {
-                xin[u] = __builtin_nontemporal_load(&x[i]);
-                gin[u] = __builtin_nontemporal_load(&dy[i]);
-            }
+            xin[u] = __builtin_nontemporal_load(&x[base + u * kThreads + threadIdx.x]);
+            gin[u] = __builtin_nontemporal_load(&dy[base + u * kThreads + threadIdx.x]);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            int64_t i = base + u * kThreads + threadIdx.x;
-            if (i >= nvec) continue;
             u32x4 out;
-            float part = 0.0f;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                bool ka, kb;
-                float ta = ds_term(S::lo(xin[u][w]), S::lo(gin[u][w]), k, ka);
-                float tb = ds_term(S::hi(xin[u][w]), S::hi(gin[u][w]), k, kb);
-                part += ta;
-                part += tb;
-                out[w] = gin[u][w] & ((ka ? 0x0000FFFFu : 0u) | (kb ? 0xFFFF0000u : 0u));
-            }
-            acc += (double)part;               // 8 terms in fp32, everything above in fp64
-            if (WRITE_DX) __builtin_nontemporal_store(out, &dx[i]);
+            acc += (double)bwd_vec<DT>(xin[u], gin[u], k, out);
+            if (WRITE_DX) __builtin_nontemporal_store(out, &dx[base + u * kThreads + threadIdx.x]);
         }
     }
-    if (blockIdx.x == 0 && threadIdx.x < (unsigned)(n - nvec * 8)) {
-        int64_t i = nvec * 8 + threadIdx.x;
-        const uint16_t* xs = reinterpret_cast<const uint16_t*>(x);
-        const uint16_t* gs = reinterpret_cast<const uint16_t*>(dy);
-        bool keep;
-        float t = ds_term(S::one(xs[i]), S::one(gs[i]), k, keep);
-        acc += (double)t;
-        if (WRITE_DX) reinterpret_cast<uint16_t*>(dx)[i] = keep ? gs[i] : (uint16_t)0;
+    if (blockIdx.x == 0) {
+        for (int64_t i = full_end + threadIdx.x; i < nvec; i += kThreads) {
+            u32x4 out;
+            acc += (double)bwd_vec<DT>(x[i], dy[i], k, out);
+            if (WRITE_DX) dx[i] = out;
+        }
+        if (threadIdx.x < (unsigned)(n - nvec * 8)) {
+            int64_t i = nvec * 8 + threadIdx.x;
+            const uint16_t* xs = reinterpret_cast<const uint16_t*>(x);
+            const uint16_t* gs = reinterpret_cast<const uint16_t*>(dy);
+            bool keep;
+            float t = ds_term(S::one(xs[i]), S::one(gs[i]), k, keep);
+            uint16_t g = gs[i];
+            acc += (double)t;
+            if (WRITE_DX) reinterpret_cast<uint16_t*>(dx)[i] = keep ? g : (uint16_t)0;
+        }
     }
 
     // block partial: lanes -> wave (shuffles) -> block (LDS), fixed order

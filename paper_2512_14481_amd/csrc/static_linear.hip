@@ -55,7 +55,7 @@ __device__ __forceinline__ float dequant(int acc, float c, float bias, bool has_
 }
 
 // ---------------------------------------------------------------------------------------------
-// Scalar kernel for shapes the MFMA kernel does not take (K not a multiple of 128): one thread
+// Scalar kernel for shapes the MFMA kernel does not take (K not a multiple of 64): one thread
 // per output element over pre-quantized activations.
 // ---------------------------------------------------------------------------------------------
 template <int DT, bool INT4>
@@ -89,39 +89,55 @@ __global__ __launch_bounds__(256) void linear_scalar_kernel(
 // ---------------------------------------------------------------------------------------------
 // int8 MFMA GEMM over pre-quantized activations.
 //
-// Workgroup tile 256 (m) x 256 (n), K step 128, 4 waves in a 2x2 arrangement, each wave owns a
-// 128x128 block as 4x4 tiles of v_mfma_i32_32x32x32_i8 (256 int32 accumulators per lane).
-// Both operand tiles go HBM/L2 -> LDS with direct 128-bit LDS loads, double buffered
-// (2 x (32 KB + 32 KB) = 128 KB of the CU's 160 KB LDS).
+// Workgroup tile 256 (m) x 256 (n), 4 waves in a 2x2 arrangement, each wave owns a 128x128 block
+// as 4x4 tiles of v_mfma_i32_32x32x32_i8 (256 int32 accumulators per lane, 1 wave per SIMD).
 //
-// LDS tile layout: row r (an m or n index) holds its 128 K-bytes as eight 16-byte chunks; chunk c
-// is stored at position c ^ swz(r), swz(r) = (r & 7) ^ ((r >> 3) & 1), so that the 128-bit reads
-// of 8 (or 16) consecutive rows at one logical chunk fall in distinct banks.
+// K pipeline: a ring of 4 LDS stages of 64 K-bytes each (16 KB per operand per stage, 128 KB in
+// all).  Operand tiles go L2 -> LDS with direct 128-bit LDS loads (no VGPR round trip), issued
+// one per four MFMAs so the wave never sits in a burst of memory issue, and three stages ahead
+// of their use.  Within a stage the fragments of the next K-substep are read from LDS while the
+// MFMAs of the current one run; there is one workgroup barrier per stage.
+//
+// LDS stage layout: row r (an m or n index) holds its 64 K-bytes as four 16-byte chunks; chunk c
+// is stored at position c ^ swz64(r), so that the 128-bit fragment reads of consecutive rows at
+// one logical chunk fall in distinct banks (rocprof: SQ_LDS_BANK_CONFLICT = 0).
 //
 // The MFMA pairs byte j of lane-group g in its A operand with byte j of lane-group g in its B
 // operand, so any assignment of K indices to (g, j) slots is valid as long as both operands use
 // the same one; here slot (g, j) of K-substep kk is k = 32*kk + 16*g + j.  The weight tile is
 // the MFMA's A operand and the activation tile its B operand: D[i][j] with i <-> n, j <-> m, so
-// a lane ends up with 4 consecutive n per accumulator quad and writes 8 contiguous bytes of Y.
+// a lane holds 4 consecutive n per accumulator quad.
+//
+// Epilogue: each wave dequantizes its 128x128 block, stages it through its own LDS region as
+// 16-bit values in [m][n] order and writes Y with 128-bit stores, 256 contiguous bytes per row.
 // ---------------------------------------------------------------------------------------------
-constexpr int kBM = 256, kBN = 256, kBK = 128;
-constexpr int kTileBytes = kBM * kBK;              // 32 KB per operand per stage
+constexpr int kBM = 256, kBN = 256, kBK = 64;
+constexpr int kStages = 4;
+constexpr int kStageBytes = kBM * kBK;              // 16 KB per operand per stage
 constexpr int kGemmThreads = 256;
+constexpr int kEpiStride = 272;                     // bytes per staged output row: 256 + 16 (bank spread)
+constexpr int kEpiBytes = 128 * kEpiStride;         // per wave
+constexpr int kGemmLds = 4 * kEpiBytes > kStages * 2 * kStageBytes ? 4 * kEpiBytes : kStages * 2 * kStageBytes;
 
-__device__ __forceinline__ int swz(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+__device__ __forceinline__ int swz64(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
 
-// XCD-aware tile order: workgroup ids are dealt round-robin to the 8 XCDs (each with its own
-// L2), so give each XCD a contiguous range of logical tiles, ordered m-fastest inside groups of
-// n-columns so that concurrently resident tiles share weight rows and activation rows in L2.
-__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn)
+// XCD-aware tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2:
+// give every XCD a contiguous range of logical tile ids, and number the tiles so that 32
+// consecutive ids (what one XCD's 32 CUs hold at a time) form an 8 (m) x 4 (n) block that shares
+// 8 activation row-panels and 4 weight row-panels in that L2.
+__device__ __forceinline__ bool tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn)
 {
     const int total = tiles_m * tiles_n;
-    const int xcd = bid & 7, slot = bid >> 3;
     const int per = (total + 7) >> 3;
-    int logical = xcd * per + slot;
-    if (logical > total) logical = total;     // total not a multiple of 8: id past the end = no tile
-    tm = logical % tiles_m;
-    tn = logical / tiles_m;
+    const int logical = (bid & 7) * per + (bid >> 3);
+    if (logical >= total) return false;
+    constexpr int PN = 4;                              // n-tiles per panel
+    const int panel = logical / (tiles_m * PN);
+    const int in = logical - panel * tiles_m * PN;
+    const int width = min(PN, tiles_n - panel * PN);   // last panel may be narrower
+    tm = in / width;
+    tn = panel * PN + in % width;
+    return true;
 }
 
 template <int DT>
@@ -132,44 +148,51 @@ void linear_mfma_kernel(const int8_t* __restrict__ xq, const int8_t* __restrict_
                         int32_t* __restrict__ acc_out, int M, int N, int K, int tiles_m, int tiles_n)
 {
     using S = Store16<DT>;
-    __shared__ __attribute__((aligned(1024))) char lds[2][2][kTileBytes];   // [stage][X|W][bytes]
+    __shared__ __attribute__((aligned(1024))) char lds[kGemmLds];
+    auto stage_ptr = [&](int st, int operand) -> char* { return &lds[(st * 2 + operand) * kStageBytes]; };
 
     int tm, tn;
-    tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
-    if (tn >= tiles_n) return;
+    if (!tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
     const int m0 = tm * kBM, n0 = tn * kBN;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave & 1, wn = wave >> 1;
 
-    // ---- global -> LDS addressing: issue j of wave w fills rows (4j + w)*8 .. +8 of a tile ----
-    const int lrow = lane >> 3;                       // row within the 8-row slab
-    const int lchunk = (lane & 7) ^ swz(wave * 8 + lrow);   // logical chunk this lane fetches
-    const int8_t* gx[8];
-    const int8_t* gw[8];
+    // ---- global -> LDS: load j of wave w fills rows (4j + w)*16 .. +16 of a stage (1 KB) ----
+    // Lane i writes LDS slot i of that 1 KB: row i/4, position i%4; it therefore fetches the
+    // logical chunk (i%4) ^ swz64(row), and swz64 of these rows depends on the lane only.
+    const int lrow = lane >> 2;
+    const int lchunk = (lane & 3) ^ (((lane >> 3) & 3) ^ ((lane >> 5) & 1));
+    const int8_t* gx[4];
+    const int8_t* gw[4];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        int r = (4 * j + wave) * 8 + lrow;
-        int mr = min(m0 + r, M - 1), nr = min(n0 + r, N - 1);
+    for (int j = 0; j < 4; ++j) {
+        const int r = (4 * j + wave) * 16 + lrow;
+        const int mr = min(m0 + r, M - 1), nr = min(n0 + r, N - 1);   // rows past the edge re-read the last row
         gx[j] = xq + (int64_t)mr * K + lchunk * 16;
         gw[j] = wq + (int64_t)nr * K + lchunk * 16;
     }
-    auto issue_tile = [&](int stage, int kt) {
-        const int koff = kt * kBK;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int slab = (4 * j + wave) * 1024;
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(gx[j] + koff), (lds_ptr_t)(&lds[stage][0][slab]), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(gw[j] + koff), (lds_ptr_t)(&lds[stage][1][slab]), 16, 0, 0);
-        }
+    // load q (0..3: activation slabs, 4..7: weight slabs) of K tile kt into stage st
+    auto issue_one = [&](int st, int kt, int q) {
+        const int j = q & 3;
+        const int slab = (4 * j + wave) * 1024;
+        if (q < 4) __builtin_amdgcn_global_load_lds((glb_ptr_t)(gx[j] + kt * kBK), (lds_ptr_t)(stage_ptr(st, 0) + slab), 16, 0, 0);
+        else       __builtin_amdgcn_global_load_lds((glb_ptr_t)(gw[j] + kt * kBK), (lds_ptr_t)(stage_ptr(st, 1) + slab), 16, 0, 0);
     };
 
-    // ---- LDS -> register addressing ----
+    // ---- LDS -> registers ----
     const int frow = lane & 31, fgrp = lane >> 5;
-    int foff[4];
+    int foff[2];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) foff[kk] = frow * kBK + (((kk * 2 + fgrp) ^ swz(frow)) << 4);
+    for (int kk = 0; kk < 2; ++kk) foff[kk] = frow * kBK + (((kk * 2 + fgrp) ^ swz64(frow)) << 4);
     const int xbase = wm * 128 * kBK, wbase = wn * 128 * kBK;
+    i32x4 fx[2][4], fw[2][4];
+    auto read_x = [&](int set, int st, int kk, int t) {
+        fx[set][t] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 0) + xbase + t * 32 * kBK + foff[kk]);
+    };
+    auto read_w = [&](int set, int st, int kk, int t) {
+        fw[set][t] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 1) + wbase + t * 32 * kBK + foff[kk]);
+    };
 
     i32x16 acc[4][4];   // [n tile][m tile]
 #pragma unroll
@@ -179,78 +202,112 @@ void linear_mfma_kernel(const int8_t* __restrict__ xq, const int8_t* __restrict_
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
 
+    // Loads past the last K tile are clamped to the last tile: they land in stages that are free
+    // anyway, keep the loop branch-free and the vmcnt bookkeeping constant.
     const int KT = K / kBK;
-    issue_tile(0, 0);
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < KT) {
-            issue_tile(cur ^ 1, kt + 1);
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(16));     // tile kt has landed, kt+1 in flight
-        } else {
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-        }
-        __builtin_amdgcn_s_barrier();
-        const char* sx = &lds[cur][0][xbase];
-        const char* sw = &lds[cur][1][wbase];
+    // prologue: tiles 0, 1, 2 and the first half of tile 3
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            i32x4 fx[4], fw[4];
+    for (int t0 = 0; t0 < 3; ++t0) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                fx[t] = *reinterpret_cast<const i32x4*>(sx + t * 32 * kBK + foff[kk]);
-                fw[t] = *reinterpret_cast<const i32x4*>(sw + t * 32 * kBK + foff[kk]);
-            }
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[a], fx[b], acc[a][b], 0, 0, 0);
-        }
-        __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
-        __builtin_amdgcn_s_barrier();                        // everyone is done reading stage cur
+        for (int q = 0; q < 8; ++q) issue_one(t0, min(t0, KT - 1), q);
     }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) issue_one(3, min(3, KT - 1), q);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(20));             // tile 0 has landed
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int t = 0; t < 4; ++t) { read_x(0, 0, 0, t); read_w(0, 0, 0, t); }
+
+    for (int kt = 0; kt < KT; ++kt) {
+        const int st = kt & 3;
+        const int t3 = min(kt + 3, KT - 1), t4 = min(kt + 4, KT - 1);
+        // phase 0: MFMAs of K-substep 0; read substep 1; second half of tile kt+3
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            read_x(1, st, 1, g); read_w(1, st, 1, g);
+            issue_one((kt + 3) & 3, t3, 4 + g);
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[0][g], fx[0][b], acc[g][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        asm volatile("" ::: "memory");
+        // Substep-1 fragments are in registers, so this stage may be refilled after the barrier;
+        // tile kt+1 has landed for this wave (the 16 newer loads may still be in flight), so after
+        // the barrier it is complete for everyone.
+        __builtin_amdgcn_s_waitcnt(kWaitLgkm0 & waitcnt_vm(16));
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        // phase 1: MFMAs of substep 1; read substep 0 of the next tile; first half of tile kt+4
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            read_x(0, (kt + 1) & 3, 0, g); read_w(0, (kt + 1) & 3, 0, g);
+            issue_one(st, t4, g);
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[1][g], fx[1][b], acc[g][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    // drain the clamped tail loads and the last fragment reads before LDS is reused
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0 & waitcnt_vm(0));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 
     // ---- epilogue: D[i][j], i = 8*(v/4) + 4*(lane/32) + v%4 -> n, j = lane%32 -> m ----
     const float s = *s_ptr;
     const bool has_bias = bias != nullptr;
-    const bool vec_ok = (N & 3) == 0;
+    char* epi = &lds[wave * kEpiBytes];
+    const int wn0 = n0 + wn * 128, wm0 = m0 + wm * 128;
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const int n = n0 + wn * 128 + a * 32 + 8 * g + 4 * fgrp;
+            const int nl = a * 32 + 8 * g + 4 * fgrp;          // column within the wave's block
             float c[4], bz[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int ne = min(n + e, N - 1);
+                const int ne = min(wn0 + nl + e, N - 1);
                 c[e] = s * s_w[ne];
                 bz[e] = has_bias ? bias[ne] : 0.0f;
             }
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                const int m = m0 + wm * 128 + b * 32 + frow;
-                if (m >= M || n >= N) continue;
-                const int64_t o = (int64_t)m * N + n;
-                if (vec_ok && n + 3 < N) {
-                    u32x2 pk;
-                    pk[0] = S::pack(dequant(acc[a][b][4 * g + 0], c[0], bz[0], has_bias),
-                                    dequant(acc[a][b][4 * g + 1], c[1], bz[1], has_bias));
-                    pk[1] = S::pack(dequant(acc[a][b][4 * g + 2], c[2], bz[2], has_bias),
-                                    dequant(acc[a][b][4 * g + 3], c[3], bz[3], has_bias));
-                    *reinterpret_cast<u32x2*>(y + o) = pk;
-                    if (acc_out) {
-                        i32x4 av = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
-                        *reinterpret_cast<i32x4*>(acc_out + o) = av;
-                    }
-                } else {
+                const int ml = b * 32 + frow;
+                u32x2 pk;
+                pk[0] = S::pack(dequant(acc[a][b][4 * g + 0], c[0], bz[0], has_bias),
+                                dequant(acc[a][b][4 * g + 1], c[1], bz[1], has_bias));
+                pk[1] = S::pack(dequant(acc[a][b][4 * g + 2], c[2], bz[2], has_bias),
+                                dequant(acc[a][b][4 * g + 3], c[3], bz[3], has_bias));
+                *reinterpret_cast<u32x2*>(epi + ml * kEpiStride + nl * 2) = pk;
+                if (acc_out) {
+                    const int m = wm0 + ml, n = wn0 + nl;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (n + e >= N) continue;
-                        y[o + e] = S::enc(dequant(acc[a][b][4 * g + e], c[e], bz[e], has_bias));
-                        if (acc_out) acc_out[o + e] = acc[a][b][4 * g + e];
-                    }
+                    for (int e = 0; e < 4; ++e)
+                        if (m < M && n + e < N) acc_out[(int64_t)m * N + n + e] = acc[a][b][4 * g + e];
                 }
             }
+        }
+    }
+    // each wave reads back only what it wrote itself: no workgroup barrier needed
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+    const bool vec_ok = (N & 7) == 0;
+    const int crow = lane >> 4, cchunk = lane & 15;            // 4 rows x 16 chunks of 16 B per pass
+#pragma unroll 4
+    for (int it = 0; it < 32; ++it) {
+        const int ml = it * 4 + crow;
+        const int m = wm0 + ml, n = wn0 + cchunk * 8;
+        if (m >= M || n >= N) continue;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(epi + ml * kEpiStride + cchunk * 16);
+        uint16_t* dst = y + (int64_t)m * N + n;
+        if (vec_ok && n + 7 < N) {
+            *reinterpret_cast<u32x4*>(dst) = v;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (n + e < N) dst[e] = (uint16_t)(v[e >> 1] >> (16 * (e & 1)));
         }
     }
 }
@@ -316,7 +373,7 @@ extern "C" int sasq_static_linear(const void* x, const float* s, const void* wq,
     }
 
     const int8_t* w8 = static_cast<const int8_t*>(wq);
-    const bool mfma_ok = (K % kBK) == 0;
+    const bool mfma_ok = (K % kBK) == 0 && K >= kBK;
     if (wf == SASQ_W_INT4_PACKED && mfma_ok) {
         const int64_t nb = N * (K / 2);
         int64_t ub = (nb + 255) / 256;
