@@ -12,7 +12,10 @@ namespace sasq {
 
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;                       // 128-bit accesses in flight per lane per stream
-constexpr int kMaxReduceBlocks = 4096;           // upper bound on partials in the workspace
+constexpr int kMaxReduceBlocks = 256;            // one block per CU: every block ends with one
+                                                 // agent-scope store + ticket atomic on a single
+                                                 // address, so more blocks only lengthen the tail
+constexpr int kMaxFwdBlocks = 2048;
 
 // Forward on one 8-element vector.
 template <int DT, bool CODES>
@@ -160,8 +163,11 @@ __global__ __launch_bounds__(kThreads) void fakequant_bwd_kernel(
 #pragma unroll
         for (int i = 0; i < kThreads / kWave; ++i) b += wave_part[i];
         __hip_atomic_store(&partials[blockIdx.x], b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __threadfence();
-        uint32_t ticket = atomicAdd(&ws_head[0], 1u);
+        // The partial went out as an agent-scope atomic store (written through to where every XCD
+        // sees it); waiting for its acknowledgement orders it before the ticket.  A release fence
+        // here would instead write back this XCD's whole L2 once per block.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        uint32_t ticket = __hip_atomic_fetch_add(&ws_head[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         is_last = (ticket == kTicketBase + gridDim.x - 1);
         if (ticket - kTicketBase >= gridDim.x)      // workspace was never initialised: fail loudly
             *ds = __uint_as_float(0x7FC00000u);
@@ -170,10 +176,19 @@ __global__ __launch_bounds__(kThreads) void fakequant_bwd_kernel(
     if (!is_last) return;
 
     // deterministic second pass by the last block to arrive: fixed strided order, fp64
-    __threadfence();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    // all of a thread's partials are requested before the first is used (one memory latency, not
+    // one per partial); the summation order stays fixed
+    constexpr int kPer = kMaxReduceBlocks / kThreads;
+    double pv[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int i = j * kThreads + threadIdx.x;
+        pv[j] = __hip_atomic_load(&partials[i < (int)gridDim.x ? i : 0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     double t = 0.0;
-    for (int i = threadIdx.x; i < (int)gridDim.x; i += kThreads)
-        t += __hip_atomic_load(&partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) t += (j * kThreads + (int)threadIdx.x < (int)gridDim.x) ? pv[j] : 0.0;
     __shared__ double tree[kThreads];
     tree[threadIdx.x] = t;
     __syncthreads();
@@ -224,7 +239,7 @@ extern "C" int sasq_fakequant_fwd(const void* x, const float* s, void* y, int8_t
     if (rc) return rc;
     if (!aligned16(x) || !aligned16(y) || (codes && (reinterpret_cast<uintptr_t>(codes) & 7u))) return SASQ_ERR_ALIGN;
     const int64_t n = rows * cols, nvec = n / 8;
-    const int grid = grid_for(nvec, 1 << 20);
+    const int grid = grid_for(nvec, kMaxFwdBlocks);
     hipStream_t st = as_stream(stream);
     auto X = static_cast<const u32x4*>(x);
     auto Y = static_cast<u32x4*>(y);

@@ -87,19 +87,27 @@ __global__ __launch_bounds__(kPrepThreads) void absmax_kernel(
     if (threadIdx.x == 0) {
         for (int i = 1; i < kPrepThreads / kWave; ++i) m = sh[i] > m ? sh[i] : m;
         __hip_atomic_store(&partials[blockIdx.x], m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __threadfence();
-        uint32_t ticket = atomicAdd(&ws_head[0], 1u);
+        // The partial went out as an agent-scope atomic store (written through to where every XCD
+        // sees it); waiting for its acknowledgement orders it before the ticket.  A release fence
+        // here would instead write back this XCD's whole L2 once per block.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        uint32_t ticket = __hip_atomic_fetch_add(&ws_head[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         is_last = (ticket == kTicketBase + gridDim.x - 1);
         if (ticket - kTicketBase >= gridDim.x) *s = __uint_as_float(0x7FC00000u);
     }
     __syncthreads();
     if (!is_last) return;
-    __threadfence();
-    uint32_t t = 0;
-    for (int i = threadIdx.x; i < (int)gridDim.x; i += kPrepThreads) {
-        uint32_t p = __hip_atomic_load(&partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        t = p > t ? p : t;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    constexpr int kPer = kMaxAbsmaxBlocks / kPrepThreads;
+    uint32_t pv[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int i = j * kPrepThreads + threadIdx.x;
+        pv[j] = __hip_atomic_load(&partials[i < (int)gridDim.x ? i : 0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    uint32_t t = 0;
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) t = pv[j] > t ? pv[j] : t;     // a duplicate of partial 0 cannot change a max
     t = wave_max(t);
     __syncthreads();
     if (threadIdx.x % kWave == 0) sh[threadIdx.x / kWave] = t;

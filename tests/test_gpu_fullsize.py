@@ -1,0 +1,136 @@
+"""GPU parity at the full sizes of the five workload configurations, in the launch configuration
+the benchmark times (MFMA path, no debug outputs for Y; int32 accumulators requested separately).
+
+Fake-quant forward/backward and the activation codes are compared over the WHOLE tensor (the
+oracle handles 2e8 elements in seconds).  The linear is compared on sampled output rows and
+columns that the oracle computes one by one (all N outputs of a sampled token, all M outputs of a
+sampled channel, always including the first/last row and column and tile-edge neighbours).
+"""
+from __future__ import annotations
+
+import functools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2512_14481_amd import binding as B
+from paper_2512_14481_amd import workloads as wl
+from tests.gpu_util import TDT, assert_same_values, dev_scalar, to_bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+CASES_ACT = [(c.name, a.name) for c in wl.CONFIGS.values() for a in c.acts]
+CASES_PROJ = [(c.name, p.name) for c in wl.CONFIGS.values() for p in c.projs]
+
+
+@functools.lru_cache(maxsize=2)
+def activation_bits(cfg_name: str, act_name: str) -> np.ndarray:
+    return wl.activation(wl.CONFIGS[cfg_name], act_name)
+
+
+@pytest.fixture(scope="module")
+def ws():
+    return B.new_workspace(1 << 20)
+
+
+@pytest.mark.parametrize("cfg_name,act_name", CASES_ACT)
+def test_fakequant_full_tensor(cfg_name, act_name, ws):
+    cfg = wl.CONFIGS[cfg_name]
+    dtype = cfg.dtype
+    xb = activation_bits(cfg_name, act_name)
+    proj = next(p for p in cfg.projs if p.x == act_name)
+    dyb = wl.upstream_grad(cfg, proj.name)
+    x, dy = to_dev(xb, dtype), to_dev(dyb, dtype)
+    s_dev = torch.zeros(1, dtype=torch.float32, device="cuda")
+    B.sasq_absmax_scale(x, s_dev, ws, 8)
+    s0 = oracle.absmax_scale(xb, 8, dtype)
+    assert np.float32(s_dev.item()) == s0, "absmax initial scale"
+    y = torch.empty_like(x)
+    dx = torch.empty_like(x)
+    codes = torch.empty(x.shape, dtype=torch.int8, device="cuda")
+    ds = torch.zeros(1, dtype=torch.float32, device="cuda")
+    for s in (s0, np.float32(s0 / 4)):           # the init scale (nothing clips) and a trained-like one
+        sd = dev_scalar(s)
+        B.sasq_fakequant_fwd(x, sd, y, codes, 8)
+        B.sasq_fakequant_bwd(x, dy, sd, dx, ds, ws, 8)
+        torch.cuda.synchronize()
+        y_ref, c_ref = oracle.fakequant_fwd(xb, s, 8, dtype)
+        assert np.array_equal(codes.cpu().numpy(), c_ref), f"codes s={s}"
+        assert_same_values(to_bits(y), y_ref, dtype, f"y s={s}", rel=1e-3)
+        assert_same_values(to_bits(y), y_ref, dtype, f"y (exact) s={s}")
+        ref = oracle.fakequant_bwd(xb, dyb, s, 8, dtype)
+        assert_same_values(to_bits(dx), ref["dx"], dtype, f"dx s={s}")
+        got = float(ds.item())
+        assert abs(got - ref["ds64"]) <= 1e-4 * abs(ref["ds64"]), (s, got, ref["ds64"], ref["sum_abs"])
+        if s == s0:
+            assert np.array_equal(to_bits(dx), dyb), "nothing clips at the absmax scale: dx == dy"
+        # the timed configuration: no codes output
+        y2 = torch.empty_like(x)
+        B.sasq_fakequant_fwd(x, sd, y2, None, 8)
+        assert torch.equal(y2.view(torch.int16), y.view(torch.int16))
+        ds2 = torch.zeros(1, dtype=torch.float32, device="cuda")
+        B.sasq_fakequant_bwd(x, dy, sd, dx, ds2, ws, 8)
+        assert ds2.view(torch.int32).item() == ds.view(torch.int32).item(), "ds is run-to-run reproducible"
+
+
+def sample_indices(n: int, tile: int, count: int, seed: int) -> np.ndarray:
+    rng = np.random.default_rng(seed)
+    fixed = [0, n - 1, min(tile - 1, n - 1), min(tile, n - 1), (n // tile) * tile - 1 if n >= tile else 0,
+             min((n // tile) * tile, n - 1), n // 2]
+    rnd = rng.integers(0, n, size=max(count - len(fixed), 0))
+    return np.unique(np.array(fixed + rnd.tolist(), dtype=np.int64))
+
+
+@pytest.mark.parametrize("cfg_name,proj_name", CASES_PROJ)
+def test_static_linear_full_size(cfg_name, proj_name, ws):
+    cfg = wl.CONFIGS[cfg_name]
+    dtype, fmt = cfg.dtype, cfg.w_fmt
+    proj = next(p for p in cfg.projs if p.name == proj_name)
+    xb = activation_bits(cfg_name, proj.x)
+    M, K, N = cfg.M, cfg.K_of(proj), proj.N
+    wf = B.SASQ_W_INT8 if fmt == "int8" else B.SASQ_W_INT4_PACKED
+
+    # frozen weights: quantized by the library on the device and by the oracle on the host
+    w = wl.weight_fp32(cfg, proj.name)
+    wq_ref, sw_ref = oracle.quantize_weight(w, fmt)
+    wd = torch.from_numpy(w).cuda()
+    wq = torch.empty(wq_ref.shape, dtype=torch.int8 if fmt == "int8" else torch.uint8, device="cuda")
+    s_w = torch.empty(N, dtype=torch.float32, device="cuda")
+    B.sasq_quantize_weight(wd, wq, s_w, wf)
+    del wd, w
+    assert np.array_equal(s_w.cpu().numpy(), sw_ref), "per-channel weight scales"
+    assert np.array_equal(wq.cpu().numpy(), wq_ref), "weight codes"
+
+    s = np.float32(oracle.absmax_scale(xb, 8, dtype) / 4)
+    x = to_dev(xb, dtype)
+    sd = dev_scalar(s)
+    y = torch.empty((M, N), dtype=TDT[dtype], device="cuda")
+    wsl = B.new_workspace(B.sasq_static_linear_workspace(M, N, K, wf))
+    B.sasq_static_linear(x, sd, wq, s_w, None, y, wf, wsl)            # the timed configuration
+    torch.cuda.synchronize()
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
+    y_dbg = torch.empty_like(y)
+    B.sasq_static_linear(x, sd, wq, s_w, None, y_dbg, wf, wsl, acc, xq)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y_dbg.view(torch.int16))
+
+    # every activation code
+    _, c_ref = oracle.fakequant_fwd(xb, s, 8, dtype)
+    assert np.array_equal(xq.cpu().numpy(), c_ref), "activation codes of the linear"
+    del xq, c_ref
+
+    rows = sample_indices(M, 256, 24, seed=1)
+    cols = sample_indices(N, 256, 24, seed=2)
+    ref_r = oracle.static_linear(np.ascontiguousarray(xb[rows]), s, wq_ref, sw_ref, None, 8, fmt, dtype, want_xq=False)
+    assert np.array_equal(acc[torch.from_numpy(rows).cuda()].cpu().numpy(), ref_r["acc"]), "int32 accumulators (rows)"
+    assert_same_values(to_bits(y[torch.from_numpy(rows).cuda()]), ref_r["y"], dtype, "Y rows", rel=1e-3)
+    assert_same_values(to_bits(y[torch.from_numpy(rows).cuda()]), ref_r["y"], dtype, "Y rows (exact)")
+    ref_c = oracle.static_linear(xb, s, np.ascontiguousarray(wq_ref[cols]), np.ascontiguousarray(sw_ref[cols]),
+                                 None, 8, fmt, dtype, want_xq=False)
+    ci = torch.from_numpy(cols).cuda()
+    assert np.array_equal(acc[:, ci].cpu().numpy(), ref_c["acc"]), "int32 accumulators (columns)"
+    assert_same_values(to_bits(y[:, ci].contiguous()), ref_c["y"], dtype, "Y columns (exact)")
+    assert torch.isfinite(y.float()).all()
