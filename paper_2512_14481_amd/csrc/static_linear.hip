@@ -1,6 +1,9 @@
 // Static-inference quantized linear (Sec. 3, Eq. 2) for gfx950: activation quantize with the
 // fixed scale, int8 MFMA GEMM against frozen per-output-channel weights, dequantizing epilogue.
 #include "sasq_device.h"
+#include <cstdlib>
+#include <cstring>
+#include <type_traits>
 
 namespace sasq {
 
@@ -115,6 +118,7 @@ constexpr int kBM = 256, kBN = 256, kBK = 64;
 constexpr int kStages = 4;
 constexpr int kStageBytes = kBM * kBK;              // 16 KB per operand per stage
 constexpr int kGemmThreads = 256;
+constexpr int64_t kFusedMaxN = 0;                   // quantize-on-load when N has at most this many columns
 constexpr int kEpiStride = 272;                     // bytes per staged output row: 256 + 16 (bank spread)
 constexpr int kEpiBytes = 128 * kEpiStride;         // per wave
 constexpr int kGemmLds = 4 * kEpiBytes > kStages * 2 * kStageBytes ? 4 * kEpiBytes : kStages * 2 * kStageBytes;
@@ -140,12 +144,28 @@ __device__ __forceinline__ bool tile_of_block(int bid, int tiles_m, int tiles_n,
     return true;
 }
 
-template <int DT>
+// Operand paths of the GEMM kernel.
+//   XMODE 0: activations were quantized by a separate pass; int8 tile goes L2 -> LDS directly.
+//   XMODE 1: quantize-on-load: the 16-bit activation tile is loaded into registers, quantized
+//            with the fixed scale (Sec. 3, Eq. 1) and written to LDS as int8.
+//   WMODE 0: int8 weights, L2 -> LDS directly.
+//   WMODE 1: packed int4 weights: loaded into registers and unpacked there.  A nibble moved to
+//            the high half of a byte is the int8 value 16*w, so two mask/shift operations turn
+//            8 nibbles into 8 bytes; the accumulator is then exactly 16*acc and is shifted back
+//            in the epilogue.  The even nibbles of a dword come out before the odd ones, so
+//            within every group of 8 consecutive k the byte order is (0,2,4,6,1,3,5,7); the
+//            activation bytes are stored in the same order (any K order common to both operands
+//            gives the same dot product).
+enum { X_PREQ = 0, X_FUSED = 1 };
+enum { W_I8 = 0, W_I4 = 1 };
+
+template <int DT, int XMODE, int WMODE>
 __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
-void linear_mfma_kernel(const int8_t* __restrict__ xq, const int8_t* __restrict__ wq,
+void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict__ wq,
                         const float* __restrict__ s_ptr, const float* __restrict__ s_w,
                         const float* __restrict__ bias, uint16_t* __restrict__ y,
-                        int32_t* __restrict__ acc_out, int M, int N, int K, int tiles_m, int tiles_n)
+                        int32_t* __restrict__ acc_out, int M, int N, int K, int a_bits,
+                        int tiles_m, int tiles_n)
 {
     using S = Store16<DT>;
     __shared__ __attribute__((aligned(1024))) char lds[kGemmLds];
@@ -155,10 +175,16 @@ void linear_mfma_kernel(const int8_t* __restrict__ xq, const int8_t* __restrict_
     if (!tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
     const int m0 = tm * kBM, n0 = tn * kBN;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave & 1, wn = wave >> 1;
+    const int KT = K / kBK;
+    auto eff_tile = [&](int T) { return min(max(T, 0), KT - 1); };
+    // LDS stage of K tile T.  Tiles before the first are directed at tile 0's own stage (an
+    // identical rewrite), tiles past the last at the stage they would own (free by then).
+    auto stage_of = [&](int T) { return (T < 0 ? 0 : T) & 3; };
 
-    // ---- global -> LDS: load j of wave w fills rows (4j + w)*16 .. +16 of a stage (1 KB) ----
+    // ---- direct L2 -> LDS path: load j of wave w fills rows (4j + w)*16 .. +16 of a stage ----
     // Lane i writes LDS slot i of that 1 KB: row i/4, position i%4; it therefore fetches the
     // logical chunk (i%4) ^ swz64(row), and swz64 of these rows depends on the lane only.
     const int lrow = lane >> 2;
@@ -169,18 +195,84 @@ void linear_mfma_kernel(const int8_t* __restrict__ xq, const int8_t* __restrict_
     for (int j = 0; j < 4; ++j) {
         const int r = (4 * j + wave) * 16 + lrow;
         const int mr = min(m0 + r, M - 1), nr = min(n0 + r, N - 1);   // rows past the edge re-read the last row
-        gx[j] = xq + (int64_t)mr * K + lchunk * 16;
-        gw[j] = wq + (int64_t)nr * K + lchunk * 16;
+        gx[j] = static_cast<const int8_t*>(xin) + (int64_t)mr * K + lchunk * 16;
+        gw[j] = reinterpret_cast<const int8_t*>(wq) + (int64_t)nr * K + lchunk * 16;
     }
-    // load q (0..3: activation slabs, 4..7: weight slabs) of K tile kt into stage st
-    auto issue_one = [&](int st, int kt, int q) {
-        const int j = q & 3;
-        const int slab = (4 * j + wave) * 1024;
-        if (q < 4) __builtin_amdgcn_global_load_lds((glb_ptr_t)(gx[j] + kt * kBK), (lds_ptr_t)(stage_ptr(st, 0) + slab), 16, 0, 0);
-        else       __builtin_amdgcn_global_load_lds((glb_ptr_t)(gw[j] + kt * kBK), (lds_ptr_t)(stage_ptr(st, 1) + slab), 16, 0, 0);
+    auto dma_x = [&](int T, int j) {
+        __builtin_amdgcn_global_load_lds((glb_ptr_t)(gx[j] + eff_tile(T) * kBK),
+                                         (lds_ptr_t)(stage_ptr(stage_of(T), 0) + (4 * j + wave) * 1024), 16, 0, 0);
+    };
+    auto dma_w = [&](int T, int j) {
+        __builtin_amdgcn_global_load_lds((glb_ptr_t)(gw[j] + eff_tile(T) * kBK),
+                                         (lds_ptr_t)(stage_ptr(stage_of(T), 1) + (4 * j + wave) * 1024), 16, 0, 0);
     };
 
-    // ---- LDS -> registers ----
+    // ---- register path: thread t owns 16-byte chunk t%4 of rows t/4 + 64j, j = 0..3 ----
+    const int rrow = tid >> 2, rchunk = tid & 3;
+    const int rslot = rrow * kBK + ((rchunk ^ swz64(rrow)) << 4);       // swz64(rrow + 64j) == swz64(rrow)
+    const QConst qk = make_qconst(*s_ptr, a_bits);
+    u32x4 xr[3][8];     // XMODE 1: three K tiles of 16-bit activations in flight (2 x 128 bit per task)
+    u32x2 wr[3][4];     // WMODE 1: three K tiles of packed int4 weights in flight (64 bit per task)
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+#pragma unroll
+        for (int b = 0; b < 8; ++b) xr[a][b] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int b = 0; b < 4; ++b) wr[a][b] = u32x2{0u, 0u};
+    }
+    const uint16_t* rx[4];
+    const uint8_t* rw[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int mr = min(m0 + rrow + 64 * j, M - 1), nr = min(n0 + rrow + 64 * j, N - 1);
+        rx[j] = static_cast<const uint16_t*>(xin) + (int64_t)mr * K + rchunk * 16;
+        rw[j] = wq + (int64_t)nr * (K / 2) + rchunk * 8;
+    }
+    // Register sets are selected with compile-time indices (a run-time index would put the arrays
+    // in scratch memory): the K loop is unrolled by 3 and passes set = tile mod 3 as a constant.
+    auto regload_x = [&](int T, auto set_c) {
+        constexpr int set = decltype(set_c)::value;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const u32x4* p = reinterpret_cast<const u32x4*>(rx[j] + eff_tile(T) * kBK);
+            xr[set][2 * j] = p[0];
+            xr[set][2 * j + 1] = p[1];
+        }
+    };
+    auto regload_w = [&](int T, auto set_c) {
+        constexpr int set = decltype(set_c)::value;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) wr[set][j] = *reinterpret_cast<const u32x2*>(rw[j] + eff_tile(T) * (kBK / 2));
+    };
+    // quantize task j of tile T (16 elements) and store the 16 int8 codes
+    auto convert_x = [&](int T, int j, auto set_c) {
+        constexpr int set = decltype(set_c)::value;
+        float c[16];
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                c[8 * h + 2 * w] = quantize(S::lo(xr[set][2 * j + h][w]), qk).c;
+                c[8 * h + 2 * w + 1] = quantize(S::hi(xr[set][2 * j + h][w]), qk).c;
+            }
+        u32x4 o;
+        if (WMODE == W_I4) {
+            o[0] = pack_codes4(c[0], c[2], c[4], c[6]);    o[1] = pack_codes4(c[1], c[3], c[5], c[7]);
+            o[2] = pack_codes4(c[8], c[10], c[12], c[14]); o[3] = pack_codes4(c[9], c[11], c[13], c[15]);
+        } else {
+            o[0] = pack_codes4(c[0], c[1], c[2], c[3]);    o[1] = pack_codes4(c[4], c[5], c[6], c[7]);
+            o[2] = pack_codes4(c[8], c[9], c[10], c[11]);  o[3] = pack_codes4(c[12], c[13], c[14], c[15]);
+        }
+        *reinterpret_cast<u32x4*>(stage_ptr(stage_of(T), 0) + (rslot + 64 * j * kBK)) = o;
+    };
+    auto convert_w = [&](int T, int j, auto set_c) {
+        constexpr int set = decltype(set_c)::value;
+        const uint32_t w0 = wr[set][j][0], w1 = wr[set][j][1];
+        u32x4 o = {(w0 << 4) & 0xF0F0F0F0u, w0 & 0xF0F0F0F0u, (w1 << 4) & 0xF0F0F0F0u, w1 & 0xF0F0F0F0u};
+        *reinterpret_cast<u32x4*>(stage_ptr(stage_of(T), 1) + (rslot + 64 * j * kBK)) = o;
+    };
+
+    // ---- LDS -> MFMA fragments ----
     const int frow = lane & 31, fgrp = lane >> 5;
     int foff[2];
 #pragma unroll
@@ -202,64 +294,88 @@ void linear_mfma_kernel(const int8_t* __restrict__ xq, const int8_t* __restrict_
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
 
-    // Loads past the last K tile are clamped to the last tile: they land in stages that are free
-    // anyway, keep the loop branch-free and the vmcnt bookkeeping constant.
-    const int KT = K / kBK;
-    // prologue: tiles 0, 1, 2 and the first half of tile 3
-#pragma unroll
-    for (int t0 = 0; t0 < 3; ++t0) {
-#pragma unroll
-        for (int q = 0; q < 8; ++q) issue_one(t0, min(t0, KT - 1), q);
-    }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) issue_one(3, min(3, KT - 1), q);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(20));             // tile 0 has landed
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-#pragma unroll
-    for (int t = 0; t < 4; ++t) { read_x(0, 0, 0, t); read_w(0, 0, 0, t); }
-
-    for (int kt = 0; kt < KT; ++kt) {
-        const int st = kt & 3;
-        const int t3 = min(kt + 3, KT - 1), t4 = min(kt + 4, KT - 1);
-        // phase 0: MFMAs of K-substep 0; read substep 1; second half of tile kt+3
+    // ---- K pipeline ----
+    // Iteration i consumes K tile i.  Its phase 0 issues the weight loads of tile i+3, its phase 1
+    // the activation loads of tile i+4, so the per-wave issue order is W(i+3), X(i+4), W(i+4), ...
+    // and every "has landed" condition below is one s_waitcnt vmcnt(n) with n = loads issued
+    // later (memory loads return in issue order).  Register-path tiles are converted into LDS
+    // ahead of use: X(i+1) half in phase 1 of iteration i-1 and half in phase 0 of iteration i,
+    // W(i+1) in phase 0 of iteration i.  Iterations -4..-1 only fill the pipeline.
+    constexpr int nX = XMODE == X_FUSED ? 8 : 4;     // loads per wave per K tile
+    constexpr int nW = 4;
+    auto iteration = [&](int i, auto math_tag, auto r_tag) {
+        constexpr bool MATH = decltype(math_tag)::value;
+        constexpr int R = decltype(r_tag)::value;              // (i + 6) % 3: register set of tile i
+        using S0 = std::integral_constant<int, R>;
+        using S1 = std::integral_constant<int, (R + 1) % 3>;
+        using S2 = std::integral_constant<int, (R + 2) % 3>;
+        const int st = i & 3;
+        // ---------------- phase 0 ----------------
+        if (WMODE == W_I4) __builtin_amdgcn_s_waitcnt(waitcnt_vm(2 * nX + nW));     // W(i+1) registers are here
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            read_x(1, st, 1, g); read_w(1, st, 1, g);
-            issue_one((kt + 3) & 3, t3, 4 + g);
+            if (MATH) { read_x(1, st, 1, g); read_w(1, st, 1, g); }
+            if (WMODE == W_I8) dma_w(i + 3, g);
+            if (WMODE == W_I4) convert_w(i + 1, g, S1{});
+            if (XMODE == X_FUSED && g >= 2) convert_x(i + 1, g, S1{});                    // second half of X(i+1)
+            if (MATH) {
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
-                acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[0][g], fx[0][b], acc[g][b], 0, 0, 0);
+                for (int b = 0; b < 4; ++b)
+                    acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[0][g], fx[0][b], acc[g][b], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
+        if (WMODE == W_I4) regload_w(i + 3, S0{});
         asm volatile("" ::: "memory");
-        // Substep-1 fragments are in registers, so this stage may be refilled after the barrier;
-        // tile kt+1 has landed for this wave (the 16 newer loads may still be in flight), so after
-        // the barrier it is complete for everyone.
-        __builtin_amdgcn_s_waitcnt(kWaitLgkm0 & waitcnt_vm(16));
+        // All LDS writes of this wave for tile i+1 are done, its last fragments of tile i are in
+        // registers (so stage i&3 may be refilled), and its direct loads of tile i+1 have landed;
+        // after the barrier tile i+1 is complete for everyone.
+        __builtin_amdgcn_s_waitcnt(kWaitLgkm0 & waitcnt_vm(2 * nX + 2 * nW));
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        // phase 1: MFMAs of substep 1; read substep 0 of the next tile; first half of tile kt+4
+        // ---------------- phase 1 ----------------
+        if (XMODE == X_FUSED) __builtin_amdgcn_s_waitcnt(waitcnt_vm(2 * nW + nX));  // X(i+2) registers are here
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            read_x(0, (kt + 1) & 3, 0, g); read_w(0, (kt + 1) & 3, 0, g);
-            issue_one(st, t4, g);
+            if (i + 1 >= 0) { read_x(0, (i + 1) & 3, 0, g); read_w(0, (i + 1) & 3, 0, g); }
+            if (XMODE == X_PREQ) dma_x(i + 4, g);
+            if (XMODE == X_FUSED && g < 2) convert_x(i + 2, g, S2{});                     // first half of X(i+2)
+            if (MATH) {
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
-                acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[1][g], fx[1][b], acc[g][b], 0, 0, 0);
+                for (int b = 0; b < 4; ++b)
+                    acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[1][g], fx[1][b], acc[g][b], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
+        if (XMODE == X_FUSED) regload_x(i + 4, S1{});
+    };
+    using R0 = std::integral_constant<int, 0>;
+    using R1 = std::integral_constant<int, 1>;
+    using R2 = std::integral_constant<int, 2>;
+    iteration(-4, std::false_type{}, R2{});
+    iteration(-3, std::false_type{}, R0{});
+    iteration(-2, std::false_type{}, R1{});
+    iteration(-1, std::false_type{}, R2{});
+    int it = 0;
+#pragma unroll 1
+    for (; it + 2 < KT; it += 3) {
+        iteration(it, std::true_type{}, R0{});
+        iteration(it + 1, std::true_type{}, R1{});
+        iteration(it + 2, std::true_type{}, R2{});
     }
-    // drain the clamped tail loads and the last fragment reads before LDS is reused
+    if (it < KT) iteration(it, std::true_type{}, R0{});
+    if (it + 1 < KT) iteration(it + 1, std::true_type{}, R1{});
+    // drain the tail loads and the last fragment reads before LDS is reused
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0 & waitcnt_vm(0));
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 
     // ---- epilogue: D[i][j], i = 8*(v/4) + 4*(lane/32) + v%4 -> n, j = lane%32 -> m ----
-    const float s = *s_ptr;
+    const float s = qk.s;
     const bool has_bias = bias != nullptr;
     char* epi = &lds[wave * kEpiBytes];
     const int wn0 = n0 + wn * 128, wm0 = m0 + wm * 128;
+    constexpr int kAccShift = WMODE == W_I4 ? 4 : 0;
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
 #pragma unroll
@@ -275,17 +391,18 @@ void linear_mfma_kernel(const int8_t* __restrict__ xq, const int8_t* __restrict_
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 const int ml = b * 32 + frow;
+                int av[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) av[e] = acc[a][b][4 * g + e] >> kAccShift;
                 u32x2 pk;
-                pk[0] = S::pack(dequant(acc[a][b][4 * g + 0], c[0], bz[0], has_bias),
-                                dequant(acc[a][b][4 * g + 1], c[1], bz[1], has_bias));
-                pk[1] = S::pack(dequant(acc[a][b][4 * g + 2], c[2], bz[2], has_bias),
-                                dequant(acc[a][b][4 * g + 3], c[3], bz[3], has_bias));
+                pk[0] = S::pack(dequant(av[0], c[0], bz[0], has_bias), dequant(av[1], c[1], bz[1], has_bias));
+                pk[1] = S::pack(dequant(av[2], c[2], bz[2], has_bias), dequant(av[3], c[3], bz[3], has_bias));
                 *reinterpret_cast<u32x2*>(epi + ml * kEpiStride + nl * 2) = pk;
                 if (acc_out) {
                     const int m = wm0 + ml, n = wn0 + nl;
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (m < M && n + e < N) acc_out[(int64_t)m * N + n + e] = acc[a][b][4 * g + e];
+                        if (m < M && n + e < N) acc_out[(int64_t)m * N + n + e] = av[e];
                 }
             }
         }
@@ -312,18 +429,80 @@ void linear_mfma_kernel(const int8_t* __restrict__ xq, const int8_t* __restrict_
     }
 }
 
-// W4 -> W8 unpack pre-pass (first version of the W4A8 path): natural K order, sign-extended.
-__global__ __launch_bounds__(256) void unpack_int4_kernel(const uint8_t* __restrict__ w4,
-                                                          int8_t* __restrict__ w8, int64_t nbytes)
+static size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Which activation path the MFMA kernel takes: 0 = by shape, 1 = separate quantize pass,
+// 2 = quantize-on-load.  Overridable with SASQ_STATIC_LINEAR_PATH=twopass|fused (tuning aid).
+static int path_override()
 {
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nbytes; i += (int64_t)gridDim.x * 256) {
-        int b = w4[i];
-        w8[2 * i] = (int8_t)(((b & 15) ^ 8) - 8);
-        w8[2 * i + 1] = (int8_t)(((b >> 4) ^ 8) - 8);
-    }
+    const char* e = getenv("SASQ_STATIC_LINEAR_PATH");
+    if (!e) return 0;
+    if (!strcmp(e, "twopass")) return 1;
+    if (!strcmp(e, "fused")) return 2;
+    return 0;
 }
 
-static size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+// Quantize-on-load re-quantizes each activation row once per column tile (about 3 VALU
+// operations per element on the SIMD that also issues the MFMAs) and doubles the A-side L2
+// traffic; the separate pass costs 3 bytes of HBM traffic per element once.  On MI355X the
+// separate pass measured faster at every workload shape, down to N = 1024 (4 column tiles:
+// 121 us against 150 us at M = K = 8192), so the shape rule currently never fuses; the fused
+// kernel stays selectable and is covered by the same parity tests.
+static bool choose_fused(int64_t M, int64_t N, int64_t K)
+{
+    (void)M; (void)K;
+    return N <= kFusedMaxN;
+}
+
+template <int DT, int XMODE, int WMODE>
+static void launch_mfma(const void* xin, const void* wq, const float* s, const float* s_w, const float* bias,
+                        void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K, int a_bits, hipStream_t st)
+{
+    const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (int)((N + kBN - 1) / kBN);
+    const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
+    linear_mfma_kernel<DT, XMODE, WMODE><<<grid, kGemmThreads, 0, st>>>(
+        xin, static_cast<const uint8_t*>(wq), s, s_w, bias, static_cast<uint16_t*>(y), acc_out,
+        (int)M, (int)N, (int)K, a_bits, tiles_m, tiles_n);
+}
+
+template <int DT>
+static void run_linear(const void* x, const float* s, const void* wq, const float* s_w, const float* bias,
+                       void* y, int32_t* acc_out, int8_t* xq_out, int64_t M, int64_t N, int64_t K, int a_bits,
+                       sasq_wfmt wf, int8_t* xq_ws, hipStream_t st)
+{
+    const int64_t n = M * K, nvec = n / 8;
+    int64_t qb = (nvec + 255) / 256;
+    const int qgrid = (int)(qb < 1 ? 1 : (qb > 65536 ? 65536 : qb));
+    auto X = static_cast<const u32x4*>(x);
+    if (xq_out) quantize_act_kernel<DT, false><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_out), nvec, n, a_bits);
+
+    const bool mfma_ok = (K % kBK) == 0;
+    const bool int4 = wf == SASQ_W_INT4_PACKED;
+    if (mfma_ok) {
+        const int ov = path_override();
+        const bool fused = ov == 2 || (ov == 0 && choose_fused(M, N, K));
+        if (fused) {
+            if (int4) launch_mfma<DT, X_FUSED, W_I4>(x, wq, s, s_w, bias, y, acc_out, M, N, K, a_bits, st);
+            else      launch_mfma<DT, X_FUSED, W_I8>(x, wq, s, s_w, bias, y, acc_out, M, N, K, a_bits, st);
+        } else {
+            // pass 1: quantize the activations once with the fixed scale (no reduction over X anywhere)
+            if (int4) {
+                quantize_act_kernel<DT, true><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_ws), nvec, n, a_bits);
+                launch_mfma<DT, X_PREQ, W_I4>(xq_ws, wq, s, s_w, bias, y, acc_out, M, N, K, a_bits, st);
+            } else {
+                quantize_act_kernel<DT, false><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_ws), nvec, n, a_bits);
+                launch_mfma<DT, X_PREQ, W_I8>(xq_ws, wq, s, s_w, bias, y, acc_out, M, N, K, a_bits, st);
+            }
+        }
+    } else {
+        quantize_act_kernel<DT, false><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_ws), nvec, n, a_bits);
+        const int64_t blocks = (M * N + 255) / 256;
+        auto W = static_cast<const uint8_t*>(wq);
+        auto Y = static_cast<uint16_t*>(y);
+        if (int4) linear_scalar_kernel<DT, true><<<(int)blocks, 256, 0, st>>>(xq_ws, W, s, s_w, bias, Y, acc_out, M, N, K);
+        else      linear_scalar_kernel<DT, false><<<(int)blocks, 256, 0, st>>>(xq_ws, W, s, s_w, bias, Y, acc_out, M, N, K);
+    }
+}
 
 }  // namespace sasq
 
@@ -331,10 +510,9 @@ using namespace sasq;
 
 extern "C" size_t sasq_static_linear_workspace(int64_t M, int64_t N, int64_t K, sasq_wfmt wf)
 {
-    if (M <= 0 || N <= 0 || K <= 0) return 0;
-    size_t bytes = round_up((size_t)M * (size_t)K, 256);              // quantized activations
-    if (wf == SASQ_W_INT4_PACKED) bytes += round_up((size_t)N * (size_t)K, 256);   // unpacked weights
-    return bytes;
+    (void)N; (void)wf;
+    if (M <= 0 || K <= 0) return 0;
+    return round_up((size_t)M * (size_t)K, 256);              // int8 activation codes of the two-pass path
 }
 
 extern "C" int sasq_static_linear(const void* x, const float* s, const void* wq, const float* s_w,
@@ -350,6 +528,7 @@ extern "C" int sasq_static_linear(const void* x, const float* s, const void* wq,
     if (wf != SASQ_W_INT8 && wf != SASQ_W_INT4_PACKED) return SASQ_ERR_UNSUPPORTED;
     if (dt != SASQ_F16 && dt != SASQ_BF16) return SASQ_ERR_UNSUPPORTED;
     if (wf == SASQ_W_INT4_PACKED && (K & 1)) return SASQ_ERR_SHAPE;
+    if ((M * N + 255) / 256 > 0x7FFFFFFF) return SASQ_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(wq) || !aligned16(y) || (acc_out && !aligned16(acc_out)) ||
         (xq_out && (reinterpret_cast<uintptr_t>(xq_out) & 7u))) return SASQ_ERR_ALIGN;
     const size_t need = sasq_static_linear_workspace(M, N, K, wf);
@@ -358,50 +537,7 @@ extern "C" int sasq_static_linear(const void* x, const float* s, const void* wq,
 
     hipStream_t st = as_stream(stream);
     int8_t* xq_ws = static_cast<int8_t*>(workspace);
-    int8_t* w8_ws = xq_ws + round_up((size_t)M * (size_t)K, 256);
-
-    // pass 1: quantize the activations with the fixed scale (no reduction over X anywhere)
-    const int64_t n = M * K, nvec = n / 8;
-    int64_t qb = (nvec + 255) / 256;
-    const int qgrid = (int)(qb < 1 ? 1 : (qb > 65536 ? 65536 : qb));
-    auto X = static_cast<const u32x4*>(x);
-    if (dt == SASQ_F16) quantize_act_kernel<SASQ_F16, false><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_ws), nvec, n, a_bits);
-    else                quantize_act_kernel<SASQ_BF16, false><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_ws), nvec, n, a_bits);
-    if (xq_out) {
-        if (dt == SASQ_F16) quantize_act_kernel<SASQ_F16, false><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_out), nvec, n, a_bits);
-        else                quantize_act_kernel<SASQ_BF16, false><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_out), nvec, n, a_bits);
-    }
-
-    const int8_t* w8 = static_cast<const int8_t*>(wq);
-    const bool mfma_ok = (K % kBK) == 0 && K >= kBK;
-    if (wf == SASQ_W_INT4_PACKED && mfma_ok) {
-        const int64_t nb = N * (K / 2);
-        int64_t ub = (nb + 255) / 256;
-        unpack_int4_kernel<<<(int)(ub > 65536 ? 65536 : ub), 256, 0, st>>>(static_cast<const uint8_t*>(wq), w8_ws, nb);
-        w8 = w8_ws;
-    }
-
-    if (mfma_ok) {
-        const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (int)((N + kBN - 1) / kBN);
-        const int total = tiles_m * tiles_n;
-        const int grid = ((total + 7) / 8) * 8;
-        if (dt == SASQ_F16)
-            linear_mfma_kernel<SASQ_F16><<<grid, kGemmThreads, 0, st>>>(xq_ws, w8, s, s_w, bias, static_cast<uint16_t*>(y), acc_out, (int)M, (int)N, (int)K, tiles_m, tiles_n);
-        else
-            linear_mfma_kernel<SASQ_BF16><<<grid, kGemmThreads, 0, st>>>(xq_ws, w8, s, s_w, bias, static_cast<uint16_t*>(y), acc_out, (int)M, (int)N, (int)K, tiles_m, tiles_n);
-    } else {
-        const int64_t total = M * N;
-        const int64_t blocks = (total + 255) / 256;
-        if (blocks > 0x7FFFFFFF) return SASQ_ERR_SHAPE;
-        auto W = static_cast<const uint8_t*>(wq);
-        auto Y = static_cast<uint16_t*>(y);
-        if (dt == SASQ_F16) {
-            if (wf == SASQ_W_INT8) linear_scalar_kernel<SASQ_F16, false><<<(int)blocks, 256, 0, st>>>(xq_ws, W, s, s_w, bias, Y, acc_out, M, N, K);
-            else                   linear_scalar_kernel<SASQ_F16, true><<<(int)blocks, 256, 0, st>>>(xq_ws, W, s, s_w, bias, Y, acc_out, M, N, K);
-        } else {
-            if (wf == SASQ_W_INT8) linear_scalar_kernel<SASQ_BF16, false><<<(int)blocks, 256, 0, st>>>(xq_ws, W, s, s_w, bias, Y, acc_out, M, N, K);
-            else                   linear_scalar_kernel<SASQ_BF16, true><<<(int)blocks, 256, 0, st>>>(xq_ws, W, s, s_w, bias, Y, acc_out, M, N, K);
-        }
-    }
+    if (dt == SASQ_F16) run_linear<SASQ_F16>(x, s, wq, s_w, bias, y, acc_out, xq_out, M, N, K, a_bits, wf, xq_ws, st);
+    else                run_linear<SASQ_BF16>(x, s, wq, s_w, bias, y, acc_out, xq_out, M, N, K, a_bits, wf, xq_ws, st);
     return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
 }

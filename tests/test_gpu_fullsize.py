@@ -9,6 +9,7 @@ sampled channel, always including the first/last row and column and tile-edge ne
 from __future__ import annotations
 
 import functools
+import os
 
 import numpy as np
 import pytest
@@ -108,8 +109,17 @@ def test_static_linear_full_size(cfg_name, proj_name, ws):
     sd = dev_scalar(s)
     y = torch.empty((M, N), dtype=TDT[dtype], device="cuda")
     wsl = B.new_workspace(B.sasq_static_linear_workspace(M, N, K, wf))
+    os.environ.pop("SASQ_STATIC_LINEAR_PATH", None)
     B.sasq_static_linear(x, sd, wq, s_w, None, y, wf, wsl)            # the timed configuration
     torch.cuda.synchronize()
+    for path in ("twopass", "fused"):                                 # both activation paths agree bit for bit
+        os.environ["SASQ_STATIC_LINEAR_PATH"] = path
+        y_alt = torch.empty_like(y)
+        B.sasq_static_linear(x, sd, wq, s_w, None, y_alt, wf, wsl)
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), y_alt.view(torch.int16)), path
+    os.environ.pop("SASQ_STATIC_LINEAR_PATH", None)
+    del y_alt
     acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
     xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
     y_dbg = torch.empty_like(y)

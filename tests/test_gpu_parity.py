@@ -6,6 +6,8 @@ within 1e-3 relative (asserted equal by value, which is stricter); ds within 1e-
 """
 from __future__ import annotations
 
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -166,7 +168,13 @@ def test_quantize_weight(fmt, shape):
 
 
 # ---------------------------------------------------------------- static linear
-def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True):
+def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True, path=None):
+    """path: None (library's choice by shape), "twopass" or "fused" (activation quantize in a
+    separate pass / on load inside the GEMM)."""
+    if path is None:
+        os.environ.pop("SASQ_STATIC_LINEAR_PATH", None)
+    else:
+        os.environ["SASQ_STATIC_LINEAR_PATH"] = path
     M, K = xb.shape
     N = wq.shape[0]
     wf = B.SASQ_W_INT8 if fmt == "int8" else B.SASQ_W_INT4_PACKED
@@ -178,6 +186,7 @@ def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True):
     B.sasq_static_linear(x, dev_scalar(s), torch.from_numpy(wq).cuda(), torch.from_numpy(s_w).cuda(),
                          None if bias is None else torch.from_numpy(bias).cuda(), y, wf, wsl, acc, xq)
     torch.cuda.synchronize()
+    os.environ.pop("SASQ_STATIC_LINEAR_PATH", None)
     return to_bits(y), (acc.cpu().numpy() if want_debug else None), (xq.cpu().numpy() if want_debug else None)
 
 
@@ -185,13 +194,14 @@ LINEAR_SHAPES = [
     (1, 1, 2), (3, 5, 8), (19, 23, 70),              # scalar path: K not a multiple of 128
     (64, 256, 256),                                   # config 1
     (1, 1, 128), (33, 47, 128), (256, 256, 128),      # MFMA path: single K step, ragged / exact tile
-    (300, 520, 384), (257, 255, 1024), (512, 768, 512),
+    (300, 520, 384), (257, 255, 1024), (512, 768, 512), (40, 300, 64), (260, 70, 192),
 ]
 
 
+@pytest.mark.parametrize("path", ["twopass", "fused"])
 @pytest.mark.parametrize("dtype,fmt", [("f16", "int8"), ("bf16", "int8"), ("bf16", "int4"), ("f16", "int4")])
 @pytest.mark.parametrize("shape", LINEAR_SHAPES)
-def test_static_linear(shape, dtype, fmt):
+def test_static_linear(shape, dtype, fmt, path):
     M, N, K = shape
     xb = wl.random_bits(12, f"lx{shape}{dtype}", (M, K), dtype, gain=2.0)
     w = wl.random_f32(12, f"lw{shape}", (N, K), 0.02)
@@ -200,11 +210,11 @@ def test_static_linear(shape, dtype, fmt):
     s = np.float32(oracle.absmax_scale(xb, 8, dtype) / 3)
     for b in (None, bias):
         ref = oracle.static_linear(xb, s, wq, s_w, b, 8, fmt, dtype)
-        y, acc, xq = run_linear(xb, s, wq, s_w, b, fmt, dtype)
+        y, acc, xq = run_linear(xb, s, wq, s_w, b, fmt, dtype, path=path)
         assert np.array_equal(xq, ref["xq"]), "activation codes"
         assert np.array_equal(acc, ref["acc"]), "int32 accumulators"
         assert_same_values(y, ref["y"], dtype, "Y")
-        y2, _, _ = run_linear(xb, s, wq, s_w, b, fmt, dtype, want_debug=False)
+        y2, _, _ = run_linear(xb, s, wq, s_w, b, fmt, dtype, want_debug=False, path=path)
         assert np.array_equal(y2, y)
 
 
@@ -216,10 +226,19 @@ def test_static_linear_extreme_codes():
     xb = wl.f32_to_storage_bits(xv, "bf16")
     wq = np.stack([np.full(K, -128), np.full(K, 127), np.full(K, -127), np.where(np.arange(K) % 2, 127, -128)]).astype(np.int8)
     ref = oracle.static_linear(xb, np.float32(1.0), wq, np.ones(4, np.float32), None, 8, "int8", "bf16")
-    y, acc, xq = run_linear(xb, np.float32(1.0), wq, np.ones(4, np.float32), None, "int8", "bf16")
     assert ref["acc"][0, 0] == 128 * 128 * K
-    assert np.array_equal(acc, ref["acc"]) and np.array_equal(xq, ref["xq"])
-    assert_same_values(y, ref["y"], "bf16", "Y")
+    for path in ("twopass", "fused"):
+        y, acc, xq = run_linear(xb, np.float32(1.0), wq, np.ones(4, np.float32), None, "int8", "bf16", path=path)
+        assert np.array_equal(acc, ref["acc"]) and np.array_equal(xq, ref["xq"])
+        assert_same_values(y, ref["y"], "bf16", "Y")
+    # int4 weights at their extremes (-8 and 7): the x16 in-register form must not overflow either
+    w4 = np.stack([np.full(K // 2, 0x88), np.full(K // 2, 0x77), np.full(K // 2, 0x78)]).astype(np.uint8)
+    ref4 = oracle.static_linear(xb, np.float32(1.0), w4, np.ones(3, np.float32), None, 8, "int4", "bf16")
+    assert ref4["acc"][0, 0] == 128 * 8 * K
+    for path in ("twopass", "fused"):
+        y, acc, xq = run_linear(xb, np.float32(1.0), w4, np.ones(3, np.float32), None, "int4", "bf16", path=path)
+        assert np.array_equal(acc, ref4["acc"])
+        assert_same_values(y, ref4["y"], "bf16", "Y int4")
 
 
 def test_cross_export_identity():
