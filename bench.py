@@ -31,6 +31,10 @@ from paper_2512_14481_amd import binding as B          # noqa: E402
 from paper_2512_14481_amd import workloads as wl       # noqa: E402
 
 INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8, published
+# HBM-side bytes per sasq_static_linear call (both kernels), averaged over gate/up/down of config 3:
+# rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a plain 1 GiB copy), see
+# profiles/bench_c3_mlp7b_counters.txt.  Algorithmic bytes are 221.2 MB.
+C3_LINEAR_TRAFFIC_BYTES = 449754 * 1024
 HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published
 LR = 2e-4
 TDT = {"f16": torch.float16, "bf16": torch.bfloat16}
@@ -115,6 +119,8 @@ def main():
     ap.add_argument("--config", default="c3_mlp7b")
     ap.add_argument("--cpu-rows", type=int, default=4096)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calib", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build is single-GPU; --gpus must be 1 (how the path would shard over "
@@ -128,6 +134,12 @@ def main():
     projs = [Projection(cfg, p, acts[p.x], ws_small) for p in cfg.projs]
     torch.cuda.synchronize()
 
+    if a.calib:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                 # 1 GiB read + 1 GiB written by a plain copy kernel
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(a.warmup):
         step(projs, ws_small)
     for p in projs:                                   # every timed run starts from the same scales
@@ -171,7 +183,11 @@ def main():
                    if cfg.name == "c3_mlp7b" else cfg.name},
         "roofline": {"bound": "mfma", "kernel": "sasq_static_linear (activation quantize + int8 MFMA GEMM + dequant)",
                      "achieved": round(lin_tops, 1), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": round(lin_tops / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
+                     "frac": round(lin_tops / INT8_MFMA_PEAK_TOPS, 4),
+                     "traffic": C3_LINEAR_TRAFFIC_BYTES if cfg.name == "c3_mlp7b" else None,
+                     "traffic_unit": "bytes per call (rocprofv3 FETCH_SIZE/WRITE_SIZE, copy-calibrated)",
+                     "algorithmic_bytes": int(sum(3 * p.M * p.K + p.M * p.K + p.N * p.K + 2 * p.M * p.N + 4 * p.N
+                                                  for p in projs) / len(projs)),
                      "avg_launch_us": round(lin_avg_ms * 1e3, 2)},
         "fakequant": {"bound": "hbm", "achieved": round(fq_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                       "frac": round(fq_gbps / HBM_PEAK_GBPS, 4),
