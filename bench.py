@@ -186,7 +186,7 @@ def main():
                      "frac": round(lin_tops / INT8_MFMA_PEAK_TOPS, 4),
                      "traffic": C3_LINEAR_TRAFFIC_BYTES if cfg.name == "c3_mlp7b" else None,
                      "traffic_unit": "bytes per call (rocprofv3 FETCH_SIZE/WRITE_SIZE, copy-calibrated)",
-                     "algorithmic_bytes": int(sum(3 * p.M * p.K + p.M * p.K + p.N * p.K + 2 * p.M * p.N + 4 * p.N
+                     "algorithmic_bytes": int(sum(3 * p.M * p.K + p.M * p.K + p.wq.numel() + 2 * p.M * p.N + 4 * p.N
                                                   for p in projs) / len(projs)),
                      "avg_launch_us": round(lin_avg_ms * 1e3, 2)},
         "fakequant": {"bound": "hbm", "achieved": round(fq_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",

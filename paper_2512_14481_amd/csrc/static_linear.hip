@@ -314,15 +314,21 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
         if (WMODE == W_I4) __builtin_amdgcn_s_waitcnt(waitcnt_vm(2 * nX + nW));     // W(i+1) registers are here
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            if (MATH) { read_x(1, st, 1, g); read_w(1, st, 1, g); }
-            if (WMODE == W_I8) dma_w(i + 3, g);
-            if (WMODE == W_I4) convert_w(i + 1, g, S1{});
-            if (XMODE == X_FUSED && g >= 2) convert_x(i + 1, g, S1{});                    // second half of X(i+1)
+            // MFMAs first: their fragments were read a phase ago, so the wait in front of them
+            // never includes the reads issued in this group.  The next substep's activation
+            // fragments are read in groups 0-1 and its weight fragments in groups 2-3, which is
+            // the order in which the next phase consumes them.
             if (MATH) {
 #pragma unroll
                 for (int b = 0; b < 4; ++b)
                     acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[0][g], fx[0][b], acc[g][b], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (g < 2) { read_x(1, st, 1, 2 * g); read_x(1, st, 1, 2 * g + 1); }
+                else       { read_w(1, st, 1, 2 * g - 4); read_w(1, st, 1, 2 * g - 3); }
             }
+            if (WMODE == W_I8) dma_w(i + 3, g);
+            if (WMODE == W_I4) convert_w(i + 1, g, S1{});
+            if (XMODE == X_FUSED && g >= 2) convert_x(i + 1, g, S1{});                    // second half of X(i+1)
             __builtin_amdgcn_sched_barrier(0);
         }
         if (WMODE == W_I4) regload_w(i + 3, S0{});
@@ -337,14 +343,18 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
         if (XMODE == X_FUSED) __builtin_amdgcn_s_waitcnt(waitcnt_vm(2 * nW + nX));  // X(i+2) registers are here
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            if (i + 1 >= 0) { read_x(0, (i + 1) & 3, 0, g); read_w(0, (i + 1) & 3, 0, g); }
-            if (XMODE == X_PREQ) dma_x(i + 4, g);
-            if (XMODE == X_FUSED && g < 2) convert_x(i + 2, g, S2{});                     // first half of X(i+2)
             if (MATH) {
 #pragma unroll
                 for (int b = 0; b < 4; ++b)
                     acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[1][g], fx[1][b], acc[g][b], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
+            if (i + 1 >= 0) {
+                if (g < 2) { read_x(0, (i + 1) & 3, 0, 2 * g); read_x(0, (i + 1) & 3, 0, 2 * g + 1); }
+                else       { read_w(0, (i + 1) & 3, 0, 2 * g - 4); read_w(0, (i + 1) & 3, 0, 2 * g - 3); }
+            }
+            if (XMODE == X_PREQ) dma_x(i + 4, g);
+            if (XMODE == X_FUSED && g < 2) convert_x(i + 2, g, S2{});                     // first half of X(i+2)
             __builtin_amdgcn_sched_barrier(0);
         }
         if (XMODE == X_FUSED) regload_x(i + 4, S1{});
