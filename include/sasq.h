@@ -64,8 +64,9 @@ const char* sasq_status_string(int status);
 int sasq_version(void);
 
 /*
- * Prepare a workspace for use by the calls below (zero-fills its control words on `stream`).
- * Call once per workspace allocation, before the first call that uses it.
+ * Prepare a workspace for use by the calls below (zero-fills its control words, the first
+ * 1024 bytes or the whole workspace if smaller, on `stream`).  Call once per workspace
+ * allocation, before the first call that uses it.  Minimum size 256 bytes.
  */
 int sasq_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 
@@ -102,6 +103,24 @@ size_t sasq_fakequant_bwd_workspace(int64_t rows, int64_t cols);
 int sasq_fakequant_bwd(const void* x, const void* dy, const float* s, void* dx, float* ds,
                        int64_t rows, int64_t cols, int bits, sasq_dtype dt,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Per-channel variants of the fake-quant operator: one learned factor per activation channel
+ * (column), the granularity of the paper's main experiments (Sec. 4; Sec. 5.1 "Implementation";
+ * Sec. 2, Fig. 2(b)).  Same element arithmetic as above with s = s[k] for column k;
+ *     ds[k] = sum over rows m of dy[m,k] * (q[m,k] - m[m,k] * x[m,k]/s[k])   (overwritten).
+ *   s, ds   [cols] device fp32
+ *   cols    at most 130560; the 128-bit path needs cols % 8 == 0, other widths take a slow
+ *           one-thread-per-column kernel (and then need no workspace)
+ * The per-channel backward uses one ticket per 512-column chunk of its workspace header; the
+ * same workspace must not be shared with an overlapping call of any other entry point.
+ */
+int sasq_fakequant_fwd_pc(const void* x, const float* s, void* y, int8_t* codes,
+                          int64_t rows, int64_t cols, int bits, sasq_dtype dt, void* stream);
+size_t sasq_fakequant_bwd_pc_workspace(int64_t rows, int64_t cols);
+int sasq_fakequant_bwd_pc(const void* x, const void* dy, const float* s, void* dx, float* ds,
+                          int64_t rows, int64_t cols, int bits, sasq_dtype dt,
+                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * One plain SGD step on the scale (the optimiser state of SASQ is the scale alone, Sec. 4.2;

@@ -174,3 +174,33 @@ def absmax_scale(x: np.ndarray, bits: int, dtype: str) -> np.float32:
 def scale_sgd(s: float, ds: float, lr: float) -> np.float32:
     return np.float32(lib().sasq_oracle_scale_sgd(ctypes.c_float(float(s)), ctypes.c_float(float(ds)),
                                                   ctypes.c_float(float(lr))))
+
+
+def fakequant_fwd_pc(x: np.ndarray, s: np.ndarray, bits: int, dtype: str) -> Tuple[np.ndarray, np.ndarray]:
+    """Per-channel forward: s has one fp32 factor per column of x [rows, cols]."""
+    x = _u16(x)
+    rows, cols = x.shape
+    s = np.ascontiguousarray(s, dtype=np.float32)
+    assert s.shape == (cols,)
+    y = np.empty(x.shape, dtype=np.uint16)
+    codes = np.empty(x.shape, dtype=np.int8)
+    rc = lib().sasq_oracle_fakequant_fwd_pc(_p(x), _p(s), _p(y), _p(codes), ctypes.c_int64(rows),
+                                            ctypes.c_int64(cols), int(bits), DT[dtype])
+    _check(rc, "fakequant_fwd_pc")
+    return y, codes
+
+
+def fakequant_bwd_pc(x: np.ndarray, dy: np.ndarray, s: np.ndarray, bits: int, dtype: str):
+    """Per-channel backward: dict(dx=uint16 bits, ds=float32 [cols], ds64=float64 [cols], sum_abs=float64 [cols])."""
+    x, dy = _u16(x), _u16(dy)
+    rows, cols = x.shape
+    s = np.ascontiguousarray(s, dtype=np.float32)
+    assert s.shape == (cols,) and dy.shape == x.shape
+    dx = np.empty(x.shape, dtype=np.uint16)
+    ds = np.empty(cols, dtype=np.float32)
+    ds64 = np.empty(cols, dtype=np.float64)
+    sabs = np.empty(cols, dtype=np.float64)
+    rc = lib().sasq_oracle_fakequant_bwd_pc(_p(x), _p(dy), _p(s), _p(dx), _p(ds), _p(ds64), _p(sabs),
+                                            ctypes.c_int64(rows), ctypes.c_int64(cols), int(bits), DT[dtype])
+    _check(rc, "fakequant_bwd_pc")
+    return {"dx": dx, "ds": ds, "ds64": ds64, "sum_abs": sabs}

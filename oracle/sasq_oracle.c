@@ -354,3 +354,57 @@ float sasq_oracle_scale_sgd(float s, float ds, float lr)
     volatile float out = s - step;
     return out;
 }
+
+/*
+ * Per-channel variants: one factor per activation column (Sec. 4: per-channel quantization for
+ * activations; Sec. 2, Fig. 2(b): the elements of a column share a factor).  Element arithmetic
+ * as above with s = s[k] for column k; the scale gradient is a sum over the rows of each column.
+ */
+int sasq_oracle_fakequant_fwd_pc(const uint16_t* x, const float* s, uint16_t* y, int8_t* codes,
+                                 int64_t rows, int64_t cols, int bits, int dt)
+{
+    int rc = check_common(bits, dt);
+    if (rc) return rc;
+    const int Qn = -(1 << (bits - 1)), Qp = (1 << (bits - 1)) - 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < cols; ++k) {
+        const float sk = s[k];
+        const float inv_s = reciprocal_f32(sk);
+        for (int64_t m = 0; m < rows; ++m) {
+            int64_t idx = m * cols + k;
+            qelem e = quantize_one(load16(x, idx, dt), inv_s, Qn, Qp, 0);
+            volatile float qf = (float)e.q;
+            volatile float yf = qf * sk;
+            if (y) y[idx] = store16(yf, dt);
+            if (codes) codes[idx] = (int8_t)e.q;
+        }
+    }
+    return OK;
+}
+
+int sasq_oracle_fakequant_bwd_pc(const uint16_t* x, const uint16_t* dy, const float* s, uint16_t* dx,
+                                 float* ds, double* ds64, double* sum_abs,
+                                 int64_t rows, int64_t cols, int bits, int dt)
+{
+    int rc = check_common(bits, dt);
+    if (rc) return rc;
+    const int Qn = -(1 << (bits - 1)), Qp = (1 << (bits - 1)) - 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < cols; ++k) {
+        const float inv_s = reciprocal_f32(s[k]);
+        double acc = 0.0, aabs = 0.0;
+        for (int64_t m = 0; m < rows; ++m) {
+            int64_t idx = m * cols + k;
+            qelem e = quantize_one(load16(x, idx, dt), inv_s, Qn, Qp, 0);
+            double g = load16(dy, idx, dt);
+            if (dx) dx[idx] = e.m ? dy[idx] : (uint16_t)0;
+            double t = e.m ? g * (e.q - e.p) : g * e.q;
+            acc += t;
+            aabs += fabs(t);
+        }
+        if (ds) ds[k] = (float)acc;
+        if (ds64) ds64[k] = acc;
+        if (sum_abs) sum_abs[k] = aabs;
+    }
+    return OK;
+}

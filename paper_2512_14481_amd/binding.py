@@ -49,6 +49,10 @@ def _lib() -> ctypes.CDLL:
         L.sasq_fakequant_bwd_workspace.argtypes = [i64, i64]
         L.sasq_fakequant_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, sz, vp]
         L.sasq_scale_sgd.argtypes = [vp, vp, f32, vp]
+        L.sasq_fakequant_fwd_pc.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp]
+        L.sasq_fakequant_bwd_pc_workspace.restype = sz
+        L.sasq_fakequant_bwd_pc_workspace.argtypes = [i64, i64]
+        L.sasq_fakequant_bwd_pc.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, sz, vp]
         L.sasq_static_linear_workspace.restype = sz
         L.sasq_static_linear_workspace.argtypes = [i64, i64, i64, i32]
         L.sasq_static_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, sz, vp]
@@ -129,6 +133,33 @@ def sasq_fakequant_bwd(x: torch.Tensor, dy: torch.Tensor, s: torch.Tensor, dx: O
     _check(_lib().sasq_fakequant_bwd(_ptr(x), _ptr(dy), _ptr(s), _ptr(dx), _ptr(ds), rows, cols, bits, _dt(x),
                                      _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
            "sasq_fakequant_bwd")
+
+
+def sasq_fakequant_fwd_pc(x: torch.Tensor, s: torch.Tensor, y: torch.Tensor,
+                          codes: Optional[torch.Tensor] = None, bits: int = 8) -> None:
+    _want(s, torch.float32, "s"); _want(codes, torch.int8, "codes")
+    rows, cols = x.shape
+    if y.dtype != x.dtype or y.shape != x.shape or s.numel() != cols:
+        raise ValueError("y must match x and s must have one element per column")
+    _check(_lib().sasq_fakequant_fwd_pc(_ptr(x), _ptr(s), _ptr(y), _ptr(codes), rows, cols, bits, _dt(x), _stream()),
+           "sasq_fakequant_fwd_pc")
+
+
+def sasq_fakequant_bwd_pc_workspace(rows: int, cols: int) -> int:
+    return int(_lib().sasq_fakequant_bwd_pc_workspace(rows, cols))
+
+
+def sasq_fakequant_bwd_pc(x: torch.Tensor, dy: torch.Tensor, s: torch.Tensor, dx: Optional[torch.Tensor],
+                          ds: torch.Tensor, workspace: Optional[torch.Tensor], bits: int = 8) -> None:
+    _want(s, torch.float32, "s"); _want(ds, torch.float32, "ds")
+    rows, cols = x.shape
+    if dy.dtype != x.dtype or dy.shape != x.shape or (dx is not None and (dx.dtype != x.dtype or dx.shape != x.shape)):
+        raise ValueError("dy and dx must match x")
+    if s.numel() != cols or ds.numel() != cols:
+        raise ValueError("s and ds must have one element per column")
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib().sasq_fakequant_bwd_pc(_ptr(x), _ptr(dy), _ptr(s), _ptr(dx), _ptr(ds), rows, cols, bits, _dt(x),
+                                        _ptr(workspace), wsb, _stream()), "sasq_fakequant_bwd_pc")
 
 
 def sasq_scale_sgd(s: torch.Tensor, ds: torch.Tensor, lr: float) -> None:

@@ -1,0 +1,305 @@
+// Per-channel fake quantization: one learned factor per activation column (Sec. 4 "we use
+// per-channel quantization for both activation and weight"; Sec. 2, Fig. 2(b): per-channel = the
+// elements of a column share a factor).  Same element arithmetic as the per-tensor operator
+// (Sec. 3, Eq. 1; Sec. 4.2, Eq. 4); the scale gradient becomes a column reduction:
+//     ds[k] = sum_m dy[m,k] * (q[m,k] - m[m,k] * x[m,k]/s[k]).
+//
+// Traversal: a lane owns 8 consecutive columns (one 128-bit access) for the whole kernel, so its
+// eight scales and reciprocals live in registers; a wave covers 512 consecutive columns of one
+// row (1 KB, fully coalesced); the 4 waves of a block take rows r, r+1, r+2, r+3 of the block's
+// row chunk.  Grid = column chunks x row chunks.
+#include "sasq_device.h"
+
+namespace sasq {
+
+constexpr int kPcThreads = 256;
+constexpr int kPcWaves = kPcThreads / kWave;
+constexpr int kPcColsPerBlock = kWave * 8;        // 512
+constexpr int kPcRowUnroll = 4;                   // rows in flight per wave
+constexpr int kPcMaxRowChunks = 64;
+
+struct PcConst {
+    float inv_s[8];
+    float s[8];
+    float lo, hi;
+};
+
+__device__ __forceinline__ PcConst load_pc(const float* __restrict__ s, int64_t col0, int64_t cols, int bits)
+{
+    PcConst c;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float v = s[col0 + e < cols ? col0 + e : cols - 1];
+        c.s[e] = v;
+        c.inv_s[e] = 1.0f / v;
+    }
+    c.lo = kMagic - (float)(1 << (bits - 1));
+    c.hi = kMagic + (float)((1 << (bits - 1)) - 1);
+    return c;
+}
+
+__device__ __forceinline__ QElem quantize_pc(float x, float inv_s, const PcConst& c)
+{
+    QElem e;
+    e.f = __builtin_fmaf(x, inv_s, kMagic);
+    e.c = __builtin_amdgcn_fmed3f(e.f, c.lo, c.hi);
+    return e;
+}
+
+template <int DT, bool CODES>
+__global__ __launch_bounds__(kPcThreads) void fakequant_fwd_pc_kernel(
+    const uint16_t* __restrict__ x, const float* __restrict__ s, uint16_t* __restrict__ y,
+    int8_t* __restrict__ codes, int64_t rows, int64_t cols, int64_t rows_per_chunk, int bits)
+{
+    using S = Store16<DT>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t col0 = (int64_t)blockIdx.x * kPcColsPerBlock + lane * 8;
+    if (col0 >= cols) return;
+    const PcConst c = load_pc(s, col0, cols, bits);
+    const int64_t r_begin = (int64_t)blockIdx.y * rows_per_chunk;
+    const int64_t r_end = min(rows, r_begin + rows_per_chunk);
+    for (int64_t r = r_begin + wave; r < r_end; r += kPcWaves * kPcRowUnroll) {
+        u32x4 in[kPcRowUnroll];
+#pragma unroll
+        for (int u = 0; u < kPcRowUnroll; ++u) {
+            const int64_t rr = min(r + u * kPcWaves, r_end - 1);
+            in[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + rr * cols + col0));
+        }
+#pragma unroll
+        for (int u = 0; u < kPcRowUnroll; ++u) {
+            const int64_t rr = r + u * kPcWaves;
+            if (rr >= r_end) break;
+            u32x4 out;
+            float cc[8];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                QElem a = quantize_pc(S::lo(in[u][w]), c.inv_s[2 * w], c);
+                QElem b = quantize_pc(S::hi(in[u][w]), c.inv_s[2 * w + 1], c);
+                out[w] = S::pack(codef_of(a) * c.s[2 * w], codef_of(b) * c.s[2 * w + 1]);
+                cc[2 * w] = a.c;
+                cc[2 * w + 1] = b.c;
+            }
+            __builtin_nontemporal_store(out, reinterpret_cast<u32x4*>(y + rr * cols + col0));
+            if (CODES) {
+                u32x2 cw = {pack_codes4(cc[0], cc[1], cc[2], cc[3]), pack_codes4(cc[4], cc[5], cc[6], cc[7])};
+                *reinterpret_cast<u32x2*>(codes + rr * cols + col0) = cw;
+            }
+        }
+    }
+}
+
+template <int DT, bool WRITE_DX>
+__global__ __launch_bounds__(kPcThreads) void fakequant_bwd_pc_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* dy, const float* __restrict__ s,
+    uint16_t* dx, float* __restrict__ ds, uint32_t* __restrict__ tickets, float* __restrict__ partials,
+    int64_t rows, int64_t cols, int64_t rows_per_chunk, int bits)
+{
+    using S = Store16<DT>;
+    __shared__ float red[kPcWaves][kPcColsPerBlock];
+    __shared__ bool is_last;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t cbase = (int64_t)blockIdx.x * kPcColsPerBlock;
+    const int64_t col0 = cbase + lane * 8;
+    const bool active = col0 < cols;
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (active) {
+        const PcConst c = load_pc(s, col0, cols, bits);
+        const int64_t r_begin = (int64_t)blockIdx.y * rows_per_chunk;
+        const int64_t r_end = min(rows, r_begin + rows_per_chunk);
+        for (int64_t r = r_begin + wave; r < r_end; r += kPcWaves * kPcRowUnroll) {
+            u32x4 xin[kPcRowUnroll], gin[kPcRowUnroll];
+#pragma unroll
+            for (int u = 0; u < kPcRowUnroll; ++u) {
+                const int64_t rr = min(r + u * kPcWaves, r_end - 1);
+                xin[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + rr * cols + col0));
+                gin[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(dy + rr * cols + col0));
+            }
+#pragma unroll
+            for (int u = 0; u < kPcRowUnroll; ++u) {
+                const int64_t rr = r + u * kPcWaves;
+                if (rr >= r_end) break;
+                u32x4 out;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const float xa = S::lo(xin[u][w]), xb = S::hi(xin[u][w]);
+                    QElem a = quantize_pc(xa, c.inv_s[2 * w], c);
+                    QElem b = quantize_pc(xb, c.inv_s[2 * w + 1], c);
+                    const bool ka = unclipped(a), kb = unclipped(b);
+                    const float qa = codef_of(a), qb = codef_of(b);
+                    const float ua = __builtin_fmaf(-xa, c.inv_s[2 * w], qa), ub = __builtin_fmaf(-xb, c.inv_s[2 * w + 1], qb);
+                    acc[2 * w] += S::lo(gin[u][w]) * (ka ? ua : qa);
+                    acc[2 * w + 1] += S::hi(gin[u][w]) * (kb ? ub : qb);
+                    out[w] = gin[u][w] & ((ka ? 0x0000FFFFu : 0u) | (kb ? 0xFFFF0000u : 0u));
+                }
+                if (WRITE_DX) __builtin_nontemporal_store(out, reinterpret_cast<u32x4*>(dx + rr * cols + col0));
+            }
+        }
+    }
+    // block partial per column: waves in fixed order
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[wave][lane * 8 + e] = acc[e];
+    __syncthreads();
+    const int nchunks = gridDim.y;
+    for (int cidx = threadIdx.x; cidx < kPcColsPerBlock; cidx += kPcThreads) {
+        float v = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kPcWaves; ++w) v += red[w][cidx];
+        if (cbase + cidx < cols)
+            __hip_atomic_store(&partials[(int64_t)blockIdx.y * cols + cbase + cidx], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // the stores above are agent-scope and acknowledged before the ticket is taken
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t ticket = __hip_atomic_fetch_add(&tickets[blockIdx.x], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        is_last = (ticket == (uint32_t)nchunks - 1);
+        if (ticket >= (uint32_t)nchunks) ds[cbase < cols ? cbase : 0] = __uint_as_float(0x7FC00000u);   // uninitialised workspace
+    }
+    __syncthreads();
+    if (!is_last) return;
+    // last block of this column chunk: row chunks summed in order, in fp64
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    for (int cidx = threadIdx.x; cidx < kPcColsPerBlock; cidx += kPcThreads) {
+        if (cbase + cidx >= cols) continue;
+        double t = 0.0;
+        for (int rc0 = 0; rc0 < nchunks; rc0 += 8) {
+            float pv[8];        // eight loads in flight, then added in row-chunk order
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int rc = rc0 + j < nchunks ? rc0 + j : nchunks - 1;
+                pv[j] = __hip_atomic_load(&partials[(int64_t)rc * cols + cbase + cidx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) t += rc0 + j < nchunks ? (double)pv[j] : 0.0;
+        }
+        ds[cbase + cidx] = (float)t;
+    }
+    if (threadIdx.x == 0) __hip_atomic_store(&tickets[blockIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// cols not a multiple of 8: one thread per column walks the rows (rarely used, kept simple)
+template <int DT>
+__global__ void fakequant_pc_scalar_kernel(const uint16_t* __restrict__ x, const uint16_t* dy, const float* __restrict__ s,
+                                           uint16_t* y, int8_t* codes, uint16_t* dx, float* ds,
+                                           int64_t rows, int64_t cols, int bits, int backward)
+{
+    using S = Store16<DT>;
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= cols) return;
+    const QConst c = make_qconst(s[k], bits);
+    double acc = 0.0;
+    for (int64_t r = 0; r < rows; ++r) {
+        const int64_t i = r * cols + k;
+        const float xv = S::one(x[i]);
+        const QElem e = quantize(xv, c);
+        if (!backward) {
+            y[i] = S::enc(codef_of(e) * c.s);
+            if (codes) codes[i] = (int8_t)code_of(e);
+        } else {
+            const bool keep = unclipped(e);
+            const float q = codef_of(e);
+            const uint16_t g = dy[i];
+            acc += (double)(S::one(g) * (keep ? __builtin_fmaf(-xv, c.inv_s, q) : q));
+            if (dx) dx[i] = keep ? g : (uint16_t)0;
+        }
+    }
+    if (backward) ds[k] = (float)acc;
+}
+
+static int pc_row_chunks(int64_t rows, int64_t col_blocks)
+{
+    // enough blocks to fill the chip (~512), at least 16 rows per block, at most kPcMaxRowChunks
+    int64_t want = (512 + col_blocks - 1) / col_blocks;
+    int64_t by_rows = (rows + 15) / 16;
+    int64_t rc = want < by_rows ? want : by_rows;
+    if (rc < 1) rc = 1;
+    if (rc > kPcMaxRowChunks) rc = kPcMaxRowChunks;
+    return (int)rc;
+}
+
+static int check_pc(int64_t rows, int64_t cols, int bits, int dt)
+{
+    if (rows <= 0 || cols <= 0) return SASQ_ERR_SHAPE;
+    if (rows > (INT64_C(1) << 40) / cols) return SASQ_ERR_SHAPE;
+    if ((cols + kPcColsPerBlock - 1) / kPcColsPerBlock > (int64_t)(kWsHeaderBytes / 4)) return SASQ_ERR_SHAPE;
+    if (bits < 2 || bits > 8) return SASQ_ERR_UNSUPPORTED;
+    if (dt != SASQ_F16 && dt != SASQ_BF16) return SASQ_ERR_UNSUPPORTED;
+    return SASQ_OK;
+}
+
+}  // namespace sasq
+
+using namespace sasq;
+
+extern "C" int sasq_fakequant_fwd_pc(const void* x, const float* s, void* y, int8_t* codes,
+                                     int64_t rows, int64_t cols, int bits, sasq_dtype dt, void* stream)
+{
+    if (!x || !s || !y) return SASQ_ERR_NULL;
+    int rc = check_pc(rows, cols, bits, (int)dt);
+    if (rc) return rc;
+    if (!aligned16(x) || !aligned16(y) || (codes && (reinterpret_cast<uintptr_t>(codes) & 7u))) return SASQ_ERR_ALIGN;
+    hipStream_t st = as_stream(stream);
+    auto X = static_cast<const uint16_t*>(x);
+    auto Y = static_cast<uint16_t*>(y);
+    if (cols % 8 != 0) {
+        const int blocks = (int)((cols + 255) / 256);
+        if (dt == SASQ_F16) fakequant_pc_scalar_kernel<SASQ_F16><<<blocks, 256, 0, st>>>(X, nullptr, s, Y, codes, nullptr, nullptr, rows, cols, bits, 0);
+        else                fakequant_pc_scalar_kernel<SASQ_BF16><<<blocks, 256, 0, st>>>(X, nullptr, s, Y, codes, nullptr, nullptr, rows, cols, bits, 0);
+        return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+    }
+    const int64_t col_blocks = (cols + kPcColsPerBlock - 1) / kPcColsPerBlock;
+    const int chunks = pc_row_chunks(rows, col_blocks);
+    const int64_t rpc = (rows + chunks - 1) / chunks;
+    dim3 grid((unsigned)col_blocks, (unsigned)chunks);
+    if (dt == SASQ_F16) {
+        if (codes) fakequant_fwd_pc_kernel<SASQ_F16, true><<<grid, kPcThreads, 0, st>>>(X, s, Y, codes, rows, cols, rpc, bits);
+        else       fakequant_fwd_pc_kernel<SASQ_F16, false><<<grid, kPcThreads, 0, st>>>(X, s, Y, codes, rows, cols, rpc, bits);
+    } else {
+        if (codes) fakequant_fwd_pc_kernel<SASQ_BF16, true><<<grid, kPcThreads, 0, st>>>(X, s, Y, codes, rows, cols, rpc, bits);
+        else       fakequant_fwd_pc_kernel<SASQ_BF16, false><<<grid, kPcThreads, 0, st>>>(X, s, Y, codes, rows, cols, rpc, bits);
+    }
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+extern "C" size_t sasq_fakequant_bwd_pc_workspace(int64_t rows, int64_t cols)
+{
+    (void)rows;
+    if (cols <= 0) return kWsHeaderBytes;
+    return kWsHeaderBytes + sizeof(float) * (size_t)kPcMaxRowChunks * (size_t)cols;
+}
+
+extern "C" int sasq_fakequant_bwd_pc(const void* x, const void* dy, const float* s, void* dx, float* ds,
+                                     int64_t rows, int64_t cols, int bits, sasq_dtype dt,
+                                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !dy || !s || !ds) return SASQ_ERR_NULL;
+    int rc = check_pc(rows, cols, bits, (int)dt);
+    if (rc) return rc;
+    if (!aligned16(x) || !aligned16(dy) || (dx && !aligned16(dx))) return SASQ_ERR_ALIGN;
+    hipStream_t st = as_stream(stream);
+    auto X = static_cast<const uint16_t*>(x);
+    auto G = static_cast<const uint16_t*>(dy);
+    auto DX = static_cast<uint16_t*>(dx);
+    if (cols % 8 != 0) {
+        const int blocks = (int)((cols + 255) / 256);
+        if (dt == SASQ_F16) fakequant_pc_scalar_kernel<SASQ_F16><<<blocks, 256, 0, st>>>(X, G, s, nullptr, nullptr, DX, ds, rows, cols, bits, 1);
+        else                fakequant_pc_scalar_kernel<SASQ_BF16><<<blocks, 256, 0, st>>>(X, G, s, nullptr, nullptr, DX, ds, rows, cols, bits, 1);
+        return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+    }
+    if (!workspace || workspace_bytes < sasq_fakequant_bwd_pc_workspace(rows, cols)) return SASQ_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SASQ_ERR_ALIGN;
+    const int64_t col_blocks = (cols + kPcColsPerBlock - 1) / kPcColsPerBlock;
+    const int chunks = pc_row_chunks(rows, col_blocks);
+    const int64_t rpc = (rows + chunks - 1) / chunks;
+    dim3 grid((unsigned)col_blocks, (unsigned)chunks);
+    auto tickets = static_cast<uint32_t*>(workspace);
+    auto parts = reinterpret_cast<float*>(static_cast<char*>(workspace) + kWsHeaderBytes);
+    if (dt == SASQ_F16) {
+        if (dx) fakequant_bwd_pc_kernel<SASQ_F16, true><<<grid, kPcThreads, 0, st>>>(X, G, s, DX, ds, tickets, parts, rows, cols, rpc, bits);
+        else    fakequant_bwd_pc_kernel<SASQ_F16, false><<<grid, kPcThreads, 0, st>>>(X, G, s, DX, ds, tickets, parts, rows, cols, rpc, bits);
+    } else {
+        if (dx) fakequant_bwd_pc_kernel<SASQ_BF16, true><<<grid, kPcThreads, 0, st>>>(X, G, s, DX, ds, tickets, parts, rows, cols, rpc, bits);
+        else    fakequant_bwd_pc_kernel<SASQ_BF16, false><<<grid, kPcThreads, 0, st>>>(X, G, s, DX, ds, tickets, parts, rows, cols, rpc, bits);
+    }
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}

@@ -143,10 +143,10 @@ extern "C" int sasq_version(void) { return 100; }
 extern "C" int sasq_workspace_init(void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!workspace) return SASQ_ERR_NULL;
-    if (workspace_bytes < kWsHeaderBytes) return SASQ_ERR_WORKSPACE;
+    if (workspace_bytes < kWsMinBytes) return SASQ_ERR_WORKSPACE;
     if (!aligned16(workspace)) return SASQ_ERR_ALIGN;
-    const int64_t words = kWsHeaderBytes / 4;
-    fill_zero_kernel<<<1, 64, 0, as_stream(stream)>>>(static_cast<uint32_t*>(workspace), words);
+    const int64_t words = (int64_t)((workspace_bytes < kWsHeaderBytes ? workspace_bytes : kWsHeaderBytes) / 4);
+    fill_zero_kernel<<<1, 256, 0, as_stream(stream)>>>(static_cast<uint32_t*>(workspace), words);
     return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
 }
 

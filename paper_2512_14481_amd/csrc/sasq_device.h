@@ -115,8 +115,10 @@ __device__ __forceinline__ uint32_t wave_max(uint32_t v)
     return v;
 }
 
-// Workspace header used by the grid-wide reductions: word 0 is the arrival ticket.
-constexpr size_t kWsHeaderBytes = 256;
+// Workspace header used by the grid-wide reductions: arrival tickets (word 0 for the scalar
+// reductions, words 0..255 one per column chunk for the per-channel backward).
+constexpr size_t kWsHeaderBytes = 1024;
+constexpr size_t kWsMinBytes = 256;
 constexpr uint32_t kTicketBase = 0;
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
