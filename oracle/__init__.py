@@ -18,6 +18,11 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "sasq_oracle.c")
 _LIB = os.path.join(_HERE, "libsasq_oracle.so")
+# The mutation tests (tests/test_oracle_mutations.py) point this at a deliberately broken copy of
+# the source to show that the pins notice; nothing else sets it.
+if os.environ.get("SASQ_ORACLE_MUTANT_SRC"):
+    _SRC = os.environ["SASQ_ORACLE_MUTANT_SRC"]
+    _LIB = os.path.splitext(_SRC)[0] + ".so"
 
 DT = {"f16": 0, "bf16": 1}
 WF = {"int8": 0, "int4": 1}

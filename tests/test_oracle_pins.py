@@ -407,3 +407,38 @@ def test_oracle_independent_of_thread_count():
     a = oracle.fakequant_bwd(x, dy, np.float32(0.05), 8, "f16")
     b = oracle.fakequant_bwd(x.reshape(200, 64), dy.reshape(200, 64), np.float32(0.05), 8, "f16")
     assert a["ds64"] == b["ds64"]
+
+
+def test_epilogue_rounding_order_is_pinned():
+    """Y = fl32(fl32(acc) * fl32(s * s_w[n])): find (by numpy fp32 arithmetic) accumulator / scale
+    triples for which multiplying in the other order lands on a different fp16 value, build inputs
+    that produce exactly those accumulators, and require the pinned order."""
+    rng = np.random.default_rng(23)
+    A = rng.integers(-60000, 60000, size=400000).astype(np.int64)
+    s = np.float32(0.0437)
+    sw = np.exp(rng.uniform(np.log(1e-4), np.log(1e-2), A.size)).astype(np.float32)
+    af = A.astype(np.float32)
+    pinned = (af * (s * sw).astype(np.float32)).astype(np.float32)
+    other = ((af * s).astype(np.float32) * sw).astype(np.float32)
+    hp, ho = wl.f32_to_storage_bits(pinned, "f16"), wl.f32_to_storage_bits(other, "f16")
+    pick = np.flatnonzero(hp != ho)[:24]
+    assert pick.size >= 8, "search found too few discriminating cases"
+    # one output channel per case: N = len(pick), K = 8, a single token
+    K = 8
+    xcodes = np.array([127, -128, 90, -77, 64, 33, -5, 1], dtype=np.int64)
+    N = pick.size
+    wq = np.zeros((N, K), dtype=np.int8)
+    for j, i in enumerate(pick):
+        # greedy integer solve of sum_k xcodes[k] * w[k] = A[i] with |w| <= 127
+        rest = int(A[i])
+        for k in range(K):
+            w = int(np.clip(round(rest / xcodes[k]), -127, 127)) if k < K - 1 else int(rest // xcodes[k])
+            wq[j, k] = w
+            rest -= w * int(xcodes[k])
+        assert rest == 0 and -127 <= wq[j, K - 1] <= 127
+    x = _bits((xcodes.astype(np.float32) * s)[None, :], "f16")
+    out = oracle.static_linear(x, s, wq, sw[pick], None, 8, "int8", "f16")
+    assert np.array_equal(out["xq"][0], xcodes.astype(np.int8))
+    assert np.array_equal(out["acc"][0].astype(np.int64), A[pick])
+    assert np.array_equal(out["y"][0], hp[pick])
+    assert not np.array_equal(out["y"][0], ho[pick])
