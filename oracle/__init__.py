@@ -209,3 +209,14 @@ def fakequant_bwd_pc(x: np.ndarray, dy: np.ndarray, s: np.ndarray, bits: int, dt
                                             ctypes.c_int64(rows), ctypes.c_int64(cols), int(bits), DT[dtype])
     _check(rc, "fakequant_bwd_pc")
     return {"dx": dx, "ds": ds, "ds64": ds64, "sum_abs": sabs}
+
+
+def scale_adamw(p: np.ndarray, g: np.ndarray, m: np.ndarray, v: np.ndarray, step: int, lr: float,
+                b1: float = 0.9, b2: float = 0.999, eps: float = 1e-8, wd: float = 0.01):
+    """One AdamW step on fp32 vectors; returns new (p, m, v)."""
+    p, m, v = (np.array(a, dtype=np.float32, copy=True) for a in (p, m, v))
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    d = ctypes.c_double
+    lib().sasq_oracle_scale_adamw(_p(p), _p(g), _p(m), _p(v), ctypes.c_int64(p.size), ctypes.c_int64(step),
+                                  d(lr), d(b1), d(b2), d(eps), d(wd))
+    return p, m, v

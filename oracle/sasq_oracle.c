@@ -408,3 +408,24 @@ int sasq_oracle_fakequant_bwd_pc(const uint16_t* x, const uint16_t* dy, const fl
     }
     return OK;
 }
+
+/*
+ * AdamW step on a vector of scales (the optimiser of the paper's runs: Sec. 5.1 "AdamW ... with a
+ * learning rate of 2e-4"; the scales are the only parameters, Sec. 4.2).  Decoupled weight decay:
+ *   p <- p - lr*wd*p;  m <- b1*m + (1-b1)*g;  v <- b2*v + (1-b2)*g^2;
+ *   p <- p - lr * (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps).
+ * Evaluated in fp64 on fp32 state; results rounded once to fp32.
+ */
+void sasq_oracle_scale_adamw(float* p, const float* g, float* m, float* v, int64_t n, int64_t step,
+                             double lr, double b1, double b2, double eps, double wd)
+{
+    const double bc1 = 1.0 - pow(b1, (double)step), bc2 = 1.0 - pow(b2, (double)step);
+    for (int64_t i = 0; i < n; ++i) {
+        double pi = (double)p[i], gi = (double)g[i];
+        pi -= lr * wd * pi;
+        double mi = b1 * (double)m[i] + (1.0 - b1) * gi;
+        double vi = b2 * (double)v[i] + (1.0 - b2) * gi * gi;
+        pi -= lr * (mi / bc1) / (sqrt(vi / bc2) + eps);
+        p[i] = (float)pi; m[i] = (float)mi; v[i] = (float)vi;
+    }
+}

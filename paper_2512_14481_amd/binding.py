@@ -49,6 +49,7 @@ def _lib() -> ctypes.CDLL:
         L.sasq_fakequant_bwd_workspace.argtypes = [i64, i64]
         L.sasq_fakequant_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, sz, vp]
         L.sasq_scale_sgd.argtypes = [vp, vp, f32, vp]
+        L.sasq_scale_adamw.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, f32, f32, vp]
         L.sasq_fakequant_fwd_pc.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp]
         L.sasq_fakequant_bwd_pc_workspace.restype = sz
         L.sasq_fakequant_bwd_pc_workspace.argtypes = [i64, i64]
@@ -165,6 +166,17 @@ def sasq_fakequant_bwd_pc(x: torch.Tensor, dy: torch.Tensor, s: torch.Tensor, dx
 def sasq_scale_sgd(s: torch.Tensor, ds: torch.Tensor, lr: float) -> None:
     _want(s, torch.float32, "s"); _want(ds, torch.float32, "ds")
     _check(_lib().sasq_scale_sgd(_ptr(s), _ptr(ds), ctypes.c_float(lr), _stream()), "sasq_scale_sgd")
+
+
+def sasq_scale_adamw(s: torch.Tensor, ds: torch.Tensor, m: torch.Tensor, v: torch.Tensor, step: int, lr: float,
+                     beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8, weight_decay: float = 0.01) -> None:
+    for t_, n_ in ((s, "s"), (ds, "ds"), (m, "m"), (v, "v")):
+        _want(t_, torch.float32, n_)
+    if not (s.numel() == ds.numel() == m.numel() == v.numel()):
+        raise ValueError("s, ds, m, v must have the same length")
+    f = ctypes.c_float
+    _check(_lib().sasq_scale_adamw(_ptr(s), _ptr(ds), _ptr(m), _ptr(v), s.numel(), int(step), f(lr), f(beta1),
+                                   f(beta2), f(eps), f(weight_decay), _stream()), "sasq_scale_adamw")
 
 
 def sasq_static_linear_workspace(M: int, N: int, K: int, wf: int) -> int:

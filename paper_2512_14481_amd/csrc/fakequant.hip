@@ -7,6 +7,7 @@
 // access, a block covers kUnroll such accesses per lane back to back so enough bytes are in
 // flight to cover HBM latency, and a scalar tail handles the last (n mod 8) elements.
 #include "sasq_device.h"
+#include <cmath>
 
 namespace sasq {
 
@@ -210,6 +211,23 @@ __global__ void scale_sgd_kernel(float* s, const float* ds, float lr)
     }
 }
 
+// AdamW with decoupled weight decay on a vector of scales; the bias corrections 1 - beta^t are
+// computed by the host in double and passed in.
+__global__ void scale_adamw_kernel(float* __restrict__ p, const float* __restrict__ g, float* __restrict__ m,
+                                   float* __restrict__ v, int64_t n, float lr, float b1, float b2, float eps,
+                                   float wd, float bc1, float bc2)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float pi = p[i];
+    const float gi = g[i];
+    pi = pi - lr * wd * pi;
+    const float mi = b1 * m[i] + (1.0f - b1) * gi;
+    const float vi = b2 * v[i] + (1.0f - b2) * gi * gi;
+    pi = pi - lr * (mi / bc1) / (sqrtf(vi / bc2) + eps);
+    p[i] = pi; m[i] = mi; v[i] = vi;
+}
+
 static int grid_for(int64_t nvec, int max_blocks)
 {
     int64_t per_block = (int64_t)kThreads * kUnroll;
@@ -292,5 +310,17 @@ extern "C" int sasq_scale_sgd(float* s, const float* ds, float lr, void* stream)
 {
     if (!s || !ds) return SASQ_ERR_NULL;
     scale_sgd_kernel<<<1, 64, 0, as_stream(stream)>>>(s, ds, lr);
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+extern "C" int sasq_scale_adamw(float* s, const float* ds, float* m, float* v, int64_t n, int64_t step,
+                                float lr, float beta1, float beta2, float eps, float weight_decay, void* stream)
+{
+    if (!s || !ds || !m || !v) return SASQ_ERR_NULL;
+    if (n <= 0 || n > (INT64_C(1) << 31) || step <= 0) return SASQ_ERR_SHAPE;
+    const float bc1 = (float)(1.0 - pow((double)beta1, (double)step));
+    const float bc2 = (float)(1.0 - pow((double)beta2, (double)step));
+    const int blocks = (int)((n + 255) / 256);
+    scale_adamw_kernel<<<blocks, 256, 0, as_stream(stream)>>>(s, ds, m, v, n, lr, beta1, beta2, eps, weight_decay, bc1, bc2);
     return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
 }

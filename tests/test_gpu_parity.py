@@ -255,3 +255,21 @@ def test_cross_export_identity():
     exact = (codes.astype(np.float64) * float(s)) @ (wq.astype(np.float64) * s_w[:, None].astype(np.float64)).T
     yv = val(y, dtype)
     assert (np.abs(yv - exact) <= 2.0 ** -10 * np.abs(exact) + 1e-6).all()
+
+
+def test_scale_adamw():
+    rng = np.random.default_rng(31)
+    for n in (1, 7, 4096, 11008):
+        p = rng.uniform(0.01, 2.0, n).astype(np.float32)
+        m, v = np.zeros(n, np.float32), np.zeros(n, np.float32)
+        pd, md, vd = (torch.from_numpy(a.copy()).cuda() for a in (p, m, v))
+        for step in range(1, 5):
+            g = (rng.standard_normal(n) * 30).astype(np.float32)
+            B.sasq_scale_adamw(pd, torch.from_numpy(g).cuda(), md, vd, step, 2e-4)
+            p, m, v = oracle.scale_adamw(p, g, m, v, step, 2e-4)
+            # fp32 kernel against the fp64-evaluated oracle: a handful of fp32 roundings
+            assert np.allclose(pd.cpu().numpy(), p, rtol=2e-6, atol=0)
+            assert np.allclose(md.cpu().numpy(), m, rtol=2e-6, atol=1e-30)
+            assert np.allclose(vd.cpu().numpy(), v, rtol=2e-6, atol=1e-30)
+            # keep both sides on the same state so that differences do not accumulate
+            pd.copy_(torch.from_numpy(p)); md.copy_(torch.from_numpy(m)); vd.copy_(torch.from_numpy(v))

@@ -442,3 +442,22 @@ def test_epilogue_rounding_order_is_pinned():
     assert np.array_equal(out["acc"][0].astype(np.int64), A[pick])
     assert np.array_equal(out["y"][0], hp[pick])
     assert not np.array_equal(out["y"][0], ho[pick])
+
+
+def test_adamw_matches_torch_optimizer():
+    """The oracle's AdamW step against torch.optim.AdamW on fp64 CPU parameters (library routine)."""
+    rng = np.random.default_rng(29)
+    n = 17
+    p0 = rng.uniform(0.01, 2.0, n).astype(np.float32)
+    grads = [rng.standard_normal(n).astype(np.float32) * 50 for _ in range(4)]
+    pt = torch.nn.Parameter(torch.tensor(p0.astype(np.float64)))
+    opt = torch.optim.AdamW([pt], lr=2e-4, betas=(0.9, 0.999), eps=1e-8, weight_decay=0.01)
+    p, m, v = p0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)
+    for step, g in enumerate(grads, start=1):
+        pt.grad = torch.tensor(g.astype(np.float64))
+        opt.step()
+        p, m, v = oracle.scale_adamw(p, g, m, v, step, 2e-4)
+        assert np.allclose(p, pt.detach().numpy(), rtol=3e-7, atol=0), step   # fp32 state rounding only
+    # first step from zero state moves every scale by ~lr against the gradient's sign
+    p1, _, _ = oracle.scale_adamw(p0, grads[0], np.zeros(n, np.float32), np.zeros(n, np.float32), 1, 2e-4, wd=0.0)
+    assert np.allclose(p1 - p0, -2e-4 * np.sign(grads[0]), rtol=1e-3, atol=1e-7)
