@@ -134,10 +134,11 @@ int sasq_scale_sgd(float* s, const float* ds, float lr, void* stream);
  *     p <- p - lr*wd*p;  m <- b1*m + (1-b1)*g;  v <- b2*v + (1-b2)*g^2;
  *     p <- p - lr * (m/(1-b1^step)) / (sqrt(v/(1-b2^step)) + eps)
  *   s, ds, m, v  [n] device fp32 (m, v: first and second moment state, zero before step 1)
- *   step         1-based step count.  fp32 arithmetic: agrees with an fp64 evaluation to ~1e-6 relative.
+ *   step         1-based step count.  Hyper-parameters are doubles (1 - beta is formed in double);
+ *                the update itself is fp32 arithmetic and agrees with an fp64 evaluation to ~1e-6 relative.
  */
 int sasq_scale_adamw(float* s, const float* ds, float* m, float* v, int64_t n, int64_t step,
-                     float lr, float beta1, float beta2, float eps, float weight_decay, void* stream);
+                     double lr, double beta1, double beta2, double eps, double weight_decay, void* stream);
 
 /* Bytes of workspace sasq_static_linear needs (pure function, host only; may be 0). */
 size_t sasq_static_linear_workspace(int64_t M, int64_t N, int64_t K, sasq_wfmt wf);

@@ -49,7 +49,7 @@ def _lib() -> ctypes.CDLL:
         L.sasq_fakequant_bwd_workspace.argtypes = [i64, i64]
         L.sasq_fakequant_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, sz, vp]
         L.sasq_scale_sgd.argtypes = [vp, vp, f32, vp]
-        L.sasq_scale_adamw.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, f32, f32, vp]
+        L.sasq_scale_adamw.argtypes = [vp, vp, vp, vp, i64, i64] + [ctypes.c_double] * 5 + [vp]
         L.sasq_fakequant_fwd_pc.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp]
         L.sasq_fakequant_bwd_pc_workspace.restype = sz
         L.sasq_fakequant_bwd_pc_workspace.argtypes = [i64, i64]
@@ -174,7 +174,7 @@ def sasq_scale_adamw(s: torch.Tensor, ds: torch.Tensor, m: torch.Tensor, v: torc
         _want(t_, torch.float32, n_)
     if not (s.numel() == ds.numel() == m.numel() == v.numel()):
         raise ValueError("s, ds, m, v must have the same length")
-    f = ctypes.c_float
+    f = ctypes.c_double
     _check(_lib().sasq_scale_adamw(_ptr(s), _ptr(ds), _ptr(m), _ptr(v), s.numel(), int(step), f(lr), f(beta1),
                                    f(beta2), f(eps), f(weight_decay), _stream()), "sasq_scale_adamw")
 

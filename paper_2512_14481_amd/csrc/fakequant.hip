@@ -214,16 +214,16 @@ __global__ void scale_sgd_kernel(float* s, const float* ds, float lr)
 // AdamW with decoupled weight decay on a vector of scales; the bias corrections 1 - beta^t are
 // computed by the host in double and passed in.
 __global__ void scale_adamw_kernel(float* __restrict__ p, const float* __restrict__ g, float* __restrict__ m,
-                                   float* __restrict__ v, int64_t n, float lr, float b1, float b2, float eps,
-                                   float wd, float bc1, float bc2)
+                                   float* __restrict__ v, int64_t n, float lr, float b1, float b2, float omb1,
+                                   float omb2, float eps, float wd, float bc1, float bc2)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     float pi = p[i];
     const float gi = g[i];
     pi = pi - lr * wd * pi;
-    const float mi = b1 * m[i] + (1.0f - b1) * gi;
-    const float vi = b2 * v[i] + (1.0f - b2) * gi * gi;
+    const float mi = b1 * m[i] + omb1 * gi;
+    const float vi = b2 * v[i] + omb2 * gi * gi;
     pi = pi - lr * (mi / bc1) / (sqrtf(vi / bc2) + eps);
     p[i] = pi; m[i] = mi; v[i] = vi;
 }
@@ -314,13 +314,16 @@ extern "C" int sasq_scale_sgd(float* s, const float* ds, float lr, void* stream)
 }
 
 extern "C" int sasq_scale_adamw(float* s, const float* ds, float* m, float* v, int64_t n, int64_t step,
-                                float lr, float beta1, float beta2, float eps, float weight_decay, void* stream)
+                                double lr, double beta1, double beta2, double eps, double weight_decay, void* stream)
 {
     if (!s || !ds || !m || !v) return SASQ_ERR_NULL;
     if (n <= 0 || n > (INT64_C(1) << 31) || step <= 0) return SASQ_ERR_SHAPE;
-    const float bc1 = (float)(1.0 - pow((double)beta1, (double)step));
-    const float bc2 = (float)(1.0 - pow((double)beta2, (double)step));
+    // 1 - beta and 1 - beta^step are formed in double: in fp32, 1 - 0.999f is off by 1e-5 relative
+    const float bc1 = (float)(1.0 - pow(beta1, (double)step));
+    const float bc2 = (float)(1.0 - pow(beta2, (double)step));
     const int blocks = (int)((n + 255) / 256);
-    scale_adamw_kernel<<<blocks, 256, 0, as_stream(stream)>>>(s, ds, m, v, n, lr, beta1, beta2, eps, weight_decay, bc1, bc2);
+    scale_adamw_kernel<<<blocks, 256, 0, as_stream(stream)>>>(s, ds, m, v, n, (float)lr, (float)beta1, (float)beta2,
+                                                              (float)(1.0 - beta1), (float)(1.0 - beta2), (float)eps,
+                                                              (float)weight_decay, bc1, bc2);
     return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
 }

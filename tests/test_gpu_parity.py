@@ -269,7 +269,8 @@ def test_scale_adamw():
             p, m, v = oracle.scale_adamw(p, g, m, v, step, 2e-4)
             # fp32 kernel against the fp64-evaluated oracle: a handful of fp32 roundings
             assert np.allclose(pd.cpu().numpy(), p, rtol=2e-6, atol=0)
-            assert np.allclose(md.cpu().numpy(), m, rtol=2e-6, atol=1e-30)
+            # the moments are sums of two terms that may cancel: absolute slack scaled by the terms
+            assert np.allclose(md.cpu().numpy(), m, rtol=2e-6, atol=2e-7 * float(np.abs(g).max()))
             assert np.allclose(vd.cpu().numpy(), v, rtol=2e-6, atol=1e-30)
             # keep both sides on the same state so that differences do not accumulate
             pd.copy_(torch.from_numpy(p)); md.copy_(torch.from_numpy(m)); vd.copy_(torch.from_numpy(v))
