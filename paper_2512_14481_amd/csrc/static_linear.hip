@@ -114,14 +114,26 @@ __global__ __launch_bounds__(256) void linear_scalar_kernel(
 // Epilogue: each wave dequantizes its 128x128 block, stages it through its own LDS region as
 // 16-bit values in [m][n] order and writes Y with 128-bit stores, 256 contiguous bytes per row.
 // ---------------------------------------------------------------------------------------------
-constexpr int kBM = 256, kBN = 256, kBK = 64;
+constexpr int kBK = 64;
 constexpr int kStages = 4;
-constexpr int kStageBytes = kBM * kBK;              // 16 KB per operand per stage
 constexpr int kGemmThreads = 256;
 constexpr int64_t kFusedMaxN = 0;                   // quantize-on-load when N has at most this many columns
-constexpr int kEpiStride = 272;                     // bytes per staged output row: 256 + 16 (bank spread)
-constexpr int kEpiBytes = 128 * kEpiStride;         // per wave
-constexpr int kGemmLds = 4 * kEpiBytes > kStages * 2 * kStageBytes ? 4 * kEpiBytes : kStages * 2 * kStageBytes;
+constexpr double kCost128x256 = 1.28, kCost128x128 = 1.42;   // time per output element relative to 256x256 tiles
+
+// Tile geometry.  BM x BN is the workgroup tile (256x256, 128x256 or 128x128); the four waves
+// form a 2x2 grid, each owning (BM/2) x (BN/2) as MF x NF tiles of 32x32.
+template <int BM, int BN>
+struct Tile {
+    static_assert((BM == 128 || BM == 256) && (BN == 128 || BN == 256) && BM <= BN, "unsupported tile");
+    static constexpr int MF = BM / 64, NF = BN / 64;                    // 32x32 tiles per wave along m, n
+    static constexpr int XS = BM / 64, WS = BN / 64;                    // 1 KB slabs per wave per stage
+    static constexpr int kXBytes = BM * kBK, kWBytes = BN * kBK;        // per stage
+    static constexpr int kStageBytes = kXBytes + kWBytes;
+    static constexpr int kEpiStride = BN + 16;                          // bytes per staged output row (+16: bank spread)
+    static constexpr int kEpiBytes = (BM / 2) * kEpiStride;             // per wave
+    static constexpr int kLds = 4 * kEpiBytes > kStages * kStageBytes ? 4 * kEpiBytes : kStages * kStageBytes;
+    static constexpr int kWavesPerSimd = (MF * NF * 16 <= 64) ? 2 : 1;  // 128x128 tiles: two workgroups per CU
+};
 
 __device__ __forceinline__ int swz64(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
 
@@ -159,8 +171,9 @@ __device__ __forceinline__ bool tile_of_block(int bid, int tiles_m, int tiles_n,
 enum { X_PREQ = 0, X_FUSED = 1 };
 enum { W_I8 = 0, W_I4 = 1 };
 
-template <int DT, int XMODE, int WMODE>
-__global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+template <int DT, int XMODE, int WMODE, int BM, int BN>
+__global__ __launch_bounds__(kGemmThreads)
+__attribute__((amdgpu_waves_per_eu(Tile<BM, BN>::kWavesPerSimd, Tile<BM, BN>::kWavesPerSimd)))
 void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict__ wq,
                         const float* __restrict__ s_ptr, const float* __restrict__ s_w,
                         const float* __restrict__ bias, uint16_t* __restrict__ y,
@@ -168,84 +181,89 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
                         int tiles_m, int tiles_n)
 {
     using S = Store16<DT>;
-    __shared__ __attribute__((aligned(1024))) char lds[kGemmLds];
-    auto stage_ptr = [&](int st, int operand) -> char* { return &lds[(st * 2 + operand) * kStageBytes]; };
+    using T = Tile<BM, BN>;
+    constexpr int MF = T::MF, NF = T::NF, XS = T::XS, WS = T::WS;
+    __shared__ __attribute__((aligned(1024))) char lds[T::kLds];
+    auto stage_ptr = [&](int st, int operand) -> char* { return &lds[st * T::kStageBytes + operand * T::kXBytes]; };
 
     int tm, tn;
     if (!tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
-    const int m0 = tm * kBM, n0 = tn * kBN;
+    const int m0 = tm * BM, n0 = tn * BN;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave & 1, wn = wave >> 1;
     const int KT = K / kBK;
-    auto eff_tile = [&](int T) { return min(max(T, 0), KT - 1); };
-    // LDS stage of K tile T.  Tiles before the first are directed at tile 0's own stage (an
+    auto eff_tile = [&](int Tk) { return min(max(Tk, 0), KT - 1); };
+    // LDS stage of K tile Tk.  Tiles before the first are directed at tile 0's own stage (an
     // identical rewrite), tiles past the last at the stage they would own (free by then).
-    auto stage_of = [&](int T) { return (T < 0 ? 0 : T) & 3; };
+    auto stage_of = [&](int Tk) { return (Tk < 0 ? 0 : Tk) & 3; };
 
     // ---- direct L2 -> LDS path: load j of wave w fills rows (4j + w)*16 .. +16 of a stage ----
     // Lane i writes LDS slot i of that 1 KB: row i/4, position i%4; it therefore fetches the
     // logical chunk (i%4) ^ swz64(row), and swz64 of these rows depends on the lane only.
     const int lrow = lane >> 2;
     const int lchunk = (lane & 3) ^ (((lane >> 3) & 3) ^ ((lane >> 5) & 1));
-    const int8_t* gx[4];
-    const int8_t* gw[4];
+    const int8_t* gx[XS];
+    const int8_t* gw[WS];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int r = (4 * j + wave) * 16 + lrow;
-        const int mr = min(m0 + r, M - 1), nr = min(n0 + r, N - 1);   // rows past the edge re-read the last row
+    for (int j = 0; j < XS; ++j) {
+        const int mr = min(m0 + (4 * j + wave) * 16 + lrow, M - 1);     // rows past the edge re-read the last row
         gx[j] = static_cast<const int8_t*>(xin) + (int64_t)mr * K + lchunk * 16;
+    }
+#pragma unroll
+    for (int j = 0; j < WS; ++j) {
+        const int nr = min(n0 + (4 * j + wave) * 16 + lrow, N - 1);
         gw[j] = reinterpret_cast<const int8_t*>(wq) + (int64_t)nr * K + lchunk * 16;
     }
-    auto dma_x = [&](int T, int j) {
-        __builtin_amdgcn_global_load_lds((glb_ptr_t)(gx[j] + eff_tile(T) * kBK),
-                                         (lds_ptr_t)(stage_ptr(stage_of(T), 0) + (4 * j + wave) * 1024), 16, 0, 0);
+    auto dma_x = [&](int Tk, int j) {
+        __builtin_amdgcn_global_load_lds((glb_ptr_t)(gx[j] + eff_tile(Tk) * kBK),
+                                         (lds_ptr_t)(stage_ptr(stage_of(Tk), 0) + (4 * j + wave) * 1024), 16, 0, 0);
     };
-    auto dma_w = [&](int T, int j) {
-        __builtin_amdgcn_global_load_lds((glb_ptr_t)(gw[j] + eff_tile(T) * kBK),
-                                         (lds_ptr_t)(stage_ptr(stage_of(T), 1) + (4 * j + wave) * 1024), 16, 0, 0);
+    auto dma_w = [&](int Tk, int j) {
+        __builtin_amdgcn_global_load_lds((glb_ptr_t)(gw[j] + eff_tile(Tk) * kBK),
+                                         (lds_ptr_t)(stage_ptr(stage_of(Tk), 1) + (4 * j + wave) * 1024), 16, 0, 0);
     };
 
-    // ---- register path: thread t owns 16-byte chunk t%4 of rows t/4 + 64j, j = 0..3 ----
+    // ---- register path: thread t owns 16-byte chunk t%4 of rows t/4 + 64j ----
     const int rrow = tid >> 2, rchunk = tid & 3;
     const int rslot = rrow * kBK + ((rchunk ^ swz64(rrow)) << 4);       // swz64(rrow + 64j) == swz64(rrow)
     const QConst qk = make_qconst(*s_ptr, a_bits);
-    u32x4 xr[3][8];     // XMODE 1: three K tiles of 16-bit activations in flight (2 x 128 bit per task)
-    u32x2 wr[3][4];     // WMODE 1: three K tiles of packed int4 weights in flight (64 bit per task)
+    u32x4 xr[3][2 * XS];   // XMODE 1: three K tiles of 16-bit activations in flight (2 x 128 bit per task)
+    u32x2 wr[3][WS];       // WMODE 1: three K tiles of packed int4 weights in flight (64 bit per task)
 #pragma unroll
     for (int a = 0; a < 3; ++a) {
 #pragma unroll
-        for (int b = 0; b < 8; ++b) xr[a][b] = u32x4{0u, 0u, 0u, 0u};
+        for (int b = 0; b < 2 * XS; ++b) xr[a][b] = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int b = 0; b < 4; ++b) wr[a][b] = u32x2{0u, 0u};
+        for (int b = 0; b < WS; ++b) wr[a][b] = u32x2{0u, 0u};
     }
-    const uint16_t* rx[4];
-    const uint8_t* rw[4];
+    const uint16_t* rx[XS];
+    const uint8_t* rw[WS];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int mr = min(m0 + rrow + 64 * j, M - 1), nr = min(n0 + rrow + 64 * j, N - 1);
-        rx[j] = static_cast<const uint16_t*>(xin) + (int64_t)mr * K + rchunk * 16;
-        rw[j] = wq + (int64_t)nr * (K / 2) + rchunk * 8;
-    }
+    for (int j = 0; j < XS; ++j)
+        rx[j] = static_cast<const uint16_t*>(xin) + (int64_t)min(m0 + rrow + 64 * j, M - 1) * K + rchunk * 16;
+#pragma unroll
+    for (int j = 0; j < WS; ++j)
+        rw[j] = wq + (int64_t)min(n0 + rrow + 64 * j, N - 1) * (K / 2) + rchunk * 8;
     // Register sets are selected with compile-time indices (a run-time index would put the arrays
     // in scratch memory): the K loop is unrolled by 3 and passes set = tile mod 3 as a constant.
-    auto regload_x = [&](int T, auto set_c) {
+    auto regload_x = [&](int Tk, auto set_c) {
         constexpr int set = decltype(set_c)::value;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const u32x4* p = reinterpret_cast<const u32x4*>(rx[j] + eff_tile(T) * kBK);
+        for (int j = 0; j < XS; ++j) {
+            const u32x4* p = reinterpret_cast<const u32x4*>(rx[j] + eff_tile(Tk) * kBK);
             xr[set][2 * j] = p[0];
             xr[set][2 * j + 1] = p[1];
         }
     };
-    auto regload_w = [&](int T, auto set_c) {
+    auto regload_w = [&](int Tk, auto set_c) {
         constexpr int set = decltype(set_c)::value;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) wr[set][j] = *reinterpret_cast<const u32x2*>(rw[j] + eff_tile(T) * (kBK / 2));
+        for (int j = 0; j < WS; ++j) wr[set][j] = *reinterpret_cast<const u32x2*>(rw[j] + eff_tile(Tk) * (kBK / 2));
     };
-    // quantize task j of tile T (16 elements) and store the 16 int8 codes
-    auto convert_x = [&](int T, int j, auto set_c) {
+    // quantize task j of tile Tk (16 elements) and store the 16 int8 codes
+    auto convert_x = [&](int Tk, int j, auto set_c) {
         constexpr int set = decltype(set_c)::value;
         float c[16];
 #pragma unroll
@@ -263,13 +281,13 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
             o[0] = pack_codes4(c[0], c[1], c[2], c[3]);    o[1] = pack_codes4(c[4], c[5], c[6], c[7]);
             o[2] = pack_codes4(c[8], c[9], c[10], c[11]);  o[3] = pack_codes4(c[12], c[13], c[14], c[15]);
         }
-        *reinterpret_cast<u32x4*>(stage_ptr(stage_of(T), 0) + (rslot + 64 * j * kBK)) = o;
+        *reinterpret_cast<u32x4*>(stage_ptr(stage_of(Tk), 0) + (rslot + 64 * j * kBK)) = o;
     };
-    auto convert_w = [&](int T, int j, auto set_c) {
+    auto convert_w = [&](int Tk, int j, auto set_c) {
         constexpr int set = decltype(set_c)::value;
         const uint32_t w0 = wr[set][j][0], w1 = wr[set][j][1];
         u32x4 o = {(w0 << 4) & 0xF0F0F0F0u, w0 & 0xF0F0F0F0u, (w1 << 4) & 0xF0F0F0F0u, w1 & 0xF0F0F0F0u};
-        *reinterpret_cast<u32x4*>(stage_ptr(stage_of(T), 1) + (rslot + 64 * j * kBK)) = o;
+        *reinterpret_cast<u32x4*>(stage_ptr(stage_of(Tk), 1) + (rslot + 64 * j * kBK)) = o;
     };
 
     // ---- LDS -> MFMA fragments ----
@@ -277,32 +295,36 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
     int foff[2];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) foff[kk] = frow * kBK + (((kk * 2 + fgrp) ^ swz64(frow)) << 4);
-    const int xbase = wm * 128 * kBK, wbase = wn * 128 * kBK;
-    i32x4 fx[2][4], fw[2][4];
-    auto read_x = [&](int set, int st, int kk, int t) {
-        fx[set][t] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 0) + xbase + t * 32 * kBK + foff[kk]);
-    };
-    auto read_w = [&](int set, int st, int kk, int t) {
-        fw[set][t] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 1) + wbase + t * 32 * kBK + foff[kk]);
+    const int xbase = wm * (BM / 2) * kBK, wbase = wn * (BN / 2) * kBK;
+    i32x4 fx[2][MF], fw[2][NF];
+    // fragment `idx` of a K-substep: the MF activation fragments first, then the NF weight ones
+    auto read_frag = [&](int set, int st, int kk, int idx) {
+        if (idx < MF) fx[set][idx] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 0) + xbase + idx * 32 * kBK + foff[kk]);
+        else          fw[set][idx - MF] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 1) + wbase + (idx - MF) * 32 * kBK + foff[kk]);
     };
 
-    i32x16 acc[4][4];   // [n tile][m tile]
+    i32x16 acc[NF][MF];   // [n tile][m tile]
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < NF; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
+        for (int b = 0; b < MF; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
 
     // ---- K pipeline ----
-    // Iteration i consumes K tile i.  Its phase 0 issues the weight loads of tile i+3, its phase 1
-    // the activation loads of tile i+4, so the per-wave issue order is W(i+3), X(i+4), W(i+4), ...
-    // and every "has landed" condition below is one s_waitcnt vmcnt(n) with n = loads issued
-    // later (memory loads return in issue order).  Register-path tiles are converted into LDS
-    // ahead of use: X(i+1) half in phase 1 of iteration i-1 and half in phase 0 of iteration i,
-    // W(i+1) in phase 0 of iteration i.  Iterations -4..-1 only fill the pipeline.
-    constexpr int nX = XMODE == X_FUSED ? 8 : 4;     // loads per wave per K tile
-    constexpr int nW = 4;
+    // Iteration i consumes K tile i in two phases (K-substeps of 32), each NF groups of MF MFMAs.
+    // Phase 0 issues the weight loads of tile i+3, phase 1 the activation loads of tile i+4, so
+    // the per-wave issue order is W(i+3), X(i+4), W(i+4), ... and every "has landed" condition
+    // below is one s_waitcnt vmcnt(n) with n = loads issued later (memory loads return in issue
+    // order).  Register-path tiles are converted into LDS ahead of use: X(i+1) half in phase 1
+    // of iteration i-1 and half in phase 0 of iteration i, W(i+1) in phase 0 of iteration i.
+    // Within a group the MFMAs come first (their fragments were read a phase ago), then the
+    // group's share of the next substep's fragment reads (activation fragments before weight
+    // fragments: the order in which the next phase needs them), then one load.  Iterations
+    // -4..-1 only fill the pipeline.
+    constexpr int nX = XMODE == X_FUSED ? 2 * XS : XS;     // loads per wave per K tile
+    constexpr int nW = WS;
+    constexpr int kFrags = MF + NF;
     auto iteration = [&](int i, auto math_tag, auto r_tag) {
         constexpr bool MATH = decltype(math_tag)::value;
         constexpr int R = decltype(r_tag)::value;              // (i + 6) % 3: register set of tile i
@@ -313,22 +335,18 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
         // ---------------- phase 0 ----------------
         if (WMODE == W_I4) __builtin_amdgcn_s_waitcnt(waitcnt_vm(2 * nX + nW));     // W(i+1) registers are here
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            // MFMAs first: their fragments were read a phase ago, so the wait in front of them
-            // never includes the reads issued in this group.  The next substep's activation
-            // fragments are read in groups 0-1 and its weight fragments in groups 2-3, which is
-            // the order in which the next phase consumes them.
+        for (int g = 0; g < NF; ++g) {
             if (MATH) {
 #pragma unroll
-                for (int b = 0; b < 4; ++b)
+                for (int b = 0; b < MF; ++b)
                     acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[0][g], fx[0][b], acc[g][b], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
-                if (g < 2) { read_x(1, st, 1, 2 * g); read_x(1, st, 1, 2 * g + 1); }
-                else       { read_w(1, st, 1, 2 * g - 4); read_w(1, st, 1, 2 * g - 3); }
+#pragma unroll
+                for (int idx = g * kFrags / NF; idx < (g + 1) * kFrags / NF; ++idx) read_frag(1, st, 1, idx);
             }
             if (WMODE == W_I8) dma_w(i + 3, g);
             if (WMODE == W_I4) convert_w(i + 1, g, S1{});
-            if (XMODE == X_FUSED && g >= 2) convert_x(i + 1, g, S1{});                    // second half of X(i+1)
+            if (XMODE == X_FUSED && g >= XS / 2 && g < XS) convert_x(i + 1, g, S1{});   // second half of X(i+1)
             __builtin_amdgcn_sched_barrier(0);
         }
         if (WMODE == W_I4) regload_w(i + 3, S0{});
@@ -342,19 +360,19 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
         // ---------------- phase 1 ----------------
         if (XMODE == X_FUSED) __builtin_amdgcn_s_waitcnt(waitcnt_vm(2 * nW + nX));  // X(i+2) registers are here
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
+        for (int g = 0; g < NF; ++g) {
             if (MATH) {
 #pragma unroll
-                for (int b = 0; b < 4; ++b)
+                for (int b = 0; b < MF; ++b)
                     acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[1][g], fx[1][b], acc[g][b], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (i + 1 >= 0) {
-                if (g < 2) { read_x(0, (i + 1) & 3, 0, 2 * g); read_x(0, (i + 1) & 3, 0, 2 * g + 1); }
-                else       { read_w(0, (i + 1) & 3, 0, 2 * g - 4); read_w(0, (i + 1) & 3, 0, 2 * g - 3); }
+#pragma unroll
+                for (int idx = g * kFrags / NF; idx < (g + 1) * kFrags / NF; ++idx) read_frag(0, (i + 1) & 3, 0, idx);
             }
-            if (XMODE == X_PREQ) dma_x(i + 4, g);
-            if (XMODE == X_FUSED && g < 2) convert_x(i + 2, g, S2{});                     // first half of X(i+2)
+            if (XMODE == X_PREQ && g < XS) dma_x(i + 4, g);
+            if (XMODE == X_FUSED && g < XS / 2) convert_x(i + 2, g, S2{});              // first half of X(i+2)
             __builtin_amdgcn_sched_barrier(0);
         }
         if (XMODE == X_FUSED) regload_x(i + 4, S1{});
@@ -381,13 +399,15 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
     asm volatile("" ::: "memory");
 
     // ---- epilogue: D[i][j], i = 8*(v/4) + 4*(lane/32) + v%4 -> n, j = lane%32 -> m ----
+    // Each wave dequantizes its (BM/2) x (BN/2) block, stages it through its own LDS region as
+    // 16-bit values in [m][n] order and writes Y with 128-bit stores, BN contiguous bytes per row.
     const float s = qk.s;
     const bool has_bias = bias != nullptr;
-    char* epi = &lds[wave * kEpiBytes];
-    const int wn0 = n0 + wn * 128, wm0 = m0 + wm * 128;
+    char* epi = &lds[wave * T::kEpiBytes];
+    const int wn0 = n0 + wn * (BN / 2), wm0 = m0 + wm * (BM / 2);
     constexpr int kAccShift = WMODE == W_I4 ? 4 : 0;
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
+    for (int a = 0; a < NF; ++a) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int nl = a * 32 + 8 * g + 4 * fgrp;          // column within the wave's block
@@ -399,7 +419,7 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
                 bz[e] = has_bias ? bias[ne] : 0.0f;
             }
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
+            for (int b = 0; b < MF; ++b) {
                 const int ml = b * 32 + frow;
                 int av[4];
 #pragma unroll
@@ -407,7 +427,7 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
                 u32x2 pk;
                 pk[0] = S::pack(dequant(av[0], c[0], bz[0], has_bias), dequant(av[1], c[1], bz[1], has_bias));
                 pk[1] = S::pack(dequant(av[2], c[2], bz[2], has_bias), dequant(av[3], c[3], bz[3], has_bias));
-                *reinterpret_cast<u32x2*>(epi + ml * kEpiStride + nl * 2) = pk;
+                *reinterpret_cast<u32x2*>(epi + ml * T::kEpiStride + nl * 2) = pk;
                 if (acc_out) {
                     const int m = wm0 + ml, n = wn0 + nl;
 #pragma unroll
@@ -421,13 +441,15 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
     const bool vec_ok = (N & 7) == 0;
-    const int crow = lane >> 4, cchunk = lane & 15;            // 4 rows x 16 chunks of 16 B per pass
+    constexpr int kChunksPerRow = BN / 16;                      // 16-byte chunks in a wave-block row
+    constexpr int kRowsPerPass = 64 / kChunksPerRow;
+    const int crow = lane / kChunksPerRow, cchunk = lane % kChunksPerRow;
 #pragma unroll 4
-    for (int it = 0; it < 32; ++it) {
-        const int ml = it * 4 + crow;
+    for (int p = 0; p < (BM / 2) / kRowsPerPass; ++p) {
+        const int ml = p * kRowsPerPass + crow;
         const int m = wm0 + ml, n = wn0 + cchunk * 8;
         if (m >= M || n >= N) continue;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(epi + ml * kEpiStride + cchunk * 16);
+        const u32x4 v = *reinterpret_cast<const u32x4*>(epi + ml * T::kEpiStride + cchunk * 16);
         uint16_t* dst = y + (int64_t)m * N + n;
         if (vec_ok && n + 7 < N) {
             *reinterpret_cast<u32x4*>(dst) = v;
@@ -464,15 +486,49 @@ static bool choose_fused(int64_t M, int64_t N, int64_t K)
     return N <= kFusedMaxN;
 }
 
+template <int DT, int XMODE, int WMODE, int BM, int BN>
+static void launch_tiles(const void* xin, const void* wq, const float* s, const float* s_w, const float* bias,
+                         void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K, int a_bits, hipStream_t st)
+{
+    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
+    const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
+    linear_mfma_kernel<DT, XMODE, WMODE, BM, BN><<<grid, kGemmThreads, 0, st>>>(
+        xin, static_cast<const uint8_t*>(wq), s, s_w, bias, static_cast<uint16_t*>(y), acc_out,
+        (int)M, (int)N, (int)K, a_bits, tiles_m, tiles_n);
+}
+
+// Tile choice.  256x256 tiles are the most efficient per operation but a launch of T tiles takes
+// ceil(T / 256) rounds on 256 CUs; problems with few tiles use 128x256 or 128x128 tiles (the
+// latter two workgroups per CU) so that the chip is filled.  Relative costs per output element
+// (measured) are folded into `cost`.  Overridable with SASQ_STATIC_LINEAR_TILE=256|128x256|128.
+static int choose_tile(int64_t M, int64_t N)
+{
+    const char* e = getenv("SASQ_STATIC_LINEAR_TILE");
+    if (e) {
+        if (!strcmp(e, "256")) return 0;
+        if (!strcmp(e, "128x256")) return 1;
+        if (!strcmp(e, "128")) return 2;
+    }
+    auto rounds = [&](int bm, int bn, int slots) {
+        const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+        return (double)((tiles + slots - 1) / slots);
+    };
+    const double c0 = rounds(256, 256, 256) * 1.00;
+    const double c1 = rounds(128, 256, 256) * 0.50 * kCost128x256;
+    const double c2 = rounds(128, 128, 512) * 0.50 * kCost128x128;   // two co-resident workgroups share a CU
+    if (c0 <= c1 && c0 <= c2) return 0;
+    return c1 <= c2 ? 1 : 2;
+}
+
 template <int DT, int XMODE, int WMODE>
 static void launch_mfma(const void* xin, const void* wq, const float* s, const float* s_w, const float* bias,
                         void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K, int a_bits, hipStream_t st)
 {
-    const int tiles_m = (int)((M + kBM - 1) / kBM), tiles_n = (int)((N + kBN - 1) / kBN);
-    const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-    linear_mfma_kernel<DT, XMODE, WMODE><<<grid, kGemmThreads, 0, st>>>(
-        xin, static_cast<const uint8_t*>(wq), s, s_w, bias, static_cast<uint16_t*>(y), acc_out,
-        (int)M, (int)N, (int)K, a_bits, tiles_m, tiles_n);
+    switch (choose_tile(M, N)) {
+        case 0: launch_tiles<DT, XMODE, WMODE, 256, 256>(xin, wq, s, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
+        case 1: launch_tiles<DT, XMODE, WMODE, 128, 256>(xin, wq, s, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
+        default: launch_tiles<DT, XMODE, WMODE, 128, 128>(xin, wq, s, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
+    }
 }
 
 template <int DT>

@@ -119,6 +119,12 @@ def test_static_linear_full_size(cfg_name, proj_name, ws):
         torch.cuda.synchronize()
         assert torch.equal(y.view(torch.int16), y_alt.view(torch.int16)), path
     os.environ.pop("SASQ_STATIC_LINEAR_PATH", None)
+    for tile in ("256", "128x256", "128"):                            # and every tile size
+        os.environ["SASQ_STATIC_LINEAR_TILE"] = tile
+        B.sasq_static_linear(x, sd, wq, s_w, None, y_alt, wf, wsl)
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), y_alt.view(torch.int16)), tile
+    os.environ.pop("SASQ_STATIC_LINEAR_TILE", None)
     del y_alt
     acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
     xq = torch.empty((M, K), dtype=torch.int8, device="cuda")

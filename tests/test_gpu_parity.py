@@ -168,13 +168,14 @@ def test_quantize_weight(fmt, shape):
 
 
 # ---------------------------------------------------------------- static linear
-def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True, path=None):
+def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True, path=None, tile=None):
     """path: None (library's choice by shape), "twopass" or "fused" (activation quantize in a
-    separate pass / on load inside the GEMM)."""
-    if path is None:
-        os.environ.pop("SASQ_STATIC_LINEAR_PATH", None)
-    else:
-        os.environ["SASQ_STATIC_LINEAR_PATH"] = path
+    separate pass / on load inside the GEMM).  tile: None (by shape), "256", "128x256", "128"."""
+    for var, val in (("SASQ_STATIC_LINEAR_PATH", path), ("SASQ_STATIC_LINEAR_TILE", tile)):
+        if val is None:
+            os.environ.pop(var, None)
+        else:
+            os.environ[var] = val
     M, K = xb.shape
     N = wq.shape[0]
     wf = B.SASQ_W_INT8 if fmt == "int8" else B.SASQ_W_INT4_PACKED
@@ -187,6 +188,7 @@ def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True, path=None):
                          None if bias is None else torch.from_numpy(bias).cuda(), y, wf, wsl, acc, xq)
     torch.cuda.synchronize()
     os.environ.pop("SASQ_STATIC_LINEAR_PATH", None)
+    os.environ.pop("SASQ_STATIC_LINEAR_TILE", None)
     return to_bits(y), (acc.cpu().numpy() if want_debug else None), (xq.cpu().numpy() if want_debug else None)
 
 
@@ -198,10 +200,11 @@ LINEAR_SHAPES = [
 ]
 
 
+@pytest.mark.parametrize("tile", ["256", "128x256", "128"])
 @pytest.mark.parametrize("path", ["twopass", "fused"])
 @pytest.mark.parametrize("dtype,fmt", [("f16", "int8"), ("bf16", "int8"), ("bf16", "int4"), ("f16", "int4")])
 @pytest.mark.parametrize("shape", LINEAR_SHAPES)
-def test_static_linear(shape, dtype, fmt, path):
+def test_static_linear(shape, dtype, fmt, path, tile):
     M, N, K = shape
     xb = wl.random_bits(12, f"lx{shape}{dtype}", (M, K), dtype, gain=2.0)
     w = wl.random_f32(12, f"lw{shape}", (N, K), 0.02)
@@ -210,11 +213,11 @@ def test_static_linear(shape, dtype, fmt, path):
     s = np.float32(oracle.absmax_scale(xb, 8, dtype) / 3)
     for b in (None, bias):
         ref = oracle.static_linear(xb, s, wq, s_w, b, 8, fmt, dtype)
-        y, acc, xq = run_linear(xb, s, wq, s_w, b, fmt, dtype, path=path)
+        y, acc, xq = run_linear(xb, s, wq, s_w, b, fmt, dtype, path=path, tile=tile)
         assert np.array_equal(xq, ref["xq"]), "activation codes"
         assert np.array_equal(acc, ref["acc"]), "int32 accumulators"
         assert_same_values(y, ref["y"], dtype, "Y")
-        y2, _, _ = run_linear(xb, s, wq, s_w, b, fmt, dtype, want_debug=False, path=path)
+        y2, _, _ = run_linear(xb, s, wq, s_w, b, fmt, dtype, want_debug=False, path=path, tile=tile)
         assert np.array_equal(y2, y)
 
 
