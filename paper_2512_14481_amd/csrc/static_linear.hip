@@ -143,11 +143,11 @@ __device__ __forceinline__ int swz64(int r) { return ((r >> 1) & 3) ^ ((r >> 3) 
 // 8 activation row-panels and 4 weight row-panels in that L2.
 __device__ __forceinline__ bool tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn)
 {
+    constexpr int PN = 4;                              // n-tiles per panel (2..8 measured within noise of each other)
     const int total = tiles_m * tiles_n;
     const int per = (total + 7) >> 3;
     const int logical = (bid & 7) * per + (bid >> 3);
     if (logical >= total) return false;
-    constexpr int PN = 4;                              // n-tiles per panel
     const int panel = logical / (tiles_m * PN);
     const int in = logical - panel * tiles_m * PN;
     const int width = min(PN, tiles_n - panel * PN);   // last panel may be narrower
