@@ -123,8 +123,8 @@ def main():
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
-        sys.exit("bench.py: this build is single-GPU; --gpus must be 1 (how the path would shard over "
-                 "GPUs is described in DESIGN.md, nothing multi-GPU is implemented)")
+        sys.exit("bench.py: this build is single-GPU; --gpus must be 1 (the path shards by token rows with "
+                 "one tiny all-gather for ds, but nothing multi-GPU is implemented)")
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
 
