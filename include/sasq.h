@@ -71,7 +71,7 @@ int sasq_version(void);
 int sasq_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Fake quantization, forward (Sec. 4.2 "fake quantization operators"; Sec. 3, Eq. 1;
+ * Fake quantization, forward (the operator Sec. 4.2 inserts before each linear; Sec. 3, Eq. 1;
  * dequantisation X' = S_x * X_int, Sec. 4.3, Eq. 5):
  *     q = clamp(round(x / s), -2^(bits-1), 2^(bits-1) - 1),   y = s * q.
  *   x      [rows, cols] device, 16-bit `dt`, read only
@@ -162,7 +162,9 @@ size_t sasq_static_linear_workspace(int64_t M, int64_t N, int64_t K, sasq_wfmt w
  *   K        multiple of 2 for int4.  Any M, N, K > 0 is accepted; the MFMA path is taken when
  *            K is a multiple of 64, other shapes use a scalar kernel.
  *   M*K, N*K, M*N must each be < 2^40; |acc| cannot overflow for K <= 131071.
- *   workspace  >= sasq_static_linear_workspace(M, N, K, wf) bytes (NULL allowed when that is 0)
+ *   workspace  >= sasq_static_linear_workspace(M, N, K, wf) bytes (NULL allowed when that is 0);
+ *              holds the int8 activation codes in a library-internal blocked order between the
+ *              quantize pass and the GEMM; contents after the call are unspecified
  */
 int sasq_static_linear(const void* x, const float* s, const void* wq, const float* s_w,
                        const float* bias, void* y, int32_t* acc_out, int8_t* xq_out,
@@ -171,7 +173,7 @@ int sasq_static_linear(const void* x, const float* s, const void* wq, const floa
 
 /*
  * Quantize frozen weights, symmetric, one factor per output channel (Sec. 3, Eq. 1 applied to
- * each row of W[N,K]; "the quantization granularity of weights is always per-channel", Sec. 5.1):
+ * each row of W[N,K]; Sec. 5.1 fixes the weight granularity to per output channel):
  *     s_w[n]  = fl32(max_k |W[n,k]| / Qp)     (1 if the row is all zero),  Qp = 127 or 7
  *     Wq[n,k] = clamp(round(W[n,k] / s_w[n]), -Qp-1, Qp)     (same rounding rule as activations)
  *   w    [N, K] device fp32;  wq: [N, K] int8 or [N, K/2] packed int4 (K even);  s_w [N] fp32

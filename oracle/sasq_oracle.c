@@ -299,7 +299,7 @@ int sasq_oracle_static_linear(const uint16_t* x, float s, const uint8_t* wq, con
 
 /*
  * Frozen-weight quantization, symmetric, one scale per output channel (row of W[N,K])
- * (Sec. 3, Eq. 1 applied per row; "granularity of weights is always per-channel", Sec. 5.1):
+ * (Sec. 3, Eq. 1 applied per row; Sec. 5.1 fixes weights to one factor per output channel):
  *   s_w[n] = fl32(max_k |W[n,k]| / Qp)   (1 if the row is all zero)
  *   Wq[n,k] = clamp(round(W[n,k] / s_w[n]), Qn, Qp), round as for activations
  * bits = 8 -> int8 [N,K];  bits = 4 -> packed [N,K/2].

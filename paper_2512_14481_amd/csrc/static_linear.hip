@@ -19,14 +19,22 @@ constexpr int kWaitLgkm0 = 0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8);
 // Activation quantize pre-pass: xq[m,k] = clamp(round(X[m,k]/s))  (Sec. 3, Eq. 1), int8.
 // PERM8: store each aligned group of 8 codes as (k0,k2,k4,k6,k1,k3,k5,k7) -- the K order in
 // which packed int4 weights unpack -- instead of natural order.
+// TILED: store in the GEMM's staging layout instead of row-major: the matrix is cut into blocks
+// of 16 rows x 64 K-bytes, block (rb, kb) is the 1 KB at ((rb * K/64) + kb) * 1024, and inside a
+// block the 16-byte chunk c of row r sits at 16 * (4r + (c ^ swz64(r))) -- byte for byte what one
+// wave's direct-to-LDS load deposits, so the GEMM fetches each block as one contiguous 1 KB read
+// (full cache lines) instead of sixteen 64-byte row pieces.  Needs K % 64 == 0.
 // ---------------------------------------------------------------------------------------------
-template <int DT, bool PERM8>
+__device__ __forceinline__ int swz64(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
+
+template <int DT, bool PERM8, bool TILED>
 __global__ __launch_bounds__(256) void quantize_act_kernel(
     const u32x4* __restrict__ x, const float* __restrict__ s_ptr, u32x2* __restrict__ xq,
-    int64_t nvec, int64_t n, int bits)
+    int64_t nvec, int64_t n, int K, int bits)
 {
     using S = Store16<DT>;
     const QConst k = make_qconst(*s_ptr, bits);
+    const int kvec = K >> 3;                      // 8-element vectors per row
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * 256) {
         u32x4 v = x[i];
         float c[8];
@@ -38,9 +46,18 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(
         u32x2 o;
         if (PERM8) { o[0] = pack_codes4(c[0], c[2], c[4], c[6]); o[1] = pack_codes4(c[1], c[3], c[5], c[7]); }
         else       { o[0] = pack_codes4(c[0], c[1], c[2], c[3]); o[1] = pack_codes4(c[4], c[5], c[6], c[7]); }
-        xq[i] = o;
+        if (TILED) {
+            const int64_t m = i / kvec;
+            const int k0 = (int)(i - m * kvec) << 3;
+            const int r = (int)(m & 15), ch = (k0 & 63) >> 4;
+            const int64_t blk = (m >> 4) * (K >> 6) + (k0 >> 6);
+            const int64_t off = blk * 1024 + ((4 * r + (ch ^ swz64(r))) << 4) + (k0 & 15);
+            *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(xq) + off) = o;
+        } else {
+            xq[i] = o;
+        }
     }
-    if (!PERM8 && blockIdx.x == 0 && threadIdx.x < (unsigned)(n - nvec * 8)) {
+    if (!PERM8 && !TILED && blockIdx.x == 0 && threadIdx.x < (unsigned)(n - nvec * 8)) {
         int64_t i = nvec * 8 + threadIdx.x;
         reinterpret_cast<int8_t*>(xq)[i] =
             (int8_t)code_of(quantize(S::one(reinterpret_cast<const uint16_t*>(x)[i]), k));
@@ -135,8 +152,6 @@ struct Tile {
     static constexpr int kWavesPerSimd = (MF * NF * 16 <= 64) ? 2 : 1;  // 128x128 tiles: two workgroups per CU
 };
 
-__device__ __forceinline__ int swz64(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
-
 // XCD-aware tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2:
 // give every XCD a contiguous range of logical tile ids, and number the tiles so that 32
 // consecutive ids (what one XCD's 32 CUs hold at a time) form an 8 (m) x 4 (n) block that shares
@@ -206,18 +221,19 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
     const int lchunk = (lane & 3) ^ (((lane >> 3) & 3) ^ ((lane >> 5) & 1));
     const int8_t* gx[XS];
     const int8_t* gw[WS];
+    // pre-quantized activations are stored tiled (see quantize_act_kernel): slab j of wave w is the
+    // contiguous 1 KB block (row block, K tile); row blocks past the edge re-read the last block
+    const int last_rb = (M - 1) >> 4;
 #pragma unroll
-    for (int j = 0; j < XS; ++j) {
-        const int mr = min(m0 + (4 * j + wave) * 16 + lrow, M - 1);     // rows past the edge re-read the last row
-        gx[j] = static_cast<const int8_t*>(xin) + (int64_t)mr * K + lchunk * 16;
-    }
+    for (int j = 0; j < XS; ++j)
+        gx[j] = static_cast<const int8_t*>(xin) + (int64_t)min((m0 >> 4) + 4 * j + wave, last_rb) * KT * 1024 + lane * 16;
 #pragma unroll
     for (int j = 0; j < WS; ++j) {
         const int nr = min(n0 + (4 * j + wave) * 16 + lrow, N - 1);
         gw[j] = reinterpret_cast<const int8_t*>(wq) + (int64_t)nr * K + lchunk * 16;
     }
     auto dma_x = [&](int Tk, int j) {
-        __builtin_amdgcn_global_load_lds((glb_ptr_t)(gx[j] + eff_tile(Tk) * kBK),
+        __builtin_amdgcn_global_load_lds((glb_ptr_t)(gx[j] + eff_tile(Tk) * 1024),
                                          (lds_ptr_t)(stage_ptr(stage_of(Tk), 0) + (4 * j + wave) * 1024), 16, 0, 0);
     };
     auto dma_w = [&](int Tk, int j) {
@@ -540,7 +556,7 @@ static void run_linear(const void* x, const float* s, const void* wq, const floa
     int64_t qb = (nvec + 255) / 256;
     const int qgrid = (int)(qb < 1 ? 1 : (qb > 65536 ? 65536 : qb));
     auto X = static_cast<const u32x4*>(x);
-    if (xq_out) quantize_act_kernel<DT, false><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_out), nvec, n, a_bits);
+    if (xq_out) quantize_act_kernel<DT, false, false><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_out), nvec, n, (int)K, a_bits);
 
     const bool mfma_ok = (K % kBK) == 0;
     const bool int4 = wf == SASQ_W_INT4_PACKED;
@@ -553,15 +569,15 @@ static void run_linear(const void* x, const float* s, const void* wq, const floa
         } else {
             // pass 1: quantize the activations once with the fixed scale (no reduction over X anywhere)
             if (int4) {
-                quantize_act_kernel<DT, true><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_ws), nvec, n, a_bits);
+                quantize_act_kernel<DT, true, true><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_ws), nvec, n, (int)K, a_bits);
                 launch_mfma<DT, X_PREQ, W_I4>(xq_ws, wq, s, s_w, bias, y, acc_out, M, N, K, a_bits, st);
             } else {
-                quantize_act_kernel<DT, false><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_ws), nvec, n, a_bits);
+                quantize_act_kernel<DT, false, true><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_ws), nvec, n, (int)K, a_bits);
                 launch_mfma<DT, X_PREQ, W_I8>(xq_ws, wq, s, s_w, bias, y, acc_out, M, N, K, a_bits, st);
             }
         }
     } else {
-        quantize_act_kernel<DT, false><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_ws), nvec, n, a_bits);
+        quantize_act_kernel<DT, false, false><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_ws), nvec, n, (int)K, a_bits);
         const int64_t blocks = (M * N + 255) / 256;
         auto W = static_cast<const uint8_t*>(wq);
         auto Y = static_cast<uint16_t*>(y);
@@ -578,7 +594,7 @@ extern "C" size_t sasq_static_linear_workspace(int64_t M, int64_t N, int64_t K, 
 {
     (void)N; (void)wf;
     if (M <= 0 || K <= 0) return 0;
-    return round_up((size_t)M * (size_t)K, 256);              // int8 activation codes of the two-pass path
+    return round_up(round_up((size_t)M, 16) * (size_t)K, 256);   // int8 activation codes of the two-pass path, rows padded to 16
 }
 
 extern "C" int sasq_static_linear(const void* x, const float* s, const void* wq, const float* s_w,
