@@ -56,6 +56,13 @@ class Projection:
         self.s_w = torch.empty(self.N, dtype=torch.float32, device="cuda")
         B.sasq_quantize_weight(w, self.wq, self.s_w, wf)
         del w
+        # frozen weights are re-arranged once at set-up into the GEMM's blocked format (SASQ_BENCH_ROWMAJOR=1
+        # keeps the row-major interchange format instead)
+        if self.K % 64 == 0 and not os.environ.get("SASQ_BENCH_ROWMAJOR"):
+            wfb = B.SASQ_W_INT8_BLOCKED if wf == B.SASQ_W_INT8 else B.SASQ_W_INT4_BLOCKED
+            packed = torch.empty(B.sasq_packed_weight_bytes(self.N, self.K, wfb), dtype=torch.uint8, device="cuda")
+            B.sasq_pack_weight(self.wq, packed, self.N, self.K, wf)
+            self.wq, self.wf = packed, wfb
         self.dy = dev16(wl.upstream_grad(cfg, proj.name), cfg.dtype)
         self.s = torch.empty(1, dtype=torch.float32, device="cuda")
         B.sasq_absmax_scale(x, self.s, ws_small, 8)           # s0 = absmax / 127

@@ -55,7 +55,12 @@ typedef enum {
 } sasq_status;
 
 typedef enum { SASQ_F16 = 0, SASQ_BF16 = 1 } sasq_dtype;            /* activation / output type */
-typedef enum { SASQ_W_INT8 = 0, SASQ_W_INT4_PACKED = 1 } sasq_wfmt; /* frozen weight storage    */
+typedef enum {                       /* frozen weight storage                                    */
+    SASQ_W_INT8 = 0,                 /* [N, K] int8, row-major                                   */
+    SASQ_W_INT4_PACKED = 1,          /* [N, K/2] bytes, row-major, two codes per byte            */
+    SASQ_W_INT8_BLOCKED = 2,         /* output of sasq_pack_weight from SASQ_W_INT8              */
+    SASQ_W_INT4_BLOCKED = 3          /* output of sasq_pack_weight from SASQ_W_INT4_PACKED       */
+} sasq_wfmt;
 
 /* Human-readable name of a status code (static storage, host pointer). */
 const char* sasq_status_string(int status);
@@ -153,7 +158,11 @@ size_t sasq_static_linear_workspace(int64_t M, int64_t N, int64_t K, sasq_wfmt w
  *   x        [M, K] device 16-bit `dt`
  *   s        device fp32 scalar
  *   wq       [N, K] device int8 (SASQ_W_INT8), or [N, K/2] bytes (SASQ_W_INT4_PACKED): element k
- *            even in the low nibble, k odd in the high nibble, two's complement, range [-8, 7]
+ *            even in the low nibble, k odd in the high nibble, two's complement, range [-8, 7];
+ *            or the sasq_packed_weight_bytes(N, K, wf) bytes sasq_pack_weight made of either
+ *            (SASQ_W_INT8_BLOCKED, SASQ_W_INT4_BLOCKED: same codes, same results bit for bit,
+ *            arranged so that the GEMM reads them in whole cache lines; the fast path for
+ *            frozen weights; K must be a multiple of 64, else SASQ_ERR_SHAPE)
  *   s_w      [N] device fp32, one factor per output channel
  *   bias     [N] device fp32 or NULL
  *   y        [M, N] device 16-bit `dt`, written
@@ -180,6 +189,26 @@ int sasq_static_linear(const void* x, const float* s, const void* wq, const floa
  */
 int sasq_quantize_weight(const float* w, void* wq, float* s_w, int64_t N, int64_t K,
                          sasq_wfmt wf, void* stream);
+
+/*
+ * Re-arrange quantized frozen weights for the GEMM (a set-up step, once per weight matrix; the
+ * weights of static inference never change, Sec. 3).  A pure permutation of the codes:
+ *   SASQ_W_INT8 -> SASQ_W_INT8_BLOCKED: 1 KB blocks of 16 rows x 64 K-bytes, block (n/16, k/64) at
+ *     ((n/16) * K/64 + k/64) * 1024; inside, the 16-byte chunk c of row r at
+ *     16 * (4r + (c ^ ((r >> 1) & 3) ^ ((r >> 3) & 1))).
+ *   SASQ_W_INT4_PACKED -> SASQ_W_INT4_BLOCKED: 1 KB blocks of 32 rows x 64 k, block (n/32, k/64) at
+ *     ((n/32) * K/64 + k/64) * 1024; the 16 codes k = 64*(k/64) + 32*kk + 16*g + (0..15) of row r
+ *     are the 8 bytes at 512*kk + 256*g + 8*r: byte b of the first four holds code b (low nibble)
+ *     and code 4+b (high nibble), byte b of the last four codes 8+b and 12+b.
+ * Rows past N in the last block are zero.
+ *   wq       device, row-major codes in format wf_src (SASQ_W_INT8 or SASQ_W_INT4_PACKED)
+ *   packed   device, sasq_packed_weight_bytes(N, K, blocked format) bytes, written; not wq
+ *   K        multiple of 64 (SASQ_ERR_SHAPE otherwise: use the row-major format for such shapes)
+ * sasq_packed_weight_bytes is a pure host function; it returns 0 for shapes or formats that have
+ * no blocked form.
+ */
+size_t sasq_packed_weight_bytes(int64_t N, int64_t K, sasq_wfmt wf);
+int sasq_pack_weight(const void* wq, void* packed, int64_t N, int64_t K, sasq_wfmt wf_src, void* stream);
 
 /* Bytes of workspace sasq_absmax_scale needs (pure function, host only). */
 size_t sasq_absmax_scale_workspace(int64_t rows, int64_t cols);

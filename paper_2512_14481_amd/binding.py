@@ -16,7 +16,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libsasq.so")
 
 SASQ_F16, SASQ_BF16 = 0, 1
-SASQ_W_INT8, SASQ_W_INT4_PACKED = 0, 1
+SASQ_W_INT8, SASQ_W_INT4_PACKED, SASQ_W_INT8_BLOCKED, SASQ_W_INT4_BLOCKED = 0, 1, 2, 3
 
 _DT = {torch.float16: SASQ_F16, torch.bfloat16: SASQ_BF16}
 
@@ -58,6 +58,9 @@ def _lib() -> ctypes.CDLL:
         L.sasq_static_linear_workspace.argtypes = [i64, i64, i64, i32]
         L.sasq_static_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, sz, vp]
         L.sasq_quantize_weight.argtypes = [vp, vp, vp, i64, i64, i32, vp]
+        L.sasq_packed_weight_bytes.restype = sz
+        L.sasq_packed_weight_bytes.argtypes = [i64, i64, i32]
+        L.sasq_pack_weight.argtypes = [vp, vp, i64, i64, i32, vp]
         L.sasq_absmax_scale_workspace.restype = sz
         L.sasq_absmax_scale_workspace.argtypes = [i64, i64]
         L.sasq_absmax_scale.argtypes = [vp, vp, i64, i64, i32, i32, vp, sz, vp]
@@ -192,9 +195,14 @@ def sasq_static_linear(x: torch.Tensor, s: torch.Tensor, wq: torch.Tensor, s_w: 
     if wq.dtype not in (torch.int8, torch.uint8):
         raise TypeError("wq must be int8 (or uint8 bytes for packed int4)")
     M, K = x.shape
-    N = wq.shape[0]
-    if wq.shape[1] != (K if wf == SASQ_W_INT8 else K // 2) or tuple(y.shape) != (M, N) or y.dtype != x.dtype:
-        raise ValueError("shape mismatch between x, wq and y")
+    if wf in (SASQ_W_INT8_BLOCKED, SASQ_W_INT4_BLOCKED):
+        N = y.shape[1]
+        if wq.numel() != sasq_packed_weight_bytes(N, K, wf) or y.shape[0] != M or y.dtype != x.dtype:
+            raise ValueError("shape mismatch between x, the packed weights and y")
+    else:
+        N = wq.shape[0]
+        if wq.shape[1] != (K if wf == SASQ_W_INT8 else K // 2) or tuple(y.shape) != (M, N) or y.dtype != x.dtype:
+            raise ValueError("shape mismatch between x, wq and y")
     if s_w.numel() != N or (bias is not None and bias.numel() != N):
         raise ValueError("s_w / bias must have N elements")
     wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
@@ -207,6 +215,19 @@ def sasq_quantize_weight(w: torch.Tensor, wq: torch.Tensor, s_w: torch.Tensor, w
     _want(w, torch.float32, "w"); _want(s_w, torch.float32, "s_w")
     N, K = w.shape
     _check(_lib().sasq_quantize_weight(_ptr(w), _ptr(wq), _ptr(s_w), N, K, wf, _stream()), "sasq_quantize_weight")
+
+
+def sasq_packed_weight_bytes(N: int, K: int, wf: int) -> int:
+    return int(_lib().sasq_packed_weight_bytes(N, K, wf))
+
+
+def sasq_pack_weight(wq: torch.Tensor, packed: torch.Tensor, N: int, K: int, wf_src: int = SASQ_W_INT8) -> None:
+    blocked = SASQ_W_INT8_BLOCKED if wf_src == SASQ_W_INT8 else SASQ_W_INT4_BLOCKED
+    if wq.numel() != (N * K if wf_src == SASQ_W_INT8 else N * (K // 2)):
+        raise ValueError("wq does not hold N x K codes in the source format")
+    if packed.numel() * packed.element_size() != sasq_packed_weight_bytes(N, K, blocked):
+        raise ValueError("packed must have sasq_packed_weight_bytes(N, K, blocked format) bytes")
+    _check(_lib().sasq_pack_weight(_ptr(wq), _ptr(packed), N, K, wf_src, _stream()), "sasq_pack_weight")
 
 
 def sasq_absmax_scale_workspace(rows: int, cols: int) -> int:

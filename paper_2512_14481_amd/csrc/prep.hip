@@ -1,4 +1,5 @@
-// Set-up operations: workspace initialisation, frozen-weight quantization, absmax initial scale.
+// Set-up operations: workspace initialisation, frozen-weight quantization and re-arrangement,
+// absmax initial scale.
 #include "sasq_device.h"
 
 namespace sasq {
@@ -52,6 +53,52 @@ __global__ __launch_bounds__(kPrepThreads) void quantize_weight_kernel(
         for (int64_t k = threadIdx.x; k < K; k += kPrepThreads)
             out[k] = (uint8_t)(code_of(quantize(row[k], kc)) & 0xFF);
     }
+}
+
+// Re-arrange row-major int8 weight codes [N,K] into the GEMM's operand blocks: 16 rows x 64
+// K-bytes per 1 KB block, block (nb, kb) at (nb * K/64 + kb) * 1024, the 16-byte chunk c of row
+// r at 16 * (4r + (c ^ swz(r))), swz(r) = ((r >> 1) & 3) ^ ((r >> 3) & 1).  One thread per
+// destination chunk; rows past N are zero.
+__global__ __launch_bounds__(kPrepThreads) void pack_weight_i8_kernel(
+    const uint8_t* __restrict__ wq, u32x4* __restrict__ out, int64_t N, int64_t K, int64_t nchunks)
+{
+    const int64_t i = (int64_t)blockIdx.x * kPrepThreads + threadIdx.x;
+    if (i >= nchunks) return;
+    const int64_t blk = i >> 6, KT = K >> 6;
+    const int sl = (int)(i & 63), r = sl >> 2;
+    const int ch = (sl & 3) ^ (((r >> 1) & 3) ^ ((r >> 3) & 1));
+    const int64_t n = (blk / KT) * 16 + r, k0 = (blk % KT) * 64 + ch * 16;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (n < N) v = *reinterpret_cast<const u32x4*>(wq + n * K + k0);
+    out[i] = v;
+}
+
+// Re-arrange row-major packed int4 weight codes [N,K/2] into 1 KB blocks of 32 rows x 64 k:
+// block (nb, kb) at (nb * K/64 + kb) * 1024; the 16 codes k = 64 kb + 32 kk + 16 g + (0..15) of
+// row r are the 8 bytes at 512 kk + 256 g + 8 r; in them byte b of the first dword holds code b
+// (low nibble) and 4 + b (high nibble), byte b of the second dword codes 8 + b and 12 + b.
+// One thread per 8 destination bytes; rows past N are zero.
+__global__ __launch_bounds__(kPrepThreads) void pack_weight_i4_kernel(
+    const uint8_t* __restrict__ wq, u32x2* __restrict__ out, int64_t N, int64_t K, int64_t nslots)
+{
+    const int64_t i = (int64_t)blockIdx.x * kPrepThreads + threadIdx.x;
+    if (i >= nslots) return;
+    const int64_t blk = i >> 7, KT = K >> 6;
+    const int sl = (int)(i & 127), kk = sl >> 6, g = (sl >> 5) & 1, r = sl & 31;
+    const int64_t n = (blk / KT) * 32 + r, k0 = (blk % KT) * 64 + 32 * kk + 16 * g;
+    u32x2 o = {0u, 0u};
+    if (n < N) {
+        const u32x2 sv = *reinterpret_cast<const u32x2*>(wq + n * (K / 2) + k0 / 2);
+        const uint64_t src = (uint64_t)sv[0] | ((uint64_t)sv[1] << 32);     // code j at bits 4j
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const uint32_t c0 = (uint32_t)(src >> (4 * b)) & 15u, c4 = (uint32_t)(src >> (4 * (4 + b))) & 15u;
+            const uint32_t c8 = (uint32_t)(src >> (4 * (8 + b))) & 15u, c12 = (uint32_t)(src >> (4 * (12 + b))) & 15u;
+            o[0] |= (c0 | (c4 << 4)) << (8 * b);
+            o[1] |= (c8 | (c12 << 4)) << (8 * b);
+        }
+    }
+    out[i] = o;
 }
 
 // max |x| over a flat 16-bit tensor: magnitudes of finite values and infinities order like their
@@ -163,6 +210,34 @@ extern "C" int sasq_quantize_weight(const float* w, void* wq, float* s_w, int64_
         quantize_weight_kernel<false><<<(int)N, kPrepThreads, 0, st>>>(w, static_cast<uint8_t*>(wq), s_w, K);
     else
         quantize_weight_kernel<true><<<(int)N, kPrepThreads, 0, st>>>(w, static_cast<uint8_t*>(wq), s_w, K);
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+extern "C" size_t sasq_packed_weight_bytes(int64_t N, int64_t K, sasq_wfmt wf)
+{
+    if (N <= 0 || K <= 0 || (K % 64) != 0) return 0;
+    if (wf == SASQ_W_INT8_BLOCKED) return (size_t)((N + 15) / 16 * 16) * (size_t)K;
+    if (wf == SASQ_W_INT4_BLOCKED) return (size_t)((N + 31) / 32 * 32) * (size_t)(K / 2);
+    return 0;
+}
+
+extern "C" int sasq_pack_weight(const void* wq, void* packed, int64_t N, int64_t K, sasq_wfmt wf_src, void* stream)
+{
+    if (!wq || !packed) return SASQ_ERR_NULL;
+    if (N <= 0 || K <= 0 || N > 0x7FFFFFFF || N > (INT64_C(1) << 40) / K) return SASQ_ERR_SHAPE;
+    if (wf_src != SASQ_W_INT8 && wf_src != SASQ_W_INT4_PACKED) return SASQ_ERR_UNSUPPORTED;
+    if (K % 64) return SASQ_ERR_SHAPE;
+    if (!aligned16(wq) || !aligned16(packed)) return SASQ_ERR_ALIGN;
+    hipStream_t st = as_stream(stream);
+    if (wf_src == SASQ_W_INT8) {
+        const int64_t nchunks = (int64_t)(sasq_packed_weight_bytes(N, K, SASQ_W_INT8_BLOCKED) / 16);
+        pack_weight_i8_kernel<<<(unsigned)((nchunks + kPrepThreads - 1) / kPrepThreads), kPrepThreads, 0, st>>>(
+            static_cast<const uint8_t*>(wq), static_cast<u32x4*>(packed), N, K, nchunks);
+    } else {
+        const int64_t nslots = (int64_t)(sasq_packed_weight_bytes(N, K, SASQ_W_INT4_BLOCKED) / 8);
+        pack_weight_i4_kernel<<<(unsigned)((nslots + kPrepThreads - 1) / kPrepThreads), kPrepThreads, 0, st>>>(
+            static_cast<const uint8_t*>(wq), static_cast<u32x2*>(packed), N, K, nslots);
+    }
     return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
 }
 

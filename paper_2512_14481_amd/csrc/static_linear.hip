@@ -183,8 +183,18 @@ __device__ __forceinline__ bool tile_of_block(int bid, int tiles_m, int tiles_n,
 //            within every group of 8 consecutive k the byte order is (0,2,4,6,1,3,5,7); the
 //            activation bytes are stored in the same order (any K order common to both operands
 //            gives the same dot product).
+//   WMODE 2: int8 weights pre-arranged by sasq_pack_weight in the same 1 KB blocks of 16 rows x 64
+//            K-bytes as the staged activations: each direct load is one contiguous 1 KB.
+//   WMODE 3: int4 weights pre-arranged by sasq_pack_weight: they go L2 -> LDS still packed (half
+//            the bytes) and are unpacked in registers between the LDS fragment read and the MFMA
+//            (4 operations per 32x16 fragment).  A 1 KB block holds 32 rows x 64 k; the 8 bytes of
+//            (K-substep kk, lane group g, row r) sit at 512 kk + 256 g + 8 r, which is exactly
+//            the order in which the 64 lanes of a fragment read fetch them (conflict-free), and
+//            their nibbles are ordered so that the two mask/shift operations per dword yield
+//            natural K order (byte b of the first dword: k = b low, k = 4 + b high; second dword
+//            likewise for k = 8.., 12..), so the activation bytes stay in natural order.
 enum { X_PREQ = 0, X_FUSED = 1 };
-enum { W_I8 = 0, W_I4 = 1 };
+enum { W_I8 = 0, W_I4 = 1, W_I8B = 2, W_I4B = 3 };
 
 template <int DT, int XMODE, int WMODE, int BM, int BN>
 __global__ __launch_bounds__(kGemmThreads)
@@ -229,15 +239,22 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
         gx[j] = static_cast<const int8_t*>(xin) + (int64_t)min((m0 >> 4) + 4 * j + wave, last_rb) * KT * 1024 + lane * 16;
 #pragma unroll
     for (int j = 0; j < WS; ++j) {
-        const int nr = min(n0 + (4 * j + wave) * 16 + lrow, N - 1);
-        gw[j] = reinterpret_cast<const int8_t*>(wq) + (int64_t)nr * K + lchunk * 16;
+        if (WMODE == W_I8B) {          // blocks of 16 rows
+            gw[j] = reinterpret_cast<const int8_t*>(wq) + (int64_t)min((n0 >> 4) + 4 * j + wave, (N - 1) >> 4) * KT * 1024 + lane * 16;
+        } else if (WMODE == W_I4B) {   // blocks of 32 rows (only the first WS/2 are used)
+            gw[j] = reinterpret_cast<const int8_t*>(wq) + (int64_t)min((n0 >> 5) + 4 * j + wave, (N - 1) >> 5) * KT * 1024 + lane * 16;
+        } else {
+            const int nr = min(n0 + (4 * j + wave) * 16 + lrow, N - 1);
+            gw[j] = reinterpret_cast<const int8_t*>(wq) + (int64_t)nr * K + lchunk * 16;
+        }
     }
+    constexpr int kWTileStep = (WMODE == W_I8B || WMODE == W_I4B) ? 1024 : kBK;   // bytes from one K tile to the next
     auto dma_x = [&](int Tk, int j) {
         __builtin_amdgcn_global_load_lds((glb_ptr_t)(gx[j] + eff_tile(Tk) * 1024),
                                          (lds_ptr_t)(stage_ptr(stage_of(Tk), 0) + (4 * j + wave) * 1024), 16, 0, 0);
     };
     auto dma_w = [&](int Tk, int j) {
-        __builtin_amdgcn_global_load_lds((glb_ptr_t)(gw[j] + eff_tile(Tk) * kBK),
+        __builtin_amdgcn_global_load_lds((glb_ptr_t)(gw[j] + eff_tile(Tk) * kWTileStep),
                                          (lds_ptr_t)(stage_ptr(stage_of(Tk), 1) + (4 * j + wave) * 1024), 16, 0, 0);
     };
 
@@ -315,8 +332,23 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
     i32x4 fx[2][MF], fw[2][NF];
     // fragment `idx` of a K-substep: the MF activation fragments first, then the NF weight ones
     auto read_frag = [&](int set, int st, int kk, int idx) {
-        if (idx < MF) fx[set][idx] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 0) + xbase + idx * 32 * kBK + foff[kk]);
-        else          fw[set][idx - MF] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 1) + wbase + (idx - MF) * 32 * kBK + foff[kk]);
+        if (idx < MF) {
+            fx[set][idx] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 0) + xbase + idx * 32 * kBK + foff[kk]);
+        } else if (WMODE == W_I4B) {
+            const u32x2 p = *reinterpret_cast<const u32x2*>(stage_ptr(st, 1) + (wn * (BN / 64) + (idx - MF)) * 1024 + kk * 512 + lane * 8);
+            fw[set][idx - MF][0] = (int)p[0];
+            fw[set][idx - MF][1] = (int)p[1];
+        } else {
+            fw[set][idx - MF] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 1) + wbase + (idx - MF) * 32 * kBK + foff[kk]);
+        }
+    };
+    // the MFMA's weight operand: as read, or (pre-arranged int4) unpacked here
+    auto wfrag = [&](int set, int g) -> i32x4 {
+        if (WMODE == W_I4B) {
+            const uint32_t p0 = (uint32_t)fw[set][g][0], p1 = (uint32_t)fw[set][g][1];
+            return i32x4{(int)((p0 << 4) & 0xF0F0F0F0u), (int)(p0 & 0xF0F0F0F0u), (int)((p1 << 4) & 0xF0F0F0F0u), (int)(p1 & 0xF0F0F0F0u)};
+        }
+        return fw[set][g];
     };
 
     i32x16 acc[NF][MF];   // [n tile][m tile]
@@ -334,13 +366,49 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
     // below is one s_waitcnt vmcnt(n) with n = loads issued later (memory loads return in issue
     // order).  Register-path tiles are converted into LDS ahead of use: X(i+1) half in phase 1
     // of iteration i-1 and half in phase 0 of iteration i, W(i+1) in phase 0 of iteration i.
-    // Within a group the MFMAs come first (their fragments were read a phase ago), then the
-    // group's share of the next substep's fragment reads (activation fragments before weight
-    // fragments: the order in which the next phase needs them), then one load.  Iterations
-    // -4..-1 only fill the pipeline.
+    // A group's side work is its share of the next substep's fragment reads (activation fragments
+    // before weight fragments: the order in which the next phase needs them), then one load.
+    // Iterations -4..-1 only fill the pipeline.
     constexpr int nX = XMODE == X_FUSED ? 2 * XS : XS;     // loads per wave per K tile
-    constexpr int nW = WS;
+    constexpr int nW = WMODE == W_I4B ? WS / 2 : WS;
     constexpr int kFrags = MF + NF;
+    // Group g of K-substep `set`: MF MFMAs with the group's side work (its share of the next
+    // substep's fragment reads, then its loads / conversions) dealt out behind them, item k
+    // behind MFMA k.  With one wave per SIMD the matrix pipe only stays busy if whatever is
+    // issued between two MFMAs fits in the 32 cycles one of them takes; a clump of a dozen
+    // instructions between groups leaves it idle.  Pre-arranged int4 weights are unpacked one
+    // group ahead, behind the first MFMA of the previous group, also across the phase boundary
+    // when the first weight fragment of the next substep has been read by then (kCross).
+    constexpr bool kCross = MF < (NF - 1) * kFrags / NF;
+    i32x4 wnext = {0, 0, 0, 0};
+    auto group = [&](int set, int g, auto math_tag, int nitems, auto&& item) {
+        constexpr bool MATH = decltype(math_tag)::value;
+        if (!MATH) {
+            for (int k = 0; k < nitems; ++k) item(k);
+            __builtin_amdgcn_sched_barrier(0);
+            return;
+        }
+        i32x4 wv = fw[set][g];
+        if (WMODE == W_I4B) {
+            if (g == 0 && !kCross) wnext = wfrag(set, 0);
+            wv = wnext;
+        }
+#pragma unroll
+        for (int b = 0; b < MF; ++b) {
+            acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wv, fx[set][b], acc[g][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (WMODE == W_I4B && b == 0) {
+                if (g + 1 < NF) wnext = wfrag(set, g + 1);
+                else if (kCross) wnext = wfrag(1 - set, 0);
+            }
+            if (b < MF - 1) {
+                if (b < nitems) item(b);
+            } else {
+                for (int k = MF - 1; k < nitems; ++k) item(k);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
     auto iteration = [&](int i, auto math_tag, auto r_tag) {
         constexpr bool MATH = decltype(math_tag)::value;
         constexpr int R = decltype(r_tag)::value;              // (i + 6) % 3: register set of tile i
@@ -352,18 +420,13 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
         if (WMODE == W_I4) __builtin_amdgcn_s_waitcnt(waitcnt_vm(2 * nX + nW));     // W(i+1) registers are here
 #pragma unroll
         for (int g = 0; g < NF; ++g) {
-            if (MATH) {
-#pragma unroll
-                for (int b = 0; b < MF; ++b)
-                    acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[0][g], fx[0][b], acc[g][b], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int idx = g * kFrags / NF; idx < (g + 1) * kFrags / NF; ++idx) read_frag(1, st, 1, idx);
-            }
-            if (WMODE == W_I8) dma_w(i + 3, g);
-            if (WMODE == W_I4) convert_w(i + 1, g, S1{});
-            if (XMODE == X_FUSED && g >= XS / 2 && g < XS) convert_x(i + 1, g, S1{});   // second half of X(i+1)
-            __builtin_amdgcn_sched_barrier(0);
+            const int r0 = g * kFrags / NF, nr = MATH ? (g + 1) * kFrags / NF - r0 : 0;
+            group(0, g, math_tag, nr + 1, [&](int k) {
+                if (k < nr) { read_frag(1, st, 1, r0 + k); return; }
+                if (WMODE != W_I4 && g < nW) dma_w(i + 3, g);
+                if (WMODE == W_I4) convert_w(i + 1, g, S1{});
+                if (XMODE == X_FUSED && g >= XS / 2 && g < XS) convert_x(i + 1, g, S1{});   // second half of X(i+1)
+            });
         }
         if (WMODE == W_I4) regload_w(i + 3, S0{});
         asm volatile("" ::: "memory");
@@ -377,19 +440,12 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
         if (XMODE == X_FUSED) __builtin_amdgcn_s_waitcnt(waitcnt_vm(2 * nW + nX));  // X(i+2) registers are here
 #pragma unroll
         for (int g = 0; g < NF; ++g) {
-            if (MATH) {
-#pragma unroll
-                for (int b = 0; b < MF; ++b)
-                    acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[1][g], fx[1][b], acc[g][b], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            if (i + 1 >= 0) {
-#pragma unroll
-                for (int idx = g * kFrags / NF; idx < (g + 1) * kFrags / NF; ++idx) read_frag(0, (i + 1) & 3, 0, idx);
-            }
-            if (XMODE == X_PREQ && g < XS) dma_x(i + 4, g);
-            if (XMODE == X_FUSED && g < XS / 2) convert_x(i + 2, g, S2{});              // first half of X(i+2)
-            __builtin_amdgcn_sched_barrier(0);
+            const int r0 = g * kFrags / NF, nr = (i + 1 >= 0) ? (g + 1) * kFrags / NF - r0 : 0;
+            group(1, g, math_tag, nr + 1, [&](int k) {
+                if (k < nr) { read_frag(0, (i + 1) & 3, 0, r0 + k); return; }
+                if (XMODE == X_PREQ && g < XS) dma_x(i + 4, g);
+                if (XMODE == X_FUSED && g < XS / 2) convert_x(i + 2, g, S2{});              // first half of X(i+2)
+            });
         }
         if (XMODE == X_FUSED) regload_x(i + 4, S1{});
     };
@@ -400,6 +456,7 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
     iteration(-3, std::false_type{}, R0{});
     iteration(-2, std::false_type{}, R1{});
     iteration(-1, std::false_type{}, R2{});
+    if (WMODE == W_I4B && kCross) wnext = wfrag(0, 0);
     int it = 0;
 #pragma unroll 1
     for (; it + 2 < KT; it += 3) {
@@ -421,7 +478,7 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
     const bool has_bias = bias != nullptr;
     char* epi = &lds[wave * T::kEpiBytes];
     const int wn0 = n0 + wn * (BN / 2), wm0 = m0 + wm * (BM / 2);
-    constexpr int kAccShift = WMODE == W_I4 ? 4 : 0;
+    constexpr int kAccShift = (WMODE == W_I4 || WMODE == W_I4B) ? 4 : 0;
 #pragma unroll
     for (int a = 0; a < NF; ++a) {
 #pragma unroll
@@ -560,7 +617,12 @@ static void run_linear(const void* x, const float* s, const void* wq, const floa
 
     const bool mfma_ok = (K % kBK) == 0;
     const bool int4 = wf == SASQ_W_INT4_PACKED;
-    if (mfma_ok) {
+    if (wf == SASQ_W_INT8_BLOCKED || wf == SASQ_W_INT4_BLOCKED) {
+        // pre-arranged weights (K % 64 == 0 was checked by the caller): always the two-pass MFMA path
+        quantize_act_kernel<DT, false, true><<<qgrid, 256, 0, st>>>(X, s, reinterpret_cast<u32x2*>(xq_ws), nvec, n, (int)K, a_bits);
+        if (wf == SASQ_W_INT8_BLOCKED) launch_mfma<DT, X_PREQ, W_I8B>(xq_ws, wq, s, s_w, bias, y, acc_out, M, N, K, a_bits, st);
+        else                           launch_mfma<DT, X_PREQ, W_I4B>(xq_ws, wq, s, s_w, bias, y, acc_out, M, N, K, a_bits, st);
+    } else if (mfma_ok) {
         const int ov = path_override();
         const bool fused = ov == 2 || (ov == 0 && choose_fused(M, N, K));
         if (fused) {
@@ -607,9 +669,11 @@ extern "C" int sasq_static_linear(const void* x, const float* s, const void* wq,
     const int64_t lim = INT64_C(1) << 40;
     if (M > lim / K || N > lim / K || M > lim / N || K > 131071 || M > 0x7FFFFFFF || N > 0x7FFFFFFF) return SASQ_ERR_SHAPE;
     if (a_bits < 2 || a_bits > 8) return SASQ_ERR_UNSUPPORTED;
-    if (wf != SASQ_W_INT8 && wf != SASQ_W_INT4_PACKED) return SASQ_ERR_UNSUPPORTED;
+    if (wf != SASQ_W_INT8 && wf != SASQ_W_INT4_PACKED && wf != SASQ_W_INT8_BLOCKED && wf != SASQ_W_INT4_BLOCKED)
+        return SASQ_ERR_UNSUPPORTED;
     if (dt != SASQ_F16 && dt != SASQ_BF16) return SASQ_ERR_UNSUPPORTED;
     if (wf == SASQ_W_INT4_PACKED && (K & 1)) return SASQ_ERR_SHAPE;
+    if ((wf == SASQ_W_INT8_BLOCKED || wf == SASQ_W_INT4_BLOCKED) && (K % kBK)) return SASQ_ERR_SHAPE;
     if ((M * N + 255) / 256 > 0x7FFFFFFF) return SASQ_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(wq) || !aligned16(y) || (acc_out && !aligned16(acc_out)) ||
         (xq_out && (reinterpret_cast<uintptr_t>(xq_out) & 7u))) return SASQ_ERR_ALIGN;

@@ -87,7 +87,9 @@ def test_host_side_validation(lib):
     assert lin(*args(M=0)) == 2
     assert lin(*args(K=5, wf=1)) == 2
     assert lin(*args(K=1 << 20)) == 2
-    assert lin(*args(wf=2)) == 4
+    assert lin(*args(wf=4)) == 4
+    assert lin(*args(wf=2)) == 2            # blocked weights need K % 64 == 0
+    assert lin(*args(wf=3, K=96)) == 2
     assert lin(*args(dt=3)) == 4
     assert lin(*args(bits=0)) == 4
     assert lin(*args(wq=odd)) == 3
@@ -96,6 +98,17 @@ def test_host_side_validation(lib):
     assert qw(None, good, good, i64(4), i64(4), 0, None) == 1
     assert qw(good, good, good, i64(4), i64(3), 1, None) == 2
     assert qw(good, good, good, i64(4), i64(4), 5, None) == 4
+    pk = lib.sasq_pack_weight
+    assert pk(None, good, i64(4), i64(64), 0, None) == 1
+    assert pk(good, good, i64(4), i64(96), 0, None) == 2
+    assert pk(good, good, i64(4), i64(64), 2, None) == 4
+    assert pk(odd, good, i64(4), i64(64), 0, None) == 3
+    lib.sasq_packed_weight_bytes.restype = ctypes.c_size_t
+    assert lib.sasq_packed_weight_bytes(i64(17), i64(128), 2) == 32 * 128
+    assert lib.sasq_packed_weight_bytes(i64(17), i64(128), 3) == 32 * 64
+    assert lib.sasq_packed_weight_bytes(i64(33), i64(128), 3) == 64 * 64
+    assert lib.sasq_packed_weight_bytes(i64(17), i64(100), 2) == 0
+    assert lib.sasq_packed_weight_bytes(i64(17), i64(128), 0) == 0
     am = lib.sasq_absmax_scale
     assert am(good, None, i64(4), i64(4), 8, 0, good, big, None) == 1
     assert am(good, good, i64(4), i64(4), 8, 0, None, ctypes.c_size_t(0), None) == 5

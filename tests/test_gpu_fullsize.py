@@ -125,7 +125,19 @@ def test_static_linear_full_size(cfg_name, proj_name, ws):
         torch.cuda.synchronize()
         assert torch.equal(y.view(torch.int16), y_alt.view(torch.int16)), tile
     os.environ.pop("SASQ_STATIC_LINEAR_TILE", None)
-    del y_alt
+    # the pre-arranged weight format (what the benchmark times): bit-identical at every tile size
+    wfb = B.SASQ_W_INT8_BLOCKED if fmt == "int8" else B.SASQ_W_INT4_BLOCKED
+    wpk = torch.empty(B.sasq_packed_weight_bytes(N, K, wfb), dtype=torch.uint8, device="cuda")
+    B.sasq_pack_weight(wq, wpk, N, K, wf)
+    for tile in (None, "256", "128x256", "128"):
+        if tile:
+            os.environ["SASQ_STATIC_LINEAR_TILE"] = tile
+        y_alt.fill_(0)
+        B.sasq_static_linear(x, sd, wpk, s_w, None, y_alt, wfb, wsl)
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), y_alt.view(torch.int16)), f"blocked weights, tile {tile}"
+    os.environ.pop("SASQ_STATIC_LINEAR_TILE", None)
+    del y_alt, wpk
     acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
     xq = torch.empty((M, K), dtype=torch.int8, device="cuda")
     y_dbg = torch.empty_like(y)

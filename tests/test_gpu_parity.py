@@ -168,9 +168,21 @@ def test_quantize_weight(fmt, shape):
 
 
 # ---------------------------------------------------------------- static linear
-def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True, path=None, tile=None):
+def pack_on_device(wq, fmt):
+    """Row-major codes (numpy) -> the library's blocked arrangement (device uint8 tensor)."""
+    N = wq.shape[0]
+    K = wq.shape[1] * (1 if fmt == "int8" else 2)
+    src = B.SASQ_W_INT8 if fmt == "int8" else B.SASQ_W_INT4_PACKED
+    dst = B.SASQ_W_INT8_BLOCKED if fmt == "int8" else B.SASQ_W_INT4_BLOCKED
+    packed = torch.full((B.sasq_packed_weight_bytes(N, K, dst),), 0xA5, dtype=torch.uint8, device="cuda")
+    B.sasq_pack_weight(torch.from_numpy(wq).cuda(), packed, N, K, src)
+    return packed, dst
+
+
+def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True, path=None, tile=None, blocked=False):
     """path: None (library's choice by shape), "twopass" or "fused" (activation quantize in a
-    separate pass / on load inside the GEMM).  tile: None (by shape), "256", "128x256", "128"."""
+    separate pass / on load inside the GEMM).  tile: None (by shape), "256", "128x256", "128".
+    blocked: hand the weights over in the pre-arranged format made by sasq_pack_weight."""
     for var, val in (("SASQ_STATIC_LINEAR_PATH", path), ("SASQ_STATIC_LINEAR_TILE", tile)):
         if val is None:
             os.environ.pop(var, None)
@@ -179,12 +191,16 @@ def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True, path=None, til
     M, K = xb.shape
     N = wq.shape[0]
     wf = B.SASQ_W_INT8 if fmt == "int8" else B.SASQ_W_INT4_PACKED
+    if blocked:
+        wdev, wf = pack_on_device(wq, fmt)
+    else:
+        wdev = torch.from_numpy(wq).cuda()
     x = to_dev(xb, dtype)
     y = torch.empty((M, N), dtype=TDT[dtype], device="cuda")
     acc = torch.empty((M, N), dtype=torch.int32, device="cuda") if want_debug else None
     xq = torch.empty((M, K), dtype=torch.int8, device="cuda") if want_debug else None
     wsl = B.new_workspace(B.sasq_static_linear_workspace(M, N, K, wf))
-    B.sasq_static_linear(x, dev_scalar(s), torch.from_numpy(wq).cuda(), torch.from_numpy(s_w).cuda(),
+    B.sasq_static_linear(x, dev_scalar(s), wdev, torch.from_numpy(s_w).cuda(),
                          None if bias is None else torch.from_numpy(bias).cuda(), y, wf, wsl, acc, xq)
     torch.cuda.synchronize()
     os.environ.pop("SASQ_STATIC_LINEAR_PATH", None)
@@ -221,6 +237,88 @@ def test_static_linear(shape, dtype, fmt, path, tile):
         assert np.array_equal(y2, y)
 
 
+def blocked_layout_reference(wq, fmt):
+    """The documented blocked arrangements, written out index by index in numpy."""
+    N = wq.shape[0]
+    if fmt == "int8":
+        K = wq.shape[1]
+        KT = K // 64
+        out = np.zeros(((N + 15) // 16 * 16) * K, dtype=np.uint8)
+        src = wq.view(np.uint8)
+        for n in range(N):
+            r = n % 16
+            sw = ((r >> 1) & 3) ^ ((r >> 3) & 1)
+            for kb in range(KT):
+                base = ((n // 16) * KT + kb) * 1024
+                for c in range(4):
+                    o = base + 16 * (4 * r + (c ^ sw))
+                    out[o:o + 16] = src[n, kb * 64 + c * 16: kb * 64 + c * 16 + 16]
+        return out
+    K = wq.shape[1] * 2
+    KT = K // 64
+    codes = np.empty((N, K), dtype=np.uint8)
+    codes[:, 0::2] = wq & 15
+    codes[:, 1::2] = wq >> 4
+    out = np.zeros(((N + 31) // 32 * 32) * (K // 2), dtype=np.uint8)
+    for n in range(N):
+        r = n % 32
+        for kb in range(KT):
+            base = ((n // 32) * KT + kb) * 1024
+            for kk in range(2):
+                for g in range(2):
+                    c = codes[n, kb * 64 + 32 * kk + 16 * g: kb * 64 + 32 * kk + 16 * g + 16]
+                    o = base + 512 * kk + 256 * g + 8 * r
+                    for b in range(4):
+                        out[o + b] = c[b] | (c[4 + b] << 4)
+                        out[o + 4 + b] = c[8 + b] | (c[12 + b] << 4)
+    return out
+
+
+@pytest.mark.parametrize("fmt", ["int8", "int4"])
+@pytest.mark.parametrize("shape", [(1, 64), (16, 64), (33, 192), (70, 128), (256, 256)])
+def test_pack_weight_layout(fmt, shape):
+    """sasq_pack_weight is the permutation the header documents, rows past N zero."""
+    N, K = shape
+    wq = (wl.random_codes(21, f"pk{shape}", (N, K), -128, 127) if fmt == "int8"
+          else wl.random_codes(21, f"pk4{shape}", (N, K // 2), -128, 127).view(np.uint8))
+    packed, _ = pack_on_device(wq, fmt)
+    assert np.array_equal(packed.cpu().numpy(), blocked_layout_reference(wq, fmt))
+
+
+def test_pack_weight_rejects_bad_shapes():
+    wq = torch.zeros((4, 96), dtype=torch.int8, device="cuda")
+    assert B.sasq_packed_weight_bytes(4, 96, B.SASQ_W_INT8_BLOCKED) == 0
+    with pytest.raises(B.SasqError):
+        B._check(B._lib().sasq_pack_weight(B._ptr(wq), B._ptr(wq), 4, 96, B.SASQ_W_INT8, None), "pack")
+    x = torch.zeros((4, 96), dtype=torch.float16, device="cuda")
+    y = torch.zeros((4, 4), dtype=torch.float16, device="cuda")
+    one = torch.ones(4, dtype=torch.float32, device="cuda")
+    rc = B._lib().sasq_static_linear(B._ptr(x), B._ptr(one), B._ptr(wq), B._ptr(one), None, B._ptr(y), None, None,
+                                     4, 4, 96, 8, B.SASQ_W_INT8_BLOCKED, B.SASQ_F16, B._ptr(wq), 384, None)
+    assert rc == 2
+
+
+@pytest.mark.parametrize("tile", ["256", "128x256", "128"])
+@pytest.mark.parametrize("dtype,fmt", [("f16", "int8"), ("bf16", "int8"), ("bf16", "int4"), ("f16", "int4")])
+@pytest.mark.parametrize("shape", [sh for sh in LINEAR_SHAPES if sh[2] % 64 == 0])
+def test_static_linear_blocked_weights(shape, dtype, fmt, tile):
+    """Pre-arranged weights give the oracle's accumulators and outputs bit for bit."""
+    M, N, K = shape
+    xb = wl.random_bits(12, f"lx{shape}{dtype}", (M, K), dtype, gain=2.0)
+    w = wl.random_f32(12, f"lw{shape}", (N, K), 0.02)
+    wq, s_w = oracle.quantize_weight(w, fmt)
+    bias = wl.random_f32(12, f"lb{shape}", (N,), 0.3)
+    s = np.float32(oracle.absmax_scale(xb, 8, dtype) / 3)
+    for b in (None, bias):
+        ref = oracle.static_linear(xb, s, wq, s_w, b, 8, fmt, dtype)
+        y, acc, xq = run_linear(xb, s, wq, s_w, b, fmt, dtype, tile=tile, blocked=True)
+        assert np.array_equal(xq, ref["xq"]), "activation codes"
+        assert np.array_equal(acc, ref["acc"]), "int32 accumulators"
+        assert_same_values(y, ref["y"], dtype, "Y")
+        y2, _, _ = run_linear(xb, s, wq, s_w, b, fmt, dtype, want_debug=False, tile=tile, blocked=True)
+        assert np.array_equal(y2, y)
+
+
 def test_static_linear_extreme_codes():
     """All-extreme codes at a long K: signs and int32 headroom through the MFMA path."""
     K = 28672
@@ -242,6 +340,12 @@ def test_static_linear_extreme_codes():
         y, acc, xq = run_linear(xb, np.float32(1.0), w4, np.ones(3, np.float32), None, "int4", "bf16", path=path)
         assert np.array_equal(acc, ref4["acc"])
         assert_same_values(y, ref4["y"], "bf16", "Y int4")
+    # and through the pre-arranged formats
+    y, acc, _ = run_linear(xb, np.float32(1.0), wq, np.ones(4, np.float32), None, "int8", "bf16", blocked=True)
+    assert np.array_equal(acc, ref["acc"])
+    y, acc, _ = run_linear(xb, np.float32(1.0), w4, np.ones(3, np.float32), None, "int4", "bf16", blocked=True)
+    assert np.array_equal(acc, ref4["acc"])
+    assert_same_values(y, ref4["y"], "bf16", "Y int4 blocked")
 
 
 def test_cross_export_identity():
