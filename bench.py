@@ -34,7 +34,7 @@ INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8, published
 # HBM-side bytes per sasq_static_linear call (both kernels), averaged over gate/up/down of config 3:
 # rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a plain 1 GiB copy), see
 # profiles/bench_c3_mlp7b_counters.txt.  Algorithmic bytes are 221.2 MB.
-C3_LINEAR_TRAFFIC_BYTES = 449754 * 1024
+C3_LINEAR_TRAFFIC_BYTES = 450721 * 1024
 HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published
 LR = 2e-4
 TDT = {"f16": torch.float16, "bf16": torch.bfloat16}
