@@ -152,6 +152,32 @@ def static_linear(x: np.ndarray, s: float, wq: np.ndarray, s_w: np.ndarray,
     return {"y": y, "acc": acc, "xq": xq}
 
 
+def static_linear_grouped(x: np.ndarray, s_g: np.ndarray, wq: np.ndarray, s_w: np.ndarray,
+                          bias: Optional[np.ndarray], group: int, a_bits: int, w_fmt: str, dtype: str):
+    """Eq. 3 form: one activation factor per `group` consecutive input channels.
+    Returns dict(y=uint16 [M,N], f=float32 [M,N] (the fp32 group sum before s_w), xq=int8 [M,K])."""
+    x = _u16(x)
+    M, K = x.shape
+    wq = np.ascontiguousarray(wq)
+    assert wq.dtype in (np.int8, np.uint8)
+    N = wq.shape[0]
+    assert wq.shape[1] == (K if w_fmt == "int8" else K // 2), (wq.shape, K, w_fmt)
+    s_g = np.ascontiguousarray(s_g, dtype=np.float32)
+    assert K % group == 0 and s_g.shape == (K // group,)
+    s_w = np.ascontiguousarray(s_w, dtype=np.float32)
+    assert s_w.shape == (N,)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+    y = np.empty((M, N), dtype=np.uint16)
+    f = np.empty((M, N), dtype=np.float32)
+    xq = np.empty((M, K), dtype=np.int8)
+    rc = lib().sasq_oracle_static_linear_grouped(_p(x), _p(s_g), _p(wq), _p(s_w), _p(bias), _p(y), _p(f), _p(xq),
+                                                 ctypes.c_int64(M), ctypes.c_int64(N), ctypes.c_int64(K),
+                                                 ctypes.c_int64(group), int(a_bits), WF[w_fmt], DT[dtype])
+    _check(rc, "static_linear_grouped")
+    return {"y": y, "f": f, "xq": xq}
+
+
 def quantize_weight(w: np.ndarray, w_fmt: str) -> Tuple[np.ndarray, np.ndarray]:
     """w: fp32 [N,K] -> (wq int8 [N,K] | uint8 [N,K/2], s_w fp32 [N])."""
     w = np.ascontiguousarray(w, dtype=np.float32)

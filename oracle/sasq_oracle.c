@@ -298,6 +298,73 @@ int sasq_oracle_static_linear(const uint16_t* x, float s, const uint8_t* wq, con
 }
 
 /*
+ * Static linear with one activation factor per group of `group` consecutive input channels
+ * (Sec. 3, Eq. 3: Y = sum_i (S_x,i * S_w) * (X_int,i . W_int), the block-wise form the paper gives
+ * for activations quantized per channel; Sec. 4 uses per-channel activation factors).  Each
+ * channel k is quantized with s_g[k / group] (Eq. 1); each group's integer product is exact in
+ * int32; the groups are accumulated in fp32 in ascending order with one fused multiply-add per
+ * group (reading: Eq. 3 fixes no rounding order), the per-output-channel weight factor and the
+ * bias are applied last:
+ *     f = 0;  for i in 0..G-1:  f = fma(fl32(acc_i), s_g[i], f);   Y = fl32(f * s_w[n]) (+ bias[n]).
+ * group = 1 is per-channel in the strict sense, group = K per-tensor (with this rounding order).
+ * f_out (optional) receives f, xq_out the codes.
+ */
+int sasq_oracle_static_linear_grouped(const uint16_t* x, const float* s_g, const uint8_t* wq, const float* s_w,
+                                      const float* bias, uint16_t* y, float* f_out, int8_t* xq_out,
+                                      int64_t M, int64_t N, int64_t K, int64_t group, int a_bits, int wf, int dt)
+{
+    int rc = check_common(a_bits, dt);
+    if (rc) return rc;
+    if (wf != WF_INT8 && wf != WF_INT4_PACKED) return ERR_ARG;
+    if (wf == WF_INT4_PACKED && (K & 1)) return ERR_ARG;
+    if (group <= 0 || K % group) return ERR_ARG;
+    const int64_t G = K / group;
+    const int Qn = -(1 << (a_bits - 1)), Qp = (1 << (a_bits - 1)) - 1;
+
+    int8_t* xq = (int8_t*)malloc((size_t)(M * K > 0 ? M * K : 1));
+    int8_t* w8 = (int8_t*)malloc((size_t)(N * K > 0 ? N * K : 1));
+    if (!xq || !w8) { free(xq); free(w8); return ERR_NOMEM; }
+
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k)
+            xq[m * K + k] = (int8_t)quantize_one(load16(x, m * K + k, dt), reciprocal_f32(s_g[k / group]), Qn, Qp, 0).q;
+    if (xq_out) memcpy(xq_out, xq, (size_t)(M * K));
+
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            if (wf == WF_INT8) w8[n * K + k] = (int8_t)wq[n * K + k];
+            else {
+                uint8_t byte = wq[n * (K / 2) + k / 2];
+                w8[n * K + k] = (int8_t)nibble_to_int((k & 1) ? (byte >> 4) : (byte & 15u));
+            }
+        }
+
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            float f = 0.0f;
+            for (int64_t i = 0; i < G; ++i) {
+                int32_t acc = 0;
+                for (int64_t k = i * group; k < (i + 1) * group; ++k)
+                    acc += (int32_t)xq[m * K + k] * (int32_t)w8[n * K + k];
+                f = fmaf((float)acc, s_g[i], f);
+            }
+            if (f_out) f_out[m * N + n] = f;
+            if (y) {
+                volatile float yf = f * s_w[n];
+                if (bias) { volatile float yb = yf + bias[n]; yf = yb; }
+                y[m * N + n] = store16(yf, dt);
+            }
+        }
+    }
+    free(xq);
+    free(w8);
+    return OK;
+}
+
+/*
  * Frozen-weight quantization, symmetric, one scale per output channel (row of W[N,K])
  * (Sec. 3, Eq. 1 applied per row; Sec. 5.1 fixes weights to one factor per output channel):
  *   s_w[n] = fl32(max_k |W[n,k]| / Qp)   (1 if the row is all zero)

@@ -38,12 +38,17 @@ MUTATIONS = [
      "static uint16_t f32_to_bf16(float f) { union { float f; uint32_t u; } c; c.f = f; return (uint16_t)(c.u >> 16); }"),
     ("per_channel_uses_first_scale", "        const float sk = s[k];", "        const float sk = s[0];"),
     ("per_channel_ds_row_indexed", "        if (ds64) ds64[k] = acc;", "        if (ds64) ds64[(k + 1) % cols] = acc;"),
+    ("grouped_unfused", "f = fmaf((float)acc, s_g[i], f);", "f = f + (float)acc * s_g[i];"),
+    ("grouped_scale_index", "reciprocal_f32(s_g[k / group])", "reciprocal_f32(s_g[k % G])"),
+    ("grouped_descending", "for (int64_t i = 0; i < G; ++i) {", "for (int64_t i = G - 1; i >= 0; --i) {"),
+    ("grouped_group_bounds", "for (int64_t k = i * group; k < (i + 1) * group; ++k)", "for (int64_t k = i * group; k < K; ++k)"),
+    ("grouped_weight_factor_first_channel", "volatile float yf = f * s_w[n];", "volatile float yf = f * s_w[0];"),
     ("sgd_plus", "volatile float out = s - step;", "volatile float out = s + step;"),
 ]
 
-PIN_FILES = ["tests/test_oracle_pins.py", "tests/test_oracle_pins_pc.py"]
+PIN_FILES = ["tests/test_oracle_pins.py", "tests/test_oracle_pins_pc.py", "tests/test_oracle_pins_grouped.py"]
 SELECT = ("hand_table or closed_forms or autograd or static_linear or int4 or weight_quantizer or scale_sgd "
-          "or encode or decode or per_channel or ds_terms or reciprocal or epilogue")
+          "or encode or decode or per_channel or ds_terms or reciprocal or epilogue or grouped")
 
 
 def run_pins(src_path: str) -> int:
