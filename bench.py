@@ -202,6 +202,34 @@ def main():
               "frac": round(tot_b / (tot_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
               "note": "per-channel fwd+bwd on x_mlp and x_down, warm repeat of 5"}
 
+    # static linear with one activation factor per group of 128 / 512 input channels (the grouped form
+    # the paper gives for per-channel activation factors), measured after the timed region
+    grouped = None
+    if cfg.name == "c3_mlp7b":
+        grouped = {}
+        for group in (128, 512):
+            tot_ops, tot_ms, calls = 0.0, 0.0, 0
+            for p in projs:
+                if p.K % group:
+                    continue
+                calls += 1
+                sg = p.s.expand(p.K // group).contiguous()
+                for _ in range(2):
+                    B.sasq_static_linear_grouped(p.x, sg, p.wq, p.s_w, None, p.y, group, p.wf, p.ws_lin)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(5):
+                    B.sasq_static_linear_grouped(p.x, sg, p.wq, p.s_w, None, p.y, group, p.wf, p.ws_lin)
+                e1.record()
+                torch.cuda.synchronize()
+                tot_ms += e0.elapsed_time(e1) / 5
+                tot_ops += p.ops
+            grouped[f"group_{group}"] = {"achieved": round(tot_ops / (tot_ms * 1e-3) / 1e12, 1), "unit": "TOP/s",
+                                         "frac": round(tot_ops / (tot_ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, 4),
+                                         "us_per_call": round(1e3 * tot_ms / calls, 1), "calls": calls}
+        grouped["note"] = ("sasq_static_linear_grouped on the projections whose K the group divides "
+                           "(gate, up, down for 128; gate, up for 512); warm repeat of 5")
+
     out = {
         "metric": "static-scale W8A8 linear TOPS (% int8 MFMA peak); fake-quant fwd+bwd GB/s",
         "value": round(total_ops / (ms_per_step * 1e-3) / 1e12, 2),
@@ -226,6 +254,7 @@ def main():
                       "bytes_per_element": 10, "note": "fwd (2+2 B/el) + bwd (2+2+2 B/el), events around the pair"},
         "per_projection": per_proj,
         "fakequant_per_channel": pc,
+        "static_linear_grouped": grouped,
     }
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, a.cpu_rows)

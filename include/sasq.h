@@ -181,6 +181,30 @@ int sasq_static_linear(const void* x, const float* s, const void* wq, const floa
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Static-inference quantized linear with one activation factor per group of `group` consecutive
+ * input channels (Sec. 3, Eq. 3: Y = sum_i (S_x,i * S_w) * (X_int,i . W_int), the block-wise form
+ * the paper gives for activations quantized per channel; Sec. 4 trains per-channel factors):
+ *     xq[m,k]    = clamp(round(X[m,k] / s_g[k / group]), -2^(a_bits-1), 2^(a_bits-1) - 1)
+ *     acc_i[m,n] = sum over the k of group i of xq[m,k] * Wq[n,k]          (exact, int32)
+ *     f[m,n]     = fma(fl32(acc_i[m,n]), s_g[i], f[m,n]) for i = 0 .. K/group - 1, from f = 0
+ *     Y[m,n]     = fl32(f[m,n] * s_w[n]) (+ bias[n])  -> 16-bit `dt`
+ * (the paper fixes no rounding order for Eq. 3; this one is what the kernels and the test oracle
+ * share.)  group = 1 is per-channel in the strict sense, group = K a per-tensor factor.
+ *   s_g      [K / group] device fp32
+ *   f_out    [M, N] device fp32 or NULL: f, for inspection and tests (slower path); xq_out as in
+ *            sasq_static_linear
+ *   group    divides K.  The MFMA path is taken when K and group are multiples of 64 (then all
+ *            four weight formats are accepted); other shapes run a scalar kernel and accept the
+ *            row-major weight formats only (SASQ_ERR_SHAPE for the pre-arranged ones).
+ *   every other argument, the workspace size and the limits are those of sasq_static_linear.
+ */
+int sasq_static_linear_grouped(const void* x, const float* s_g, const void* wq, const float* s_w,
+                               const float* bias, void* y, float* f_out, int8_t* xq_out,
+                               int64_t M, int64_t N, int64_t K, int64_t group, int a_bits,
+                               sasq_wfmt wf, sasq_dtype dt, void* workspace, size_t workspace_bytes,
+                               void* stream);
+
+/*
  * Quantize frozen weights, symmetric, one factor per output channel (Sec. 3, Eq. 1 applied to
  * each row of W[N,K]; Sec. 5.1 fixes the weight granularity to per output channel):
  *     s_w[n]  = fl32(max_k |W[n,k]| / Qp)     (1 if the row is all zero),  Qp = 127 or 7

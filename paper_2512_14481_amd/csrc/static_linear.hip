@@ -64,6 +64,53 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(
     }
 }
 
+// Same pre-pass with one factor per group of `group` consecutive channels (Sec. 3, Eq. 3; Eq. 1
+// per group): the vector form needs group % 8 == 0 and K % 8 == 0 (a vector never straddles two
+// groups), the element form takes any group.
+template <int DT, bool PERM8, bool TILED>
+__global__ __launch_bounds__(256) void quantize_act_grouped_kernel(
+    const u32x4* __restrict__ x, const float* __restrict__ s_g, u32x2* __restrict__ xq,
+    int64_t nvec, int K, int group, int bits)
+{
+    using S = Store16<DT>;
+    const int kvec = K >> 3;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * 256) {
+        const int64_t m = i / kvec;
+        const int k0 = (int)(i - m * kvec) << 3;
+        const QConst k = make_qconst(s_g[k0 / group], bits);
+        u32x4 v = x[i];
+        float c[8];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            c[2 * w] = quantize(S::lo(v[w]), k).c;
+            c[2 * w + 1] = quantize(S::hi(v[w]), k).c;
+        }
+        u32x2 o;
+        if (PERM8) { o[0] = pack_codes4(c[0], c[2], c[4], c[6]); o[1] = pack_codes4(c[1], c[3], c[5], c[7]); }
+        else       { o[0] = pack_codes4(c[0], c[1], c[2], c[3]); o[1] = pack_codes4(c[4], c[5], c[6], c[7]); }
+        if (TILED) {
+            const int r = (int)(m & 15), ch = (k0 & 63) >> 4;
+            const int64_t blk = (m >> 4) * (K >> 6) + (k0 >> 6);
+            const int64_t off = blk * 1024 + ((4 * r + (ch ^ swz64(r))) << 4) + (k0 & 15);
+            *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(xq) + off) = o;
+        } else {
+            xq[i] = o;
+        }
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void quantize_act_grouped_elem_kernel(
+    const uint16_t* __restrict__ x, const float* __restrict__ s_g, int8_t* __restrict__ xq,
+    int64_t n, int K, int group, int bits)
+{
+    using S = Store16<DT>;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const QConst k = make_qconst(s_g[(int)(i % K) / group], bits);
+        xq[i] = (int8_t)code_of(quantize(S::one(x[i]), k));
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Epilogue arithmetic, identical on every path:  y = fl32(fl32(acc) * fl32(s*s_w[n])) (+ bias).
 // ---------------------------------------------------------------------------------------------
@@ -104,6 +151,40 @@ __global__ __launch_bounds__(256) void linear_scalar_kernel(
     const float c = *s_ptr * s_w[n];
     y[idx] = S::enc(dequant(acc, c, bias ? bias[n] : 0.0f, bias != nullptr));
     if (acc_out) acc_out[idx] = acc;
+}
+
+// Grouped form (Sec. 3, Eq. 3) for shapes the MFMA kernel does not take: per group an exact int32
+// product, folded into fp32 with one fused multiply-add per group in ascending order.
+template <int DT, bool INT4>
+__global__ __launch_bounds__(256) void linear_grouped_scalar_kernel(
+    const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq, const float* __restrict__ s_g,
+    const float* __restrict__ s_w, const float* __restrict__ bias, uint16_t* __restrict__ y,
+    float* __restrict__ f_out, int64_t M, int64_t N, int64_t K, int64_t group)
+{
+    using S = Store16<DT>;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= M * N) return;
+    const int64_t m = idx / N, n = idx % N;
+    const int8_t* xr = xq + m * K;
+    float f = 0.0f;
+    for (int64_t g0 = 0; g0 < K; g0 += group) {
+        int acc = 0;
+        for (int64_t k = g0; k < g0 + group; ++k) {
+            int w;
+            if (INT4) {
+                const int b = wq[n * (K / 2) + k / 2];
+                w = (((k & 1) ? (b >> 4) : (b & 15)) ^ 8) - 8;
+            } else {
+                w = reinterpret_cast<const int8_t*>(wq)[n * K + k];
+            }
+            acc += (int)xr[k] * w;
+        }
+        f = __builtin_fmaf((float)acc, s_g[g0 / group], f);
+    }
+    if (f_out) f_out[idx] = f;
+    float yv = f * s_w[n];
+    if (bias) yv = yv + bias[n];
+    y[idx] = S::enc(yv);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -196,17 +277,24 @@ __device__ __forceinline__ bool tile_of_block(int bid, int tiles_m, int tiles_n,
 enum { X_PREQ = 0, X_FUSED = 1 };
 enum { W_I8 = 0, W_I4 = 1, W_I8B = 2, W_I4B = 3 };
 
-template <int DT, int XMODE, int WMODE, int BM, int BN>
+// GROUPED (Sec. 3, Eq. 3): one activation factor per group of `group_tiles` K tiles.  s_ptr then
+// points at the G factors; the int32 accumulators cover one group at a time (the first K-substep
+// of a group multiplies into a zero accumulator operand) and are folded into fp32 sums at each
+// group's end, f = fma(fl32(acc), s_g, f) in ascending group order; the epilogue applies s_w and
+// the bias to f.  acc_out then receives f (as float).  Needs tiles with at most 128 accumulators
+// per lane (128x256, 128x128), as f takes as many registers again.
+template <int DT, int XMODE, int WMODE, int BM, int BN, bool GROUPED = false>
 __global__ __launch_bounds__(kGemmThreads)
 __attribute__((amdgpu_waves_per_eu(Tile<BM, BN>::kWavesPerSimd, Tile<BM, BN>::kWavesPerSimd)))
 void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict__ wq,
                         const float* __restrict__ s_ptr, const float* __restrict__ s_w,
                         const float* __restrict__ bias, uint16_t* __restrict__ y,
                         int32_t* __restrict__ acc_out, int M, int N, int K, int a_bits,
-                        int tiles_m, int tiles_n)
+                        int tiles_m, int tiles_n, int group_tiles)
 {
     using S = Store16<DT>;
     using T = Tile<BM, BN>;
+    static_assert(!GROUPED || (BM == 128 && XMODE == X_PREQ), "grouped factors: 128-row tiles over staged activations");
     constexpr int MF = T::MF, NF = T::NF, XS = T::XS, WS = T::WS;
     __shared__ __attribute__((aligned(1024))) char lds[T::kLds];
     auto stage_ptr = [&](int st, int operand) -> char* { return &lds[st * T::kStageBytes + operand * T::kXBytes]; };
@@ -352,6 +440,13 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
     };
 
     i32x16 acc[NF][MF];   // [n tile][m tile]
+    f32x16 fsum[GROUPED ? NF : 1][GROUPED ? MF : 1];   // fp32 sums over groups
+#pragma unroll
+    for (int a = 0; a < (GROUPED ? NF : 1); ++a)
+#pragma unroll
+        for (int b = 0; b < (GROUPED ? MF : 1); ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) fsum[a][b][v] = 0.0f;
 #pragma unroll
     for (int a = 0; a < NF; ++a)
 #pragma unroll
@@ -381,8 +476,10 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
     // when the first weight fragment of the next substep has been read by then (kCross).
     constexpr bool kCross = MF < (NF - 1) * kFrags / NF;
     i32x4 wnext = {0, 0, 0, 0};
-    auto group = [&](int set, int g, auto math_tag, int nitems, auto&& item) {
-        constexpr bool MATH = decltype(math_tag)::value;
+    // mode 0: pipeline fill (no math); 1: math; 2: math, and the K tile opens a group of factors
+    auto group = [&](int set, int g, auto mode_tag, int nitems, auto&& item) {
+        constexpr int MODE = decltype(mode_tag)::value;
+        constexpr bool MATH = MODE != 0;
         if (!MATH) {
             for (int k = 0; k < nitems; ++k) item(k);
             __builtin_amdgcn_sched_barrier(0);
@@ -395,7 +492,12 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
         }
 #pragma unroll
         for (int b = 0; b < MF; ++b) {
-            acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wv, fx[set][b], acc[g][b], 0, 0, 0);
+            if (MODE == 2 && set == 0) {
+                const i32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wv, fx[set][b], zero, 0, 0, 0);
+            } else {
+                acc[g][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wv, fx[set][b], acc[g][b], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
             if (WMODE == W_I4B && b == 0) {
                 if (g + 1 < NF) wnext = wfrag(set, g + 1);
@@ -409,8 +511,8 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    auto iteration = [&](int i, auto math_tag, auto r_tag) {
-        constexpr bool MATH = decltype(math_tag)::value;
+    auto iteration = [&](int i, auto mode_tag, auto r_tag) {
+        constexpr bool MATH = decltype(mode_tag)::value != 0;
         constexpr int R = decltype(r_tag)::value;              // (i + 6) % 3: register set of tile i
         using S0 = std::integral_constant<int, R>;
         using S1 = std::integral_constant<int, (R + 1) % 3>;
@@ -421,7 +523,7 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
 #pragma unroll
         for (int g = 0; g < NF; ++g) {
             const int r0 = g * kFrags / NF, nr = MATH ? (g + 1) * kFrags / NF - r0 : 0;
-            group(0, g, math_tag, nr + 1, [&](int k) {
+            group(0, g, mode_tag, nr + 1, [&](int k) {
                 if (k < nr) { read_frag(1, st, 1, r0 + k); return; }
                 if (WMODE != W_I4 && g < nW) dma_w(i + 3, g);
                 if (WMODE == W_I4) convert_w(i + 1, g, S1{});
@@ -441,7 +543,7 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
 #pragma unroll
         for (int g = 0; g < NF; ++g) {
             const int r0 = g * kFrags / NF, nr = (i + 1 >= 0) ? (g + 1) * kFrags / NF - r0 : 0;
-            group(1, g, math_tag, nr + 1, [&](int k) {
+            group(1, g, mode_tag, nr + 1, [&](int k) {
                 if (k < nr) { read_frag(0, (i + 1) & 3, 0, r0 + k); return; }
                 if (XMODE == X_PREQ && g < XS) dma_x(i + 4, g);
                 if (XMODE == X_FUSED && g < XS / 2) convert_x(i + 2, g, S2{});              // first half of X(i+2)
@@ -452,20 +554,44 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
     using R0 = std::integral_constant<int, 0>;
     using R1 = std::integral_constant<int, 1>;
     using R2 = std::integral_constant<int, 2>;
-    iteration(-4, std::false_type{}, R2{});
-    iteration(-3, std::false_type{}, R0{});
-    iteration(-2, std::false_type{}, R1{});
-    iteration(-1, std::false_type{}, R2{});
+    using Fill = std::integral_constant<int, 0>;
+    using Math = std::integral_constant<int, 1>;
+    using Open = std::integral_constant<int, 2>;
+    iteration(-4, Fill{}, R2{});
+    iteration(-3, Fill{}, R0{});
+    iteration(-2, Fill{}, R1{});
+    iteration(-1, Fill{}, R2{});
     if (WMODE == W_I4B && kCross) wnext = wfrag(0, 0);
+    // one K tile of math; with grouped factors also the group bookkeeping (all of it uniform)
+    int in_group = 0, group_idx = 0;
+    constexpr float kAccScale = (WMODE == W_I4 || WMODE == W_I4B) ? 0.0625f : 1.0f;   // int4 accumulators are 16 x acc
+    auto step = [&](int i, auto r_tag) {
+        if (!GROUPED) { iteration(i, Math{}, r_tag); return; }
+        if (in_group == 0) iteration(i, Open{}, r_tag);
+        else               iteration(i, Math{}, r_tag);
+        if (++in_group == group_tiles) {
+            // fl32(16 a) = 16 fl32(a) and s/16 is exact, so the fused multiply-add below rounds
+            // exactly like fma(fl32(a), s, f)
+            const float sg = s_ptr[group_idx] * kAccScale;
+#pragma unroll
+            for (int a = 0; a < (GROUPED ? NF : 1); ++a)
+#pragma unroll
+                for (int b = 0; b < (GROUPED ? MF : 1); ++b)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) fsum[a][b][v] = __builtin_fmaf((float)acc[a][b][v], sg, fsum[a][b][v]);
+            in_group = 0;
+            ++group_idx;
+        }
+    };
     int it = 0;
 #pragma unroll 1
     for (; it + 2 < KT; it += 3) {
-        iteration(it, std::true_type{}, R0{});
-        iteration(it + 1, std::true_type{}, R1{});
-        iteration(it + 2, std::true_type{}, R2{});
+        step(it, R0{});
+        step(it + 1, R1{});
+        step(it + 2, R2{});
     }
-    if (it < KT) iteration(it, std::true_type{}, R0{});
-    if (it + 1 < KT) iteration(it + 1, std::true_type{}, R1{});
+    if (it < KT) step(it, R0{});
+    if (it + 1 < KT) step(it + 1, R1{});
     // drain the tail loads and the last fragment reads before LDS is reused
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0 & waitcnt_vm(0));
     __builtin_amdgcn_s_barrier();
@@ -488,18 +614,32 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int ne = min(wn0 + nl + e, N - 1);
-                c[e] = s * s_w[ne];
+                c[e] = GROUPED ? s_w[ne] : s * s_w[ne];
                 bz[e] = has_bias ? bias[ne] : 0.0f;
             }
 #pragma unroll
             for (int b = 0; b < MF; ++b) {
                 const int ml = b * 32 + frow;
                 int av[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) av[e] = acc[a][b][4 * g + e] >> kAccShift;
                 u32x2 pk;
-                pk[0] = S::pack(dequant(av[0], c[0], bz[0], has_bias), dequant(av[1], c[1], bz[1], has_bias));
-                pk[1] = S::pack(dequant(av[2], c[2], bz[2], has_bias), dequant(av[3], c[3], bz[3], has_bias));
+                if (GROUPED) {
+                    // Y = fl32(f * s_w[n]) (+ bias); the debug output is f itself
+                    float fv[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        fv[e] = fsum[GROUPED ? a : 0][GROUPED ? b : 0][4 * g + e];
+                        av[e] = __float_as_int(fv[e]);
+                        fv[e] = fv[e] * c[e];
+                        if (has_bias) fv[e] = fv[e] + bz[e];
+                    }
+                    pk[0] = S::pack(fv[0], fv[1]);
+                    pk[1] = S::pack(fv[2], fv[3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) av[e] = acc[a][b][4 * g + e] >> kAccShift;
+                    pk[0] = S::pack(dequant(av[0], c[0], bz[0], has_bias), dequant(av[1], c[1], bz[1], has_bias));
+                    pk[1] = S::pack(dequant(av[2], c[2], bz[2], has_bias), dequant(av[3], c[3], bz[3], has_bias));
+                }
                 *reinterpret_cast<u32x2*>(epi + ml * T::kEpiStride + nl * 2) = pk;
                 if (acc_out) {
                     const int m = wm0 + ml, n = wn0 + nl;
@@ -559,15 +699,16 @@ static bool choose_fused(int64_t M, int64_t N, int64_t K)
     return N <= kFusedMaxN;
 }
 
-template <int DT, int XMODE, int WMODE, int BM, int BN>
+template <int DT, int XMODE, int WMODE, int BM, int BN, bool GROUPED = false>
 static void launch_tiles(const void* xin, const void* wq, const float* s, const float* s_w, const float* bias,
-                         void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K, int a_bits, hipStream_t st)
+                         void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K, int a_bits, hipStream_t st,
+                         int group_tiles = 0)
 {
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
     const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-    linear_mfma_kernel<DT, XMODE, WMODE, BM, BN><<<grid, kGemmThreads, 0, st>>>(
+    linear_mfma_kernel<DT, XMODE, WMODE, BM, BN, GROUPED><<<grid, kGemmThreads, 0, st>>>(
         xin, static_cast<const uint8_t*>(wq), s, s_w, bias, static_cast<uint16_t*>(y), acc_out,
-        (int)M, (int)N, (int)K, a_bits, tiles_m, tiles_n);
+        (int)M, (int)N, (int)K, a_bits, tiles_m, tiles_n, group_tiles);
 }
 
 // Tile choice.  256x256 tiles are the most efficient per operation but a launch of T tiles takes
@@ -648,6 +789,64 @@ static void run_linear(const void* x, const float* s, const void* wq, const floa
     }
 }
 
+// Grouped factors: 128-row tiles only (the fp32 group sums double the accumulator registers).
+template <int DT, int WMODE>
+static void launch_mfma_grouped(const void* xin, const void* wq, const float* s_g, const float* s_w, const float* bias,
+                                void* y, float* f_out, int64_t M, int64_t N, int64_t K, int a_bits, int group_tiles,
+                                hipStream_t st)
+{
+    auto rounds = [&](int bm, int bn, int slots) {
+        const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+        return (double)((tiles + slots - 1) / slots);
+    };
+    int tile = rounds(128, 256, 256) * kCost128x256 <= rounds(128, 128, 512) * kCost128x128 ? 1 : 2;
+    if (const char* e = getenv("SASQ_STATIC_LINEAR_TILE")) {
+        if (!strcmp(e, "128x256")) tile = 1;
+        if (!strcmp(e, "128")) tile = 2;
+    }
+    auto acc_out = reinterpret_cast<int32_t*>(f_out);
+    if (tile == 1) launch_tiles<DT, X_PREQ, WMODE, 128, 256, true>(xin, wq, s_g, s_w, bias, y, acc_out, M, N, K, a_bits, st, group_tiles);
+    else           launch_tiles<DT, X_PREQ, WMODE, 128, 128, true>(xin, wq, s_g, s_w, bias, y, acc_out, M, N, K, a_bits, st, group_tiles);
+}
+
+template <int DT>
+static void run_linear_grouped(const void* x, const float* s_g, const void* wq, const float* s_w, const float* bias,
+                               void* y, float* f_out, int8_t* xq_out, int64_t M, int64_t N, int64_t K, int64_t group,
+                               int a_bits, sasq_wfmt wf, int8_t* xq_ws, hipStream_t st)
+{
+    const int64_t n = M * K, nvec = n / 8;
+    auto grid_of = [](int64_t work) { int64_t b = (work + 255) / 256; return (int)(b < 1 ? 1 : (b > 65536 ? 65536 : b)); };
+    const bool vec_ok = (K % 8) == 0 && (group % 8) == 0;
+    auto X = static_cast<const u32x4*>(x);
+    auto quantize_rowmajor = [&](int8_t* dst) {
+        if (vec_ok) quantize_act_grouped_kernel<DT, false, false><<<grid_of(nvec), 256, 0, st>>>(X, s_g, reinterpret_cast<u32x2*>(dst), nvec, (int)K, (int)group, a_bits);
+        else        quantize_act_grouped_elem_kernel<DT><<<grid_of(n), 256, 0, st>>>(static_cast<const uint16_t*>(x), s_g, dst, n, (int)K, (int)group, a_bits);
+    };
+    if (xq_out) quantize_rowmajor(xq_out);
+    const bool mfma_ok = (K % kBK) == 0 && (group % kBK) == 0;
+    if (mfma_ok) {
+        // row-major packed int4 unpacks in (0,2,4,6,1,3,5,7) order: the activation bytes are stored to match
+        if (wf == SASQ_W_INT4_PACKED)
+            quantize_act_grouped_kernel<DT, true, true><<<grid_of(nvec), 256, 0, st>>>(X, s_g, reinterpret_cast<u32x2*>(xq_ws), nvec, (int)K, (int)group, a_bits);
+        else
+            quantize_act_grouped_kernel<DT, false, true><<<grid_of(nvec), 256, 0, st>>>(X, s_g, reinterpret_cast<u32x2*>(xq_ws), nvec, (int)K, (int)group, a_bits);
+        const int gt = (int)(group / kBK);
+        switch (wf) {
+            case SASQ_W_INT8:         launch_mfma_grouped<DT, W_I8>(xq_ws, wq, s_g, s_w, bias, y, f_out, M, N, K, a_bits, gt, st); break;
+            case SASQ_W_INT4_PACKED:  launch_mfma_grouped<DT, W_I4>(xq_ws, wq, s_g, s_w, bias, y, f_out, M, N, K, a_bits, gt, st); break;
+            case SASQ_W_INT8_BLOCKED: launch_mfma_grouped<DT, W_I8B>(xq_ws, wq, s_g, s_w, bias, y, f_out, M, N, K, a_bits, gt, st); break;
+            default:                  launch_mfma_grouped<DT, W_I4B>(xq_ws, wq, s_g, s_w, bias, y, f_out, M, N, K, a_bits, gt, st); break;
+        }
+    } else {
+        quantize_rowmajor(xq_ws);
+        const int64_t blocks = (M * N + 255) / 256;
+        auto W = static_cast<const uint8_t*>(wq);
+        auto Y = static_cast<uint16_t*>(y);
+        if (wf == SASQ_W_INT4_PACKED) linear_grouped_scalar_kernel<DT, true><<<(int)blocks, 256, 0, st>>>(xq_ws, W, s_g, s_w, bias, Y, f_out, M, N, K, group);
+        else                          linear_grouped_scalar_kernel<DT, false><<<(int)blocks, 256, 0, st>>>(xq_ws, W, s_g, s_w, bias, Y, f_out, M, N, K, group);
+    }
+}
+
 }  // namespace sasq
 
 using namespace sasq;
@@ -685,5 +884,36 @@ extern "C" int sasq_static_linear(const void* x, const float* s, const void* wq,
     int8_t* xq_ws = static_cast<int8_t*>(workspace);
     if (dt == SASQ_F16) run_linear<SASQ_F16>(x, s, wq, s_w, bias, y, acc_out, xq_out, M, N, K, a_bits, wf, xq_ws, st);
     else                run_linear<SASQ_BF16>(x, s, wq, s_w, bias, y, acc_out, xq_out, M, N, K, a_bits, wf, xq_ws, st);
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+extern "C" int sasq_static_linear_grouped(const void* x, const float* s_g, const void* wq, const float* s_w,
+                                          const float* bias, void* y, float* f_out, int8_t* xq_out,
+                                          int64_t M, int64_t N, int64_t K, int64_t group, int a_bits,
+                                          sasq_wfmt wf, sasq_dtype dt, void* workspace, size_t workspace_bytes,
+                                          void* stream)
+{
+    if (!x || !s_g || !wq || !s_w || !y) return SASQ_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0 || group <= 0 || K % group) return SASQ_ERR_SHAPE;
+    const int64_t lim = INT64_C(1) << 40;
+    if (M > lim / K || N > lim / K || M > lim / N || K > 131071 || M > 0x7FFFFFFF || N > 0x7FFFFFFF) return SASQ_ERR_SHAPE;
+    if (a_bits < 2 || a_bits > 8) return SASQ_ERR_UNSUPPORTED;
+    if (wf != SASQ_W_INT8 && wf != SASQ_W_INT4_PACKED && wf != SASQ_W_INT8_BLOCKED && wf != SASQ_W_INT4_BLOCKED)
+        return SASQ_ERR_UNSUPPORTED;
+    if (dt != SASQ_F16 && dt != SASQ_BF16) return SASQ_ERR_UNSUPPORTED;
+    if (wf == SASQ_W_INT4_PACKED && (K & 1)) return SASQ_ERR_SHAPE;
+    // the pre-arranged formats exist for the MFMA kernel only, which takes whole K tiles per group
+    if ((wf == SASQ_W_INT8_BLOCKED || wf == SASQ_W_INT4_BLOCKED) && ((K % kBK) || (group % kBK))) return SASQ_ERR_SHAPE;
+    if ((M * N + 255) / 256 > 0x7FFFFFFF) return SASQ_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(wq) || !aligned16(y) || (f_out && !aligned16(f_out)) ||
+        (xq_out && (reinterpret_cast<uintptr_t>(xq_out) & 7u))) return SASQ_ERR_ALIGN;
+    const size_t need = sasq_static_linear_workspace(M, N, K, wf);
+    if (!workspace || workspace_bytes < need) return SASQ_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SASQ_ERR_ALIGN;
+
+    hipStream_t st = as_stream(stream);
+    int8_t* xq_ws = static_cast<int8_t*>(workspace);
+    if (dt == SASQ_F16) run_linear_grouped<SASQ_F16>(x, s_g, wq, s_w, bias, y, f_out, xq_out, M, N, K, group, a_bits, wf, xq_ws, st);
+    else                run_linear_grouped<SASQ_BF16>(x, s_g, wq, s_w, bias, y, f_out, xq_out, M, N, K, group, a_bits, wf, xq_ws, st);
     return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
 }

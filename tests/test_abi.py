@@ -94,6 +94,17 @@ def test_host_side_validation(lib):
     assert lin(*args(bits=0)) == 4
     assert lin(*args(wq=odd)) == 3
     assert lin(*args(ws=None, wsb=ctypes.c_size_t(0))) == 5
+    lg = lib.sasq_static_linear_grouped
+    gargs = lambda **kw: [kw.get("x", good), good, good, good, None, good, None, None,
+                          i64(4), i64(4), i64(kw.get("K", 128)), i64(kw.get("group", 64)), kw.get("bits", 8),
+                          kw.get("wf", 0), 0, kw.get("ws", good), big, None]
+    assert lg(*gargs(x=None)) == 1
+    assert lg(*gargs(group=0)) == 2
+    assert lg(*gargs(group=48)) == 2
+    assert lg(*gargs(group=32, wf=2)) == 2
+    assert lg(*gargs(wf=9)) == 4
+    assert lg(*gargs(bits=1)) == 4
+    assert lg(*gargs(ws=None)) == 5
     qw = lib.sasq_quantize_weight
     assert qw(None, good, good, i64(4), i64(4), 0, None) == 1
     assert qw(good, good, good, i64(4), i64(3), 1, None) == 2
