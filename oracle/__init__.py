@@ -178,6 +178,31 @@ def static_linear_grouped(x: np.ndarray, s_g: np.ndarray, wq: np.ndarray, s_w: n
     return {"y": y, "f": f, "xq": xq}
 
 
+def dynamic_linear(x: np.ndarray, wq: np.ndarray, s_w: np.ndarray, bias: Optional[np.ndarray],
+                   a_bits: int, w_fmt: str, dtype: str):
+    """Dynamic per-token linear (one absmax factor per row, computed from the row itself).
+    Returns dict(y=uint16 [M,N], acc=int32 [M,N], xq=int8 [M,K], s_row=float32 [M])."""
+    x = _u16(x)
+    M, K = x.shape
+    wq = np.ascontiguousarray(wq)
+    assert wq.dtype in (np.int8, np.uint8)
+    N = wq.shape[0]
+    assert wq.shape[1] == (K if w_fmt == "int8" else K // 2), (wq.shape, K, w_fmt)
+    s_w = np.ascontiguousarray(s_w, dtype=np.float32)
+    assert s_w.shape == (N,)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+    y = np.empty((M, N), dtype=np.uint16)
+    acc = np.empty((M, N), dtype=np.int32)
+    xq = np.empty((M, K), dtype=np.int8)
+    s_row = np.empty((M,), dtype=np.float32)
+    rc = lib().sasq_oracle_dynamic_linear(_p(x), _p(wq), _p(s_w), _p(bias), _p(y), _p(acc), _p(xq), _p(s_row),
+                                          ctypes.c_int64(M), ctypes.c_int64(N), ctypes.c_int64(K),
+                                          int(a_bits), WF[w_fmt], DT[dtype])
+    _check(rc, "dynamic_linear")
+    return {"y": y, "acc": acc, "xq": xq, "s_row": s_row}
+
+
 def quantize_weight(w: np.ndarray, w_fmt: str) -> Tuple[np.ndarray, np.ndarray]:
     """w: fp32 [N,K] -> (wq int8 [N,K] | uint8 [N,K/2], s_w fp32 [N])."""
     w = np.ascontiguousarray(w, dtype=np.float32)

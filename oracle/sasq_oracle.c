@@ -365,6 +365,79 @@ int sasq_oracle_static_linear_grouped(const uint16_t* x, const float* s_g, const
 }
 
 /*
+ * Dynamic per-token linear: the baseline the paper's static factors replace (Sec. 3: dynamic
+ * quantization computes the factors during inference; per-token = one factor per row of X,
+ * Fig. 2(b); Sec. 4.5 compares against it).  For every row m:
+ *     s_m      = fl32(max_k |X[m,k]| / Qp)          (Eq. 1's S on the row; 1 if the row is all zero)
+ *     xq[m,k]  = clamp(RHE(X[m,k] * fl32(1/s_m)))    (Eq. 1)
+ *     acc[m,n] = sum_k xq[m,k] * Wq[n,k]             (exact int32)
+ *     Y[m,n]   = fl32(fl32(acc) * fl32(s_m * s_w[n])) (+ bias[n])       (Eq. 2 with S_x per row)
+ * Inputs must be finite.  s_row_out (optional) receives the M factors.
+ */
+int sasq_oracle_dynamic_linear(const uint16_t* x, const uint8_t* wq, const float* s_w, const float* bias,
+                               uint16_t* y, int32_t* acc_out, int8_t* xq_out, float* s_row_out,
+                               int64_t M, int64_t N, int64_t K, int a_bits, int wf, int dt)
+{
+    int rc = check_common(a_bits, dt);
+    if (rc) return rc;
+    if (wf != WF_INT8 && wf != WF_INT4_PACKED) return ERR_ARG;
+    if (wf == WF_INT4_PACKED && (K & 1)) return ERR_ARG;
+    const int Qn = -(1 << (a_bits - 1)), Qp = (1 << (a_bits - 1)) - 1;
+
+    int8_t* xq = (int8_t*)malloc((size_t)(M * K > 0 ? M * K : 1));
+    int8_t* w8 = (int8_t*)malloc((size_t)(N * K > 0 ? N * K : 1));
+    float* srow = (float*)malloc(sizeof(float) * (size_t)(M > 0 ? M : 1));
+    if (!xq || !w8 || !srow) { free(xq); free(w8); free(srow); return ERR_NOMEM; }
+
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        double amax = 0.0;
+        for (int64_t k = 0; k < K; ++k) { double a = fabs(load16(x, m * K + k, dt)); if (a > amax) amax = a; }
+        volatile float num = (float)amax;            /* exact: a 16-bit float */
+        volatile float den = (float)Qp;
+        volatile float sm = num / den;
+        if (amax == 0.0) sm = 1.0f;
+        srow[m] = sm;
+        const float inv = reciprocal_f32(sm);
+        for (int64_t k = 0; k < K; ++k)
+            xq[m * K + k] = (int8_t)quantize_one(load16(x, m * K + k, dt), inv, Qn, Qp, 0).q;
+    }
+    if (xq_out) memcpy(xq_out, xq, (size_t)(M * K));
+    if (s_row_out) memcpy(s_row_out, srow, sizeof(float) * (size_t)M);
+
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            if (wf == WF_INT8) w8[n * K + k] = (int8_t)wq[n * K + k];
+            else {
+                uint8_t byte = wq[n * (K / 2) + k / 2];
+                w8[n * K + k] = (int8_t)nibble_to_int((k & 1) ? (byte >> 4) : (byte & 15u));
+            }
+        }
+
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            int32_t acc = 0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += (int32_t)xq[m * K + k] * (int32_t)w8[n * K + k];
+            if (acc_out) acc_out[m * N + n] = acc;
+            if (y) {
+                volatile float c = srow[m] * s_w[n];
+                volatile float af = (float)acc;
+                volatile float yf = af * c;
+                if (bias) { volatile float yb = yf + bias[n]; yf = yb; }
+                y[m * N + n] = store16(yf, dt);
+            }
+        }
+    }
+    free(xq);
+    free(w8);
+    free(srow);
+    return OK;
+}
+
+/*
  * Frozen-weight quantization, symmetric, one scale per output channel (row of W[N,K])
  * (Sec. 3, Eq. 1 applied per row; Sec. 5.1 fixes weights to one factor per output channel):
  *   s_w[n] = fl32(max_k |W[n,k]| / Qp)   (1 if the row is all zero)

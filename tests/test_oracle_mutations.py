@@ -43,12 +43,17 @@ MUTATIONS = [
     ("grouped_descending", "for (int64_t i = 0; i < G; ++i) {", "for (int64_t i = G - 1; i >= 0; --i) {"),
     ("grouped_group_bounds", "for (int64_t k = i * group; k < (i + 1) * group; ++k)", "for (int64_t k = i * group; k < K; ++k)"),
     ("grouped_weight_factor_first_channel", "volatile float yf = f * s_w[n];", "volatile float yf = f * s_w[0];"),
+    ("dynamic_uses_first_row_factor", "volatile float c = srow[m] * s_w[n];", "volatile float c = srow[0] * s_w[n];"),
+    ("dynamic_factor_divides_by_128", "volatile float den = (float)Qp;\n        volatile float sm = num / den;",
+     "volatile float den = (float)(Qp + 1);\n        volatile float sm = num / den;"),
+    ("dynamic_zero_row_unhandled", "if (amax == 0.0) sm = 1.0f;", ""),
     ("sgd_plus", "volatile float out = s - step;", "volatile float out = s + step;"),
 ]
 
-PIN_FILES = ["tests/test_oracle_pins.py", "tests/test_oracle_pins_pc.py", "tests/test_oracle_pins_grouped.py"]
+PIN_FILES = ["tests/test_oracle_pins.py", "tests/test_oracle_pins_pc.py", "tests/test_oracle_pins_grouped.py",
+             "tests/test_oracle_pins_dynamic.py"]
 SELECT = ("hand_table or closed_forms or autograd or static_linear or int4 or weight_quantizer or scale_sgd "
-          "or encode or decode or per_channel or ds_terms or reciprocal or epilogue or grouped")
+          "or encode or decode or per_channel or ds_terms or reciprocal or epilogue or grouped or dynamic")
 
 
 def run_pins(src_path: str) -> int:
