@@ -230,6 +230,36 @@ def main():
         grouped["note"] = ("sasq_static_linear_grouped on the projections whose K the group divides "
                            "(gate, up, down for 128; gate, up for 512); warm repeat of 5")
 
+    # dynamic per-token linear (per-row absmax + quantize + the same GEMM + per-row dequantize): the
+    # baseline whose online reduction the static scale removes, on the same tensors
+    dynamic = None
+    if cfg.name == "c3_mlp7b":
+        dynamic = {}
+        tot_ops, tot_ms = 0.0, 0.0
+        for p in projs:
+            wsd = B.new_workspace(B.sasq_dynamic_linear_workspace(p.M, p.N, p.K, p.wf))
+            for _ in range(2):
+                B.sasq_dynamic_linear(p.x, p.wq, p.s_w, None, p.y, p.wf, wsd)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                B.sasq_dynamic_linear(p.x, p.wq, p.s_w, None, p.y, p.wf, wsd)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 5
+            e0.record()
+            for _ in range(5):
+                B.sasq_static_linear(p.x, p.s, p.wq, p.s_w, None, p.y, p.wf, p.ws_lin)
+            e1.record()
+            torch.cuda.synchronize()
+            ms_static = e0.elapsed_time(e1) / 5
+            dynamic[p.name] = {"dynamic_us": round(1e3 * ms, 1), "static_us": round(1e3 * ms_static, 1)}
+            tot_ms += ms
+            tot_ops += p.ops
+        dynamic["achieved"] = round(tot_ops / (tot_ms * 1e-3) / 1e12, 1)
+        dynamic["unit"] = "TOP/s"
+        dynamic["note"] = "sasq_dynamic_linear vs sasq_static_linear, same tensors, warm repeat of 5 each"
+
     out = {
         "metric": "static-scale W8A8 linear TOPS (% int8 MFMA peak); fake-quant fwd+bwd GB/s",
         "value": round(total_ops / (ms_per_step * 1e-3) / 1e12, 2),
@@ -255,6 +285,7 @@ def main():
         "per_projection": per_proj,
         "fakequant_per_channel": pc,
         "static_linear_grouped": grouped,
+        "dynamic_linear": dynamic,
     }
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, a.cpu_rows)

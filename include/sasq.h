@@ -205,6 +205,25 @@ int sasq_static_linear_grouped(const void* x, const float* s_g, const void* wq, 
                                void* stream);
 
 /*
+ * Dynamic per-token quantized linear: the baseline whose online step the static factors remove
+ * (Sec. 3: dynamic quantization computes the factors during inference, per-token = one factor per
+ * row of X; Sec. 4.5 compares against it).  For every row m:
+ *     s_m      = fl32(max_k |X[m,k]| / (2^(a_bits-1) - 1))      (1 if the row is all zero)
+ *     xq[m,k]  = clamp(round(X[m,k] / s_m), -2^(a_bits-1), 2^(a_bits-1) - 1)
+ *     acc[m,n] = sum_k xq[m,k] * Wq[n,k]                        (exact, int32)
+ *     Y[m,n]   = fl32(fl32(acc[m,n]) * fl32(s_m * s_w[n])) (+ bias[n])  -> 16-bit `dt`
+ *   x must be finite.  s_row_out [M] device fp32 or NULL: the factors (inspection, tests, or use as
+ *   an absmax calibration pass).  acc_out, xq_out, wq, s_w, bias, y, shapes, weight formats
+ *   and limits as in sasq_static_linear.
+ *   workspace >= sasq_dynamic_linear_workspace(M, N, K, wf) bytes.
+ */
+size_t sasq_dynamic_linear_workspace(int64_t M, int64_t N, int64_t K, sasq_wfmt wf);
+int sasq_dynamic_linear(const void* x, const void* wq, const float* s_w, const float* bias, void* y,
+                        int32_t* acc_out, int8_t* xq_out, float* s_row_out,
+                        int64_t M, int64_t N, int64_t K, int a_bits, sasq_wfmt wf, sasq_dtype dt,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Quantize frozen weights, symmetric, one factor per output channel (Sec. 3, Eq. 1 applied to
  * each row of W[N,K]; Sec. 5.1 fixes the weight granularity to per output channel):
  *     s_w[n]  = fl32(max_k |W[n,k]| / Qp)     (1 if the row is all zero),  Qp = 127 or 7

@@ -58,6 +58,9 @@ def _lib() -> ctypes.CDLL:
         L.sasq_static_linear_workspace.argtypes = [i64, i64, i64, i32]
         L.sasq_static_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, sz, vp]
         L.sasq_static_linear_grouped.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, i32, i32, vp, sz, vp]
+        L.sasq_dynamic_linear_workspace.restype = sz
+        L.sasq_dynamic_linear_workspace.argtypes = [i64, i64, i64, i32]
+        L.sasq_dynamic_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, sz, vp]
         L.sasq_quantize_weight.argtypes = [vp, vp, vp, i64, i64, i32, vp]
         L.sasq_packed_weight_bytes.restype = sz
         L.sasq_packed_weight_bytes.argtypes = [i64, i64, i32]
@@ -236,6 +239,34 @@ def sasq_static_linear_grouped(x: torch.Tensor, s_g: torch.Tensor, wq: torch.Ten
     _check(_lib().sasq_static_linear_grouped(_ptr(x), _ptr(s_g), _ptr(wq), _ptr(s_w), _ptr(bias), _ptr(y), _ptr(f_out),
                                              _ptr(xq_out), M, N, K, group, a_bits, wf, _dt(x), _ptr(workspace), wsb,
                                              _stream()), "sasq_static_linear_grouped")
+
+
+def sasq_dynamic_linear_workspace(M: int, N: int, K: int, wf: int) -> int:
+    return int(_lib().sasq_dynamic_linear_workspace(M, N, K, wf))
+
+
+def sasq_dynamic_linear(x: torch.Tensor, wq: torch.Tensor, s_w: torch.Tensor, bias: Optional[torch.Tensor],
+                        y: torch.Tensor, wf: int = SASQ_W_INT8, workspace: Optional[torch.Tensor] = None,
+                        acc_out: Optional[torch.Tensor] = None, xq_out: Optional[torch.Tensor] = None,
+                        s_row_out: Optional[torch.Tensor] = None, a_bits: int = 8) -> None:
+    _want(s_w, torch.float32, "s_w"); _want(bias, torch.float32, "bias"); _want(s_row_out, torch.float32, "s_row_out")
+    _want(acc_out, torch.int32, "acc_out"); _want(xq_out, torch.int8, "xq_out")
+    if wq.dtype not in (torch.int8, torch.uint8):
+        raise TypeError("wq must be int8 (or uint8 bytes for packed int4 / pre-arranged weights)")
+    M, K = x.shape
+    N = y.shape[1]
+    if wf in (SASQ_W_INT8_BLOCKED, SASQ_W_INT4_BLOCKED):
+        ok = wq.numel() == sasq_packed_weight_bytes(N, K, wf)
+    else:
+        ok = tuple(wq.shape) == (N, K if wf == SASQ_W_INT8 else K // 2)
+    if not ok or y.shape[0] != M or y.dtype != x.dtype:
+        raise ValueError("shape mismatch between x, wq and y")
+    if s_w.numel() != N or (bias is not None and bias.numel() != N) or (s_row_out is not None and s_row_out.numel() != M):
+        raise ValueError("s_w / bias must have N elements, s_row_out M")
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib().sasq_dynamic_linear(_ptr(x), _ptr(wq), _ptr(s_w), _ptr(bias), _ptr(y), _ptr(acc_out), _ptr(xq_out),
+                                      _ptr(s_row_out), M, N, K, a_bits, wf, _dt(x), _ptr(workspace), wsb, _stream()),
+           "sasq_dynamic_linear")
 
 
 def sasq_quantize_weight(w: torch.Tensor, wq: torch.Tensor, s_w: torch.Tensor, wf: int = SASQ_W_INT8) -> None:

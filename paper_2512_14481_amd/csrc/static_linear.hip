@@ -111,6 +111,73 @@ __global__ __launch_bounds__(256) void quantize_act_grouped_elem_kernel(
     }
 }
 
+// Dynamic per-token pre-pass (the online step static factors remove, Sec. 3): one workgroup per
+// row finds the row's absmax (an integer max of 15-bit magnitudes: exact, order-independent),
+// forms s_m = fl32(absmax / Qp) (1 for an all-zero row), then re-reads the row (it is in L2) and
+// quantizes it with s_m.  VEC: K % 8 == 0, 128-bit accesses, optional staging layout; otherwise
+// element by element, row-major only.
+template <int DT, bool PERM8, bool TILED, bool VEC>
+__global__ __launch_bounds__(256) void quantize_rows_kernel(
+    const uint16_t* __restrict__ x, int8_t* __restrict__ xq, float* __restrict__ s_row, int K, int bits)
+{
+    using S = Store16<DT>;
+    __shared__ uint32_t sh[4];
+    const int64_t m = blockIdx.x;
+    const uint16_t* row = x + m * K;
+    uint32_t mx = 0;
+    if (VEC) {
+        const u32x4* rv = reinterpret_cast<const u32x4*>(row);
+        for (int i = threadIdx.x; i < (K >> 3); i += 256) {
+            const u32x4 v = rv[i];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const uint32_t lo = v[w] & 0x7FFFu, hi = (v[w] >> 16) & 0x7FFFu;
+                mx = lo > mx ? lo : mx;
+                mx = hi > mx ? hi : mx;
+            }
+        }
+    } else {
+        for (int i = threadIdx.x; i < K; i += 256) {
+            const uint32_t a = row[i] & 0x7FFFu;
+            mx = a > mx ? a : mx;
+        }
+    }
+    mx = wave_max(mx);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = max(max(sh[0], sh[1]), max(sh[2], sh[3]));
+    const float sm = mx == 0 ? 1.0f : S::one((uint16_t)mx) / (float)((1 << (bits - 1)) - 1);
+    if (threadIdx.x == 0) s_row[m] = sm;
+    const QConst k = make_qconst(sm, bits);
+    if (VEC) {
+        const u32x4* rv = reinterpret_cast<const u32x4*>(row);
+        for (int i = threadIdx.x; i < (K >> 3); i += 256) {
+            const u32x4 v = rv[i];
+            float c[8];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                c[2 * w] = quantize(S::lo(v[w]), k).c;
+                c[2 * w + 1] = quantize(S::hi(v[w]), k).c;
+            }
+            u32x2 o;
+            if (PERM8) { o[0] = pack_codes4(c[0], c[2], c[4], c[6]); o[1] = pack_codes4(c[1], c[3], c[5], c[7]); }
+            else       { o[0] = pack_codes4(c[0], c[1], c[2], c[3]); o[1] = pack_codes4(c[4], c[5], c[6], c[7]); }
+            const int k0 = i << 3;
+            if (TILED) {
+                const int r = (int)(m & 15), ch = (k0 & 63) >> 4;
+                const int64_t blk = (m >> 4) * (K >> 6) + (k0 >> 6);
+                const int64_t off = blk * 1024 + ((4 * r + (ch ^ swz64(r))) << 4) + (k0 & 15);
+                *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(xq) + off) = o;
+            } else {
+                *reinterpret_cast<u32x2*>(xq + m * K + k0) = o;
+            }
+        }
+    } else {
+        for (int i = threadIdx.x; i < K; i += 256)
+            xq[m * K + i] = (int8_t)code_of(quantize(S::one(row[i]), k));
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Epilogue arithmetic, identical on every path:  y = fl32(fl32(acc) * fl32(s*s_w[n])) (+ bias).
 // ---------------------------------------------------------------------------------------------
@@ -125,7 +192,7 @@ __device__ __forceinline__ float dequant(int acc, float c, float bias, bool has_
 // Scalar kernel for shapes the MFMA kernel does not take (K not a multiple of 64): one thread
 // per output element over pre-quantized activations.
 // ---------------------------------------------------------------------------------------------
-template <int DT, bool INT4>
+template <int DT, bool INT4, bool ROWS = false>
 __global__ __launch_bounds__(256) void linear_scalar_kernel(
     const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq, const float* __restrict__ s_ptr,
     const float* __restrict__ s_w, const float* __restrict__ bias, uint16_t* __restrict__ y,
@@ -148,7 +215,7 @@ __global__ __launch_bounds__(256) void linear_scalar_kernel(
         const int8_t* wr = reinterpret_cast<const int8_t*>(wq) + n * K;
         for (int64_t k = 0; k < K; ++k) acc += (int)xr[k] * (int)wr[k];
     }
-    const float c = *s_ptr * s_w[n];
+    const float c = s_ptr[ROWS ? m : 0] * s_w[n];      // ROWS: one factor per row (dynamic per-token)
     y[idx] = S::enc(dequant(acc, c, bias ? bias[n] : 0.0f, bias != nullptr));
     if (acc_out) acc_out[idx] = acc;
 }
@@ -283,7 +350,9 @@ enum { W_I8 = 0, W_I4 = 1, W_I8B = 2, W_I4B = 3 };
 // group's end, f = fma(fl32(acc), s_g, f) in ascending group order; the epilogue applies s_w and
 // the bias to f.  acc_out then receives f (as float).  Needs tiles with at most 128 accumulators
 // per lane (128x256, 128x128), as f takes as many registers again.
-template <int DT, int XMODE, int WMODE, int BM, int BN, bool GROUPED = false>
+// ROWS: one activation factor per row of X (dynamic per-token quantization, the baseline of
+// Sec. 3 / Sec. 4.5): s_ptr points at the M factors and the epilogue uses fl32(s_m * s_w[n]).
+template <int DT, int XMODE, int WMODE, int BM, int BN, bool GROUPED = false, bool ROWS = false>
 __global__ __launch_bounds__(kGemmThreads)
 __attribute__((amdgpu_waves_per_eu(Tile<BM, BN>::kWavesPerSimd, Tile<BM, BN>::kWavesPerSimd)))
 void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict__ wq,
@@ -295,6 +364,7 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
     using S = Store16<DT>;
     using T = Tile<BM, BN>;
     static_assert(!GROUPED || (BM == 128 && XMODE == X_PREQ), "grouped factors: 128-row tiles over staged activations");
+    static_assert(!ROWS || (!GROUPED && XMODE == X_PREQ), "per-row factors: staged activations");
     constexpr int MF = T::MF, NF = T::NF, XS = T::XS, WS = T::WS;
     __shared__ __attribute__((aligned(1024))) char lds[T::kLds];
     auto stage_ptr = [&](int st, int operand) -> char* { return &lds[st * T::kStageBytes + operand * T::kXBytes]; };
@@ -614,7 +684,7 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int ne = min(wn0 + nl + e, N - 1);
-                c[e] = GROUPED ? s_w[ne] : s * s_w[ne];
+                c[e] = (GROUPED || ROWS) ? s_w[ne] : s * s_w[ne];
                 bz[e] = has_bias ? bias[ne] : 0.0f;
             }
 #pragma unroll
@@ -635,10 +705,15 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
                     pk[0] = S::pack(fv[0], fv[1]);
                     pk[1] = S::pack(fv[2], fv[3]);
                 } else {
+                    float cc[4];
+                    const float sr = ROWS ? s_ptr[min(wm0 + ml, M - 1)] : 1.0f;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) av[e] = acc[a][b][4 * g + e] >> kAccShift;
-                    pk[0] = S::pack(dequant(av[0], c[0], bz[0], has_bias), dequant(av[1], c[1], bz[1], has_bias));
-                    pk[1] = S::pack(dequant(av[2], c[2], bz[2], has_bias), dequant(av[3], c[3], bz[3], has_bias));
+                    for (int e = 0; e < 4; ++e) {
+                        av[e] = acc[a][b][4 * g + e] >> kAccShift;
+                        cc[e] = ROWS ? sr * c[e] : c[e];
+                    }
+                    pk[0] = S::pack(dequant(av[0], cc[0], bz[0], has_bias), dequant(av[1], cc[1], bz[1], has_bias));
+                    pk[1] = S::pack(dequant(av[2], cc[2], bz[2], has_bias), dequant(av[3], cc[3], bz[3], has_bias));
                 }
                 *reinterpret_cast<u32x2*>(epi + ml * T::kEpiStride + nl * 2) = pk;
                 if (acc_out) {
@@ -699,14 +774,14 @@ static bool choose_fused(int64_t M, int64_t N, int64_t K)
     return N <= kFusedMaxN;
 }
 
-template <int DT, int XMODE, int WMODE, int BM, int BN, bool GROUPED = false>
+template <int DT, int XMODE, int WMODE, int BM, int BN, bool GROUPED = false, bool ROWS = false>
 static void launch_tiles(const void* xin, const void* wq, const float* s, const float* s_w, const float* bias,
                          void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K, int a_bits, hipStream_t st,
                          int group_tiles = 0)
 {
     const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
     const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-    linear_mfma_kernel<DT, XMODE, WMODE, BM, BN, GROUPED><<<grid, kGemmThreads, 0, st>>>(
+    linear_mfma_kernel<DT, XMODE, WMODE, BM, BN, GROUPED, ROWS><<<grid, kGemmThreads, 0, st>>>(
         xin, static_cast<const uint8_t*>(wq), s, s_w, bias, static_cast<uint16_t*>(y), acc_out,
         (int)M, (int)N, (int)K, a_bits, tiles_m, tiles_n, group_tiles);
 }
@@ -847,6 +922,48 @@ static void run_linear_grouped(const void* x, const float* s_g, const void* wq, 
     }
 }
 
+template <int DT, int WMODE>
+static void launch_mfma_rows(const void* xin, const void* wq, const float* s_row, const float* s_w, const float* bias,
+                             void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K, int a_bits, hipStream_t st)
+{
+    switch (choose_tile(M, N)) {
+        case 0: launch_tiles<DT, X_PREQ, WMODE, 256, 256, false, true>(xin, wq, s_row, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
+        case 1: launch_tiles<DT, X_PREQ, WMODE, 128, 256, false, true>(xin, wq, s_row, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
+        default: launch_tiles<DT, X_PREQ, WMODE, 128, 128, false, true>(xin, wq, s_row, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
+    }
+}
+
+template <int DT>
+static void run_dynamic(const void* x, const void* wq, const float* s_w, const float* bias, void* y, int32_t* acc_out,
+                        int8_t* xq_out, float* s_row, int64_t M, int64_t N, int64_t K, int a_bits, sasq_wfmt wf,
+                        int8_t* xq_ws, hipStream_t st)
+{
+    auto X = static_cast<const uint16_t*>(x);
+    const bool vec = (K % 8) == 0;
+    auto quantize_rowmajor = [&](int8_t* dst) {
+        if (vec) quantize_rows_kernel<DT, false, false, true><<<(int)M, 256, 0, st>>>(X, dst, s_row, (int)K, a_bits);
+        else     quantize_rows_kernel<DT, false, false, false><<<(int)M, 256, 0, st>>>(X, dst, s_row, (int)K, a_bits);
+    };
+    if (xq_out) quantize_rowmajor(xq_out);
+    if ((K % kBK) == 0) {
+        if (wf == SASQ_W_INT4_PACKED) quantize_rows_kernel<DT, true, true, true><<<(int)M, 256, 0, st>>>(X, xq_ws, s_row, (int)K, a_bits);
+        else                          quantize_rows_kernel<DT, false, true, true><<<(int)M, 256, 0, st>>>(X, xq_ws, s_row, (int)K, a_bits);
+        switch (wf) {
+            case SASQ_W_INT8:         launch_mfma_rows<DT, W_I8>(xq_ws, wq, s_row, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
+            case SASQ_W_INT4_PACKED:  launch_mfma_rows<DT, W_I4>(xq_ws, wq, s_row, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
+            case SASQ_W_INT8_BLOCKED: launch_mfma_rows<DT, W_I8B>(xq_ws, wq, s_row, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
+            default:                  launch_mfma_rows<DT, W_I4B>(xq_ws, wq, s_row, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
+        }
+    } else {
+        quantize_rowmajor(xq_ws);
+        const int64_t blocks = (M * N + 255) / 256;
+        auto W = static_cast<const uint8_t*>(wq);
+        auto Y = static_cast<uint16_t*>(y);
+        if (wf == SASQ_W_INT4_PACKED) linear_scalar_kernel<DT, true, true><<<(int)blocks, 256, 0, st>>>(xq_ws, W, s_row, s_w, bias, Y, acc_out, M, N, K);
+        else                          linear_scalar_kernel<DT, false, true><<<(int)blocks, 256, 0, st>>>(xq_ws, W, s_row, s_w, bias, Y, acc_out, M, N, K);
+    }
+}
+
 }  // namespace sasq
 
 using namespace sasq;
@@ -915,5 +1032,43 @@ extern "C" int sasq_static_linear_grouped(const void* x, const float* s_g, const
     int8_t* xq_ws = static_cast<int8_t*>(workspace);
     if (dt == SASQ_F16) run_linear_grouped<SASQ_F16>(x, s_g, wq, s_w, bias, y, f_out, xq_out, M, N, K, group, a_bits, wf, xq_ws, st);
     else                run_linear_grouped<SASQ_BF16>(x, s_g, wq, s_w, bias, y, f_out, xq_out, M, N, K, group, a_bits, wf, xq_ws, st);
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+extern "C" size_t sasq_dynamic_linear_workspace(int64_t M, int64_t N, int64_t K, sasq_wfmt wf)
+{
+    if (M <= 0 || K <= 0) return 0;
+    return sasq_static_linear_workspace(M, N, K, wf) + round_up(sizeof(float) * (size_t)M, 256);   // codes + row factors
+}
+
+extern "C" int sasq_dynamic_linear(const void* x, const void* wq, const float* s_w, const float* bias, void* y,
+                                   int32_t* acc_out, int8_t* xq_out, float* s_row_out,
+                                   int64_t M, int64_t N, int64_t K, int a_bits, sasq_wfmt wf, sasq_dtype dt,
+                                   void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !wq || !s_w || !y) return SASQ_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0) return SASQ_ERR_SHAPE;
+    const int64_t lim = INT64_C(1) << 40;
+    if (M > lim / K || N > lim / K || M > lim / N || K > 131071 || M > 0x7FFFFFFF || N > 0x7FFFFFFF) return SASQ_ERR_SHAPE;
+    if (a_bits < 2 || a_bits > 8) return SASQ_ERR_UNSUPPORTED;
+    if (wf != SASQ_W_INT8 && wf != SASQ_W_INT4_PACKED && wf != SASQ_W_INT8_BLOCKED && wf != SASQ_W_INT4_BLOCKED)
+        return SASQ_ERR_UNSUPPORTED;
+    if (dt != SASQ_F16 && dt != SASQ_BF16) return SASQ_ERR_UNSUPPORTED;
+    if (wf == SASQ_W_INT4_PACKED && (K & 1)) return SASQ_ERR_SHAPE;
+    if ((wf == SASQ_W_INT8_BLOCKED || wf == SASQ_W_INT4_BLOCKED) && (K % kBK)) return SASQ_ERR_SHAPE;
+    if ((M * N + 255) / 256 > 0x7FFFFFFF) return SASQ_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(wq) || !aligned16(y) || (acc_out && !aligned16(acc_out)) ||
+        (xq_out && (reinterpret_cast<uintptr_t>(xq_out) & 7u)) || (s_row_out && (reinterpret_cast<uintptr_t>(s_row_out) & 3u)))
+        return SASQ_ERR_ALIGN;
+    const size_t need = sasq_dynamic_linear_workspace(M, N, K, wf);
+    if (!workspace || workspace_bytes < need) return SASQ_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SASQ_ERR_ALIGN;
+
+    hipStream_t st = as_stream(stream);
+    int8_t* xq_ws = static_cast<int8_t*>(workspace);
+    float* s_row = s_row_out ? s_row_out
+                             : reinterpret_cast<float*>(static_cast<char*>(workspace) + sasq_static_linear_workspace(M, N, K, wf));
+    if (dt == SASQ_F16) run_dynamic<SASQ_F16>(x, wq, s_w, bias, y, acc_out, xq_out, s_row, M, N, K, a_bits, wf, xq_ws, st);
+    else                run_dynamic<SASQ_BF16>(x, wq, s_w, bias, y, acc_out, xq_out, s_row, M, N, K, a_bits, wf, xq_ws, st);
     return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
 }

@@ -105,6 +105,20 @@ def test_host_side_validation(lib):
     assert lg(*gargs(wf=9)) == 4
     assert lg(*gargs(bits=1)) == 4
     assert lg(*gargs(ws=None)) == 5
+    dl = lib.sasq_dynamic_linear
+    dargs = lambda **kw: [kw.get("x", good), good, good, None, good, None, None, None,
+                          i64(kw.get("M", 4)), i64(4), i64(kw.get("K", 128)), kw.get("bits", 8),
+                          kw.get("wf", 0), 0, kw.get("ws", good), kw.get("wsb", big), None]
+    assert dl(*dargs(x=None)) == 1
+    assert dl(*dargs(M=0)) == 2
+    assert dl(*dargs(K=96, wf=2)) == 2
+    assert dl(*dargs(wf=4)) == 4
+    assert dl(*dargs(bits=9)) == 4
+    assert dl(*dargs(wsb=ctypes.c_size_t(16))) == 5
+    lib.sasq_dynamic_linear_workspace.restype = ctypes.c_size_t
+    lib.sasq_static_linear_workspace.restype = ctypes.c_size_t
+    assert (lib.sasq_dynamic_linear_workspace(i64(100), i64(4), i64(128), 0)
+            >= lib.sasq_static_linear_workspace(i64(100), i64(4), i64(128), 0) + 400)
     qw = lib.sasq_quantize_weight
     assert qw(None, good, good, i64(4), i64(4), 0, None) == 1
     assert qw(good, good, good, i64(4), i64(3), 1, None) == 2
