@@ -16,7 +16,8 @@ constexpr int kPcThreads = 256;
 constexpr int kPcWaves = kPcThreads / kWave;
 constexpr int kPcColsPerBlock = kWave * 8;        // 512
 constexpr int kPcRowUnroll = 4;                   // rows in flight per wave
-constexpr int kPcMaxRowChunks = 64;
+constexpr int kPcMaxRowChunks = 128;              // more row chunks than this lengthen the reduction tail (measured)
+constexpr int kPcTargetBlocks = 2048;             // 8 blocks per CU
 
 struct PcConst {
     float inv_s[8];
@@ -55,37 +56,59 @@ __global__ __launch_bounds__(kPcThreads) void fakequant_fwd_pc_kernel(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t col0 = (int64_t)blockIdx.x * kPcColsPerBlock + lane * 8;
     if (col0 >= cols) return;
-    const PcConst c = load_pc(s, col0, cols, bits);
     const int64_t r_begin = (int64_t)blockIdx.y * rows_per_chunk;
     const int64_t r_end = min(rows, r_begin + rows_per_chunk);
-    for (int64_t r = r_begin + wave; r < r_end; r += kPcWaves * kPcRowUnroll) {
-        u32x4 in[kPcRowUnroll];
+    // Groups of kPcRowUnroll rows per wave, double-buffered: the next group's loads are in flight
+    // while the current one is computed, and the first group's loads are issued before the
+    // column factors are fetched and inverted (few waves per CU: latency must be hidden in-wave).
+    constexpr int64_t kStep = kPcWaves * kPcRowUnroll;
+    auto full = [&](int64_t rr) { return rr + (kPcRowUnroll - 1) * kPcWaves < r_end; };
+    auto load_group = [&](u32x4 (&buf)[kPcRowUnroll], int64_t rr) {
 #pragma unroll
-        for (int u = 0; u < kPcRowUnroll; ++u) {
-            const int64_t rr = min(r + u * kPcWaves, r_end - 1);
-            in[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + rr * cols + col0));
+        for (int u = 0; u < kPcRowUnroll; ++u)
+            buf[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + (rr + u * kPcWaves) * cols + col0));
+    };
+    int64_t r = r_begin + wave;
+    u32x4 bufa[kPcRowUnroll], bufb[kPcRowUnroll];
+    bool have = full(r);
+    if (have) load_group(bufa, r);
+    const PcConst c = load_pc(s, col0, cols, bits);
+    auto one_row = [&](const u32x4 in, int64_t rr) {
+        u32x4 out;
+        float cc[8];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            QElem a = quantize_pc(S::lo(in[w]), c.inv_s[2 * w], c);
+            QElem b = quantize_pc(S::hi(in[w]), c.inv_s[2 * w + 1], c);
+            out[w] = S::pack(codef_of(a) * c.s[2 * w], codef_of(b) * c.s[2 * w + 1]);
+            cc[2 * w] = a.c;
+            cc[2 * w + 1] = b.c;
         }
-#pragma unroll
-        for (int u = 0; u < kPcRowUnroll; ++u) {
-            const int64_t rr = r + u * kPcWaves;
-            if (rr >= r_end) break;
-            u32x4 out;
-            float cc[8];
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                QElem a = quantize_pc(S::lo(in[u][w]), c.inv_s[2 * w], c);
-                QElem b = quantize_pc(S::hi(in[u][w]), c.inv_s[2 * w + 1], c);
-                out[w] = S::pack(codef_of(a) * c.s[2 * w], codef_of(b) * c.s[2 * w + 1]);
-                cc[2 * w] = a.c;
-                cc[2 * w + 1] = b.c;
-            }
-            __builtin_nontemporal_store(out, reinterpret_cast<u32x4*>(y + rr * cols + col0));
-            if (CODES) {
-                u32x2 cw = {pack_codes4(cc[0], cc[1], cc[2], cc[3]), pack_codes4(cc[4], cc[5], cc[6], cc[7])};
-                *reinterpret_cast<u32x2*>(codes + rr * cols + col0) = cw;
-            }
+        __builtin_nontemporal_store(out, reinterpret_cast<u32x4*>(y + rr * cols + col0));
+        if (CODES) {
+            u32x2 cw = {pack_codes4(cc[0], cc[1], cc[2], cc[3]), pack_codes4(cc[4], cc[5], cc[6], cc[7])};
+            *reinterpret_cast<u32x2*>(codes + rr * cols + col0) = cw;
         }
+    };
+    // full groups without per-row predication (a clamp or an early exit inside the unrolled loop
+    // makes the compiler serialize the loads), then the leftover rows
+    while (have) {
+        bool more = full(r + kStep);
+        if (more) load_group(bufb, r + kStep);
+#pragma unroll
+        for (int u = 0; u < kPcRowUnroll; ++u) one_row(bufa[u], r + u * kPcWaves);
+        r += kStep;
+        have = more;
+        if (!have) break;
+        more = full(r + kStep);
+        if (more) load_group(bufa, r + kStep);
+#pragma unroll
+        for (int u = 0; u < kPcRowUnroll; ++u) one_row(bufb[u], r + u * kPcWaves);
+        r += kStep;
+        have = more;
     }
+    for (; r < r_end; r += kPcWaves)
+        one_row(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + r * cols + col0)), r);
 }
 
 template <int DT, bool WRITE_DX>
@@ -103,49 +126,81 @@ __global__ __launch_bounds__(kPcThreads) void fakequant_bwd_pc_kernel(
     const bool active = col0 < cols;
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (active) {
-        const PcConst c = load_pc(s, col0, cols, bits);
         const int64_t r_begin = (int64_t)blockIdx.y * rows_per_chunk;
         const int64_t r_end = min(rows, r_begin + rows_per_chunk);
-        for (int64_t r = r_begin + wave; r < r_end; r += kPcWaves * kPcRowUnroll) {
-            u32x4 xin[kPcRowUnroll], gin[kPcRowUnroll];
+        // same double-buffered traversal as the forward kernel, two input streams
+        constexpr int64_t kStep = kPcWaves * kPcRowUnroll;
+        auto full = [&](int64_t rr) { return rr + (kPcRowUnroll - 1) * kPcWaves < r_end; };
+        auto load_group = [&](u32x4 (&bx)[kPcRowUnroll], u32x4 (&bg)[kPcRowUnroll], int64_t rr) {
 #pragma unroll
             for (int u = 0; u < kPcRowUnroll; ++u) {
-                const int64_t rr = min(r + u * kPcWaves, r_end - 1);
-                xin[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + rr * cols + col0));
-                gin[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(dy + rr * cols + col0));
+                bx[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + (rr + u * kPcWaves) * cols + col0));
+                bg[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(dy + (rr + u * kPcWaves) * cols + col0));
             }
+        };
+        int64_t r = r_begin + wave;
+        u32x4 xa_[kPcRowUnroll], ga_[kPcRowUnroll], xb_[kPcRowUnroll], gb_[kPcRowUnroll];
+        bool have = full(r);
+        if (have) load_group(xa_, ga_, r);
+        const PcConst c = load_pc(s, col0, cols, bits);
+        auto one_row = [&](const u32x4 xin, const u32x4 gin, int64_t rr) {
+            u32x4 out;
 #pragma unroll
-            for (int u = 0; u < kPcRowUnroll; ++u) {
-                const int64_t rr = r + u * kPcWaves;
-                if (rr >= r_end) break;
-                u32x4 out;
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    const float xa = S::lo(xin[u][w]), xb = S::hi(xin[u][w]);
-                    QElem a = quantize_pc(xa, c.inv_s[2 * w], c);
-                    QElem b = quantize_pc(xb, c.inv_s[2 * w + 1], c);
-                    const bool ka = unclipped(a), kb = unclipped(b);
-                    const float qa = codef_of(a), qb = codef_of(b);
-                    const float ua = __builtin_fmaf(-xa, c.inv_s[2 * w], qa), ub = __builtin_fmaf(-xb, c.inv_s[2 * w + 1], qb);
-                    acc[2 * w] += S::lo(gin[u][w]) * (ka ? ua : qa);
-                    acc[2 * w + 1] += S::hi(gin[u][w]) * (kb ? ub : qb);
-                    out[w] = gin[u][w] & ((ka ? 0x0000FFFFu : 0u) | (kb ? 0xFFFF0000u : 0u));
-                }
-                if (WRITE_DX) __builtin_nontemporal_store(out, reinterpret_cast<u32x4*>(dx + rr * cols + col0));
+            for (int w = 0; w < 4; ++w) {
+                const float xa = S::lo(xin[w]), xb = S::hi(xin[w]);
+                QElem a = quantize_pc(xa, c.inv_s[2 * w], c);
+                QElem b = quantize_pc(xb, c.inv_s[2 * w + 1], c);
+                const bool ka = unclipped(a), kb = unclipped(b);
+                const float qa = codef_of(a), qb = codef_of(b);
+                const float ua = __builtin_fmaf(-xa, c.inv_s[2 * w], qa), ub = __builtin_fmaf(-xb, c.inv_s[2 * w + 1], qb);
+                acc[2 * w] += S::lo(gin[w]) * (ka ? ua : qa);
+                acc[2 * w + 1] += S::hi(gin[w]) * (kb ? ub : qb);
+                out[w] = gin[w] & ((ka ? 0x0000FFFFu : 0u) | (kb ? 0xFFFF0000u : 0u));
             }
+            if (WRITE_DX) __builtin_nontemporal_store(out, reinterpret_cast<u32x4*>(dx + rr * cols + col0));
+        };
+        // full groups, then the leftover rows (same row order per wave either way)
+        while (have) {
+            bool more = full(r + kStep);
+            if (more) load_group(xb_, gb_, r + kStep);
+#pragma unroll
+            for (int u = 0; u < kPcRowUnroll; ++u) one_row(xa_[u], ga_[u], r + u * kPcWaves);
+            r += kStep;
+            have = more;
+            if (!have) break;
+            more = full(r + kStep);
+            if (more) load_group(xa_, ga_, r + kStep);
+#pragma unroll
+            for (int u = 0; u < kPcRowUnroll; ++u) one_row(xb_[u], gb_[u], r + u * kPcWaves);
+            r += kStep;
+            have = more;
         }
+        for (; r < r_end; r += kPcWaves)
+            one_row(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + r * cols + col0)),
+                    __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(dy + r * cols + col0)), r);
     }
     // block partial per column: waves in fixed order
 #pragma unroll
     for (int e = 0; e < 8; ++e) red[wave][lane * 8 + e] = acc[e];
     __syncthreads();
     const int nchunks = gridDim.y;
-    for (int cidx = threadIdx.x; cidx < kPcColsPerBlock; cidx += kPcThreads) {
-        float v = 0.0f;
+    // One 128-bit store per 4 columns, with the agent-scope cache policy the compiler gives its own
+    // agent-scope atomic stores (sc1): 4-byte stores of the same data are four times as many
+    // write-through transactions, and every block waits for their acknowledgement below.
+    if (threadIdx.x < kPcColsPerBlock / 4) {
+        const int c4 = threadIdx.x * 4;
+        f32x4 v;
 #pragma unroll
-        for (int w = 0; w < kPcWaves; ++w) v += red[w][cidx];
-        if (cbase + cidx < cols)
-            __hip_atomic_store(&partials[(int64_t)blockIdx.y * cols + cbase + cidx], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int e = 0; e < 4; ++e) {
+            float a = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kPcWaves; ++w) a += red[w][c4 + e];
+            v[e] = a;
+        }
+        if (cbase + c4 < cols) {        // cols is a multiple of 8: a group of 4 is all in or all out
+            float* dst = &partials[(int64_t)blockIdx.y * cols + cbase + c4];
+            asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(dst), "v"(v) : "memory");
+        }
     }
     // the stores above are agent-scope and acknowledged before the ticket is taken
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -157,22 +212,36 @@ __global__ __launch_bounds__(kPcThreads) void fakequant_bwd_pc_kernel(
     }
     __syncthreads();
     if (!is_last) return;
-    // last block of this column chunk: row chunks summed in order, in fp64
+    // last block of this column chunk: row chunks summed in ascending order, in fp64.  A thread
+    // takes columns tid and tid + 256 and keeps 2 x 32 partial loads in flight (loading them a
+    // few at a time leaves the whole grid's tail waiting on a chain of memory latencies).
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    for (int cidx = threadIdx.x; cidx < kPcColsPerBlock; cidx += kPcThreads) {
-        if (cbase + cidx >= cols) continue;
-        double t = 0.0;
-        for (int rc0 = 0; rc0 < nchunks; rc0 += 8) {
-            float pv[8];        // eight loads in flight, then added in row-chunk order
+    {
+        constexpr int kBatch = 32;
+        int64_t colv[2];
+        bool ok[2];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
+        for (int h = 0; h < 2; ++h) {
+            const int64_t cc = cbase + threadIdx.x + h * kPcThreads;
+            ok[h] = cc < cols;
+            colv[h] = ok[h] ? cc : cols - 1;
+        }
+        double t0 = 0.0, t1 = 0.0;
+        for (int rc0 = 0; rc0 < nchunks; rc0 += kBatch) {
+            float pv[2][kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
                 const int rc = rc0 + j < nchunks ? rc0 + j : nchunks - 1;
-                pv[j] = __hip_atomic_load(&partials[(int64_t)rc * cols + cbase + cidx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    pv[h][j] = __hip_atomic_load(&partials[(int64_t)rc * cols + colv[h]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
 #pragma unroll
-            for (int j = 0; j < 8; ++j) t += rc0 + j < nchunks ? (double)pv[j] : 0.0;
+            for (int j = 0; j < kBatch; ++j)
+                if (rc0 + j < nchunks) { t0 += (double)pv[0][j]; t1 += (double)pv[1][j]; }
         }
-        ds[cbase + cidx] = (float)t;
+        if (ok[0]) ds[colv[0]] = (float)t0;
+        if (ok[1]) ds[colv[1]] = (float)t1;
     }
     if (threadIdx.x == 0) __hip_atomic_store(&tickets[blockIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -208,8 +277,8 @@ __global__ void fakequant_pc_scalar_kernel(const uint16_t* __restrict__ x, const
 
 static int pc_row_chunks(int64_t rows, int64_t col_blocks)
 {
-    // enough blocks to fill the chip (~512), at least 16 rows per block, at most kPcMaxRowChunks
-    int64_t want = (512 + col_blocks - 1) / col_blocks;
+    // enough blocks to fill the chip, at least 16 rows per block, at most kPcMaxRowChunks
+    int64_t want = (kPcTargetBlocks + col_blocks - 1) / col_blocks;
     int64_t by_rows = (rows + 15) / 16;
     int64_t rc = want < by_rows ? want : by_rows;
     if (rc < 1) rc = 1;
@@ -248,8 +317,9 @@ extern "C" int sasq_fakequant_fwd_pc(const void* x, const float* s, void* y, int
         return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
     }
     const int64_t col_blocks = (cols + kPcColsPerBlock - 1) / kPcColsPerBlock;
-    const int chunks = pc_row_chunks(rows, col_blocks);
-    const int64_t rpc = (rows + chunks - 1) / chunks;
+    // rows per chunk: a multiple of 16 (whole unpredicated groups in every chunk but the last)
+    const int64_t rpc = ((rows + pc_row_chunks(rows, col_blocks) - 1) / pc_row_chunks(rows, col_blocks) + 15) / 16 * 16;
+    const int chunks = (int)((rows + rpc - 1) / rpc);
     dim3 grid((unsigned)col_blocks, (unsigned)chunks);
     if (dt == SASQ_F16) {
         if (codes) fakequant_fwd_pc_kernel<SASQ_F16, true><<<grid, kPcThreads, 0, st>>>(X, s, Y, codes, rows, cols, rpc, bits);
@@ -289,8 +359,9 @@ extern "C" int sasq_fakequant_bwd_pc(const void* x, const void* dy, const float*
     if (!workspace || workspace_bytes < sasq_fakequant_bwd_pc_workspace(rows, cols)) return SASQ_ERR_WORKSPACE;
     if (!aligned16(workspace)) return SASQ_ERR_ALIGN;
     const int64_t col_blocks = (cols + kPcColsPerBlock - 1) / kPcColsPerBlock;
-    const int chunks = pc_row_chunks(rows, col_blocks);
-    const int64_t rpc = (rows + chunks - 1) / chunks;
+    // rows per chunk: a multiple of 16 (whole unpredicated groups in every chunk but the last)
+    const int64_t rpc = ((rows + pc_row_chunks(rows, col_blocks) - 1) / pc_row_chunks(rows, col_blocks) + 15) / 16 * 16;
+    const int chunks = (int)((rows + rpc - 1) / rpc);
     dim3 grid((unsigned)col_blocks, (unsigned)chunks);
     auto tickets = static_cast<uint32_t*>(workspace);
     auto parts = reinterpret_cast<float*>(static_cast<char*>(workspace) + kWsHeaderBytes);
