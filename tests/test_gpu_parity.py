@@ -179,7 +179,7 @@ def pack_on_device(wq, fmt):
     return packed, dst
 
 
-def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True, path=None, tile=None, blocked=False):
+def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True, path=None, tile=None, blocked=False, a_bits=8):
     """path: None (library's choice by shape), "twopass" or "fused" (activation quantize in a
     separate pass / on load inside the GEMM).  tile: None (by shape), "256", "128x256", "128".
     blocked: hand the weights over in the pre-arranged format made by sasq_pack_weight."""
@@ -201,7 +201,7 @@ def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True, path=None, til
     xq = torch.empty((M, K), dtype=torch.int8, device="cuda") if want_debug else None
     wsl = B.new_workspace(B.sasq_static_linear_workspace(M, N, K, wf))
     B.sasq_static_linear(x, dev_scalar(s), wdev, torch.from_numpy(s_w).cuda(),
-                         None if bias is None else torch.from_numpy(bias).cuda(), y, wf, wsl, acc, xq)
+                         None if bias is None else torch.from_numpy(bias).cuda(), y, wf, wsl, acc, xq, a_bits)
     torch.cuda.synchronize()
     os.environ.pop("SASQ_STATIC_LINEAR_PATH", None)
     os.environ.pop("SASQ_STATIC_LINEAR_TILE", None)
@@ -317,6 +317,23 @@ def test_static_linear_blocked_weights(shape, dtype, fmt, tile):
         assert_same_values(y, ref["y"], dtype, "Y")
         y2, _, _ = run_linear(xb, s, wq, s_w, b, fmt, dtype, want_debug=False, tile=tile, blocked=True)
         assert np.array_equal(y2, y)
+
+
+@pytest.mark.parametrize("a_bits", [4, 6, 2])
+@pytest.mark.parametrize("path,blocked", [("twopass", False), ("fused", False), (None, True)])
+def test_static_linear_low_bit_activations(a_bits, path, blocked):
+    """Activation widths below 8 (codes still travel as int8): W8A4-style and W4A4-style linears."""
+    M, N, K = 70, 90, 256
+    for dtype, fmt in (("f16", "int8"), ("bf16", "int4")):
+        xb = wl.random_bits(15, f"lbx{dtype}", (M, K), dtype, gain=2.0)
+        w = wl.random_f32(15, "lbw", (N, K), 0.02)
+        wq, s_w = oracle.quantize_weight(w, fmt)
+        s = np.float32(oracle.absmax_scale(xb, a_bits, dtype) / 2)
+        ref = oracle.static_linear(xb, s, wq, s_w, None, a_bits, fmt, dtype)
+        y, acc, xq = run_linear(xb, s, wq, s_w, None, fmt, dtype, path=path, blocked=blocked, a_bits=a_bits)
+        assert np.array_equal(xq, ref["xq"]) and np.array_equal(acc, ref["acc"])
+        assert np.abs(xq.astype(np.int32)).max() <= 1 << (a_bits - 1)
+        assert_same_values(y, ref["y"], dtype, "Y")
 
 
 def test_static_linear_extreme_codes():
