@@ -128,6 +128,37 @@ int sasq_fakequant_bwd_pc(const void* x, const void* dy, const float* s, void* d
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The fake-quant operators of several tensors in one launch (a decoder layer has seven, one in
+ * front of each linear, Sec. 4.2; at LLaMA-2-7B sizes a separate launch per tensor spends a fifth
+ * of its time ramping up and draining).  Element arithmetic, outputs and error rules are those of
+ * sasq_fakequant_fwd / sasq_fakequant_bwd applied to each item; ds of an item is reduced in a
+ * fixed order that depends on the batch's composition only (deterministic from run to run; it may
+ * differ from the single-tensor call's ds in the last bits).
+ *   items   HOST array of `count` descriptors (1 <= count <= SASQ_MAX_BATCH), read before the call
+ *           returns; the pointers inside are device pointers with the meaning of the single calls:
+ *           x, s always; out = y (forward, required) or dx (backward, may be NULL); dy and ds
+ *           backward only.  Items must not overlap each other's outputs.
+ *   workspace (backward)  >= sasq_fakequant_bwd_batch_workspace(count) bytes, initialised once
+ *           with sasq_workspace_init; not shared with an overlapping call.
+ */
+#define SASQ_MAX_BATCH 8
+typedef struct {
+    const void* x;      /* [rows, cols] device, 16-bit `dt`                      */
+    const void* dy;     /* backward: [rows, cols] device, 16-bit `dt`            */
+    const float* s;     /* device fp32 scalar                                     */
+    void* out;          /* forward: y; backward: dx or NULL                       */
+    float* ds;          /* backward: device fp32 scalar, overwritten              */
+    int64_t rows, cols;
+} sasq_fq_item;
+int sasq_fakequant_fwd_batch(const sasq_fq_item* items, int count, int bits, sasq_dtype dt, void* stream);
+size_t sasq_fakequant_bwd_batch_workspace(int count);
+int sasq_fakequant_bwd_batch(const sasq_fq_item* items, int count, int bits, sasq_dtype dt,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* SGD step of sasq_scale_sgd on a vector of n scales (the scales of one layer in one launch). */
+int sasq_scale_sgd_vec(float* s, const float* ds, int64_t n, float lr, void* stream);
+
+/*
  * One plain SGD step on the scale (the optimiser state of SASQ is the scale alone, Sec. 4.2;
  * the paper's own runs use AdamW, Sec. 5.1):  *s = fl32(*s - fl32(lr * *ds)).
  */

@@ -18,7 +18,14 @@ LIB_PATH = os.path.join(_PKG, "libsasq.so")
 SASQ_F16, SASQ_BF16 = 0, 1
 SASQ_W_INT8, SASQ_W_INT4_PACKED, SASQ_W_INT8_BLOCKED, SASQ_W_INT4_BLOCKED = 0, 1, 2, 3
 
+SASQ_MAX_BATCH = 8
+
 _DT = {torch.float16: SASQ_F16, torch.bfloat16: SASQ_BF16}
+
+
+class _FqItem(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("dy", ctypes.c_void_p), ("s", ctypes.c_void_p), ("out", ctypes.c_void_p),
+                ("ds", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64)]
 
 
 class SasqError(RuntimeError):
@@ -49,6 +56,11 @@ def _lib() -> ctypes.CDLL:
         L.sasq_fakequant_bwd_workspace.argtypes = [i64, i64]
         L.sasq_fakequant_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, sz, vp]
         L.sasq_scale_sgd.argtypes = [vp, vp, f32, vp]
+        L.sasq_scale_sgd_vec.argtypes = [vp, vp, i64, f32, vp]
+        L.sasq_fakequant_fwd_batch.argtypes = [ctypes.POINTER(_FqItem), i32, i32, i32, vp]
+        L.sasq_fakequant_bwd_batch_workspace.restype = sz
+        L.sasq_fakequant_bwd_batch_workspace.argtypes = [i32]
+        L.sasq_fakequant_bwd_batch.argtypes = [ctypes.POINTER(_FqItem), i32, i32, i32, vp, sz, vp]
         L.sasq_scale_adamw.argtypes = [vp, vp, vp, vp, i64, i64] + [ctypes.c_double] * 5 + [vp]
         L.sasq_fakequant_fwd_pc.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp]
         L.sasq_fakequant_bwd_pc_workspace.restype = sz
@@ -168,6 +180,57 @@ def sasq_fakequant_bwd_pc(x: torch.Tensor, dy: torch.Tensor, s: torch.Tensor, dx
     wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(_lib().sasq_fakequant_bwd_pc(_ptr(x), _ptr(dy), _ptr(s), _ptr(dx), _ptr(ds), rows, cols, bits, _dt(x),
                                         _ptr(workspace), wsb, _stream()), "sasq_fakequant_bwd_pc")
+
+
+def _fq_items(items, backward: bool):
+    """items: sequence of (x, s, y) for the forward or (x, dy, s, dx_or_None, ds) for the backward."""
+    if not 1 <= len(items) <= SASQ_MAX_BATCH:
+        raise ValueError(f"a batch holds 1..{SASQ_MAX_BATCH} tensors")
+    arr = (_FqItem * len(items))()
+    dt = None
+    for i, it in enumerate(items):
+        if backward:
+            x, dy, s, dx, ds = it
+            if dy.dtype != x.dtype or dy.shape != x.shape or (dx is not None and (dx.dtype != x.dtype or dx.shape != x.shape)):
+                raise ValueError("dy and dx must match x")
+            _want(ds, torch.float32, "ds")
+            arr[i].dy, arr[i].out, arr[i].ds = _ptr(dy).value, (None if dx is None else _ptr(dx).value), _ptr(ds).value
+        else:
+            x, s, y = it
+            if y.dtype != x.dtype or y.shape != x.shape:
+                raise ValueError("y must match x")
+            arr[i].out = _ptr(y).value
+        _want(s, torch.float32, "s")
+        if dt is None:
+            dt = _dt(x)
+        elif _dt(x) != dt:
+            raise TypeError("all tensors of a batch must have the same dtype")
+        arr[i].x, arr[i].s = _ptr(x).value, _ptr(s).value
+        arr[i].rows, arr[i].cols = x.shape[0], x.numel() // max(x.shape[0], 1)
+    return arr, dt
+
+
+def sasq_fakequant_fwd_batch(items, bits: int = 8) -> None:
+    arr, dt = _fq_items(items, False)
+    _check(_lib().sasq_fakequant_fwd_batch(arr, len(items), bits, dt, _stream()), "sasq_fakequant_fwd_batch")
+
+
+def sasq_fakequant_bwd_batch_workspace(count: int) -> int:
+    return int(_lib().sasq_fakequant_bwd_batch_workspace(count))
+
+
+def sasq_fakequant_bwd_batch(items, workspace: torch.Tensor, bits: int = 8) -> None:
+    arr, dt = _fq_items(items, True)
+    _check(_lib().sasq_fakequant_bwd_batch(arr, len(items), bits, dt, _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _stream()),
+           "sasq_fakequant_bwd_batch")
+
+
+def sasq_scale_sgd_vec(s: torch.Tensor, ds: torch.Tensor, lr: float) -> None:
+    _want(s, torch.float32, "s"); _want(ds, torch.float32, "ds")
+    if s.numel() != ds.numel():
+        raise ValueError("s and ds must have the same length")
+    _check(_lib().sasq_scale_sgd_vec(_ptr(s), _ptr(ds), s.numel(), ctypes.c_float(lr), _stream()), "sasq_scale_sgd_vec")
 
 
 def sasq_scale_sgd(s: torch.Tensor, ds: torch.Tensor, lr: float) -> None:

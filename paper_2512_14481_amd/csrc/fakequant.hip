@@ -38,17 +38,18 @@ __device__ __forceinline__ void fwd_vec(const u32x4& in, const QConst& k, u32x4&
     }
 }
 
+// Forward over one tensor by block `block` of the `nblocks` that share it.
 template <int DT, bool CODES>
-__global__ __launch_bounds__(kThreads) void fakequant_fwd_kernel(
+__device__ __forceinline__ void fwd_body(
     const u32x4* __restrict__ x, const float* __restrict__ s_ptr, u32x4* __restrict__ y,
-    u32x2* __restrict__ codes, int64_t nvec, int64_t n, int bits)
+    u32x2* __restrict__ codes, int64_t nvec, int64_t n, int bits, int block, int nblocks)
 {
     using S = Store16<DT>;
     const QConst k = make_qconst(*s_ptr, bits);
     constexpr int64_t kChunk = (int64_t)kThreads * kUnroll;
     const int64_t full_end = nvec / kChunk * kChunk;
     // full chunks: no predication, all kUnroll loads of a lane in flight together
-    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < full_end; base += (int64_t)gridDim.x * kChunk) {
+    for (int64_t base = (int64_t)block * kChunk; base < full_end; base += (int64_t)nblocks * kChunk) {
         u32x4 in[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) in[u] = __builtin_nontemporal_load(&x[base + u * kThreads + threadIdx.x]);
@@ -61,7 +62,7 @@ __global__ __launch_bounds__(kThreads) void fakequant_fwd_kernel(
             if (CODES) codes[base + u * kThreads + threadIdx.x] = cw;
         }
     }
-    if (blockIdx.x != 0) return;
+    if (block != 0) return;
     // remainder: fewer than kChunk vectors, then fewer than 8 scalars
     for (int64_t i = full_end + threadIdx.x; i < nvec; i += kThreads) {
         u32x4 out;
@@ -78,6 +79,50 @@ __global__ __launch_bounds__(kThreads) void fakequant_fwd_kernel(
         ys[i] = S::enc(codef_of(e) * k.s);
         if (CODES) reinterpret_cast<int8_t*>(codes)[i] = (int8_t)code_of(e);
     }
+}
+
+template <int DT, bool CODES>
+__global__ __launch_bounds__(kThreads) void fakequant_fwd_kernel(
+    const u32x4* __restrict__ x, const float* __restrict__ s_ptr, u32x4* __restrict__ y,
+    u32x2* __restrict__ codes, int64_t nvec, int64_t n, int bits)
+{
+    fwd_body<DT, CODES>(x, s_ptr, y, codes, nvec, n, bits, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// Several tensors in one launch (the fake-quant operators of one decoder layer): the grid is cut
+// into one run of blocks per tensor, sized by the host in proportion to the tensor.
+constexpr int kMaxBatch = SASQ_MAX_BATCH;
+struct FqBatchItem {
+    const u32x4* x;
+    const u32x4* dy;
+    const float* s;
+    u32x4* out;
+    float* ds;
+    int64_t nvec, n;
+};
+struct FqBatch {
+    FqBatchItem it[kMaxBatch];
+    int first_block[kMaxBatch + 1];
+    int count;
+    int index0;      // index in the caller's batch of it[0]
+};
+
+__device__ __forceinline__ int batch_item_of(const FqBatch& b, int block)
+{
+    int k = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxBatch; ++i)
+        if (i < b.count && block >= b.first_block[i]) k = i;
+    return k;
+}
+
+template <int DT>
+__global__ __launch_bounds__(kThreads) void fakequant_fwd_batch_kernel(const FqBatch b, int bits)
+{
+    const int k = batch_item_of(b, (int)blockIdx.x);
+    const FqBatchItem& it = b.it[k];
+    fwd_body<DT, false>(it.x, it.s, it.out, nullptr, it.nvec, it.n, bits,
+                        (int)blockIdx.x - b.first_block[k], b.first_block[k + 1] - b.first_block[k]);
 }
 
 // Per-element backward term.  For an unclipped element q == round(p), and fma(-x, inv_s, q)
@@ -109,18 +154,20 @@ __device__ __forceinline__ float bwd_vec(const u32x4& xin, const u32x4& gin, con
     return part;
 }
 
+// Backward over one tensor by block `block` of the `nblocks` (<= kMaxReduceBlocks) that share it;
+// `ticket` and `partials` belong to this tensor alone.
 template <int DT, bool WRITE_DX>
-__global__ __launch_bounds__(kThreads) void fakequant_bwd_kernel(
+__device__ __forceinline__ void bwd_body(
     const u32x4* __restrict__ x, const u32x4* dy, const float* __restrict__ s_ptr,
-    u32x4* dx, float* __restrict__ ds, uint32_t* __restrict__ ws_head,
-    double* __restrict__ partials, int64_t nvec, int64_t n, int bits)
+    u32x4* dx, float* __restrict__ ds, uint32_t* __restrict__ ticket_word,
+    double* __restrict__ partials, int64_t nvec, int64_t n, int bits, int block, int nblocks)
 {
     using S = Store16<DT>;
     const QConst k = make_qconst(*s_ptr, bits);
     double acc = 0.0;       // 8 terms are summed in fp32, everything above that in fp64
     constexpr int64_t kChunk = (int64_t)kThreads * kUnroll;
     const int64_t full_end = nvec / kChunk * kChunk;
-    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < full_end; base += (int64_t)gridDim.x * kChunk) {
+    for (int64_t base = (int64_t)block * kChunk; base < full_end; base += (int64_t)nblocks * kChunk) {
         u32x4 xin[kUnroll], gin[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -134,7 +181,7 @@ __global__ __launch_bounds__(kThreads) void fakequant_bwd_kernel(
             if (WRITE_DX) __builtin_nontemporal_store(out, &dx[base + u * kThreads + threadIdx.x]);
         }
     }
-    if (blockIdx.x == 0) {
+    if (block == 0) {
         for (int64_t i = full_end + threadIdx.x; i < nvec; i += kThreads) {
             u32x4 out;
             acc += (double)bwd_vec<DT>(x[i], dy[i], k, out);
@@ -163,14 +210,14 @@ __global__ __launch_bounds__(kThreads) void fakequant_bwd_kernel(
         double b = 0.0;
 #pragma unroll
         for (int i = 0; i < kThreads / kWave; ++i) b += wave_part[i];
-        __hip_atomic_store(&partials[blockIdx.x], b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&partials[block], b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         // The partial went out as an agent-scope atomic store (written through to where every XCD
         // sees it); waiting for its acknowledgement orders it before the ticket.  A release fence
         // here would instead write back this XCD's whole L2 once per block.
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        uint32_t ticket = __hip_atomic_fetch_add(&ws_head[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        is_last = (ticket == kTicketBase + gridDim.x - 1);
-        if (ticket - kTicketBase >= gridDim.x)      // workspace was never initialised: fail loudly
+        uint32_t ticket = __hip_atomic_fetch_add(ticket_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        is_last = (ticket == kTicketBase + (uint32_t)nblocks - 1);
+        if (ticket - kTicketBase >= (uint32_t)nblocks)      // workspace was never initialised: fail loudly
             *ds = __uint_as_float(0x7FC00000u);
     }
     __syncthreads();
@@ -185,11 +232,11 @@ __global__ __launch_bounds__(kThreads) void fakequant_bwd_kernel(
 #pragma unroll
     for (int j = 0; j < kPer; ++j) {
         const int i = j * kThreads + threadIdx.x;
-        pv[j] = __hip_atomic_load(&partials[i < (int)gridDim.x ? i : 0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        pv[j] = __hip_atomic_load(&partials[i < nblocks ? i : 0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     double t = 0.0;
 #pragma unroll
-    for (int j = 0; j < kPer; ++j) t += (j * kThreads + (int)threadIdx.x < (int)gridDim.x) ? pv[j] : 0.0;
+    for (int j = 0; j < kPer; ++j) t += (j * kThreads + (int)threadIdx.x < nblocks) ? pv[j] : 0.0;
     __shared__ double tree[kThreads];
     tree[threadIdx.x] = t;
     __syncthreads();
@@ -199,7 +246,39 @@ __global__ __launch_bounds__(kThreads) void fakequant_bwd_kernel(
     }
     if (threadIdx.x == 0) {
         *ds = (float)tree[0];
-        __hip_atomic_store(&ws_head[0], kTicketBase, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(ticket_word, kTicketBase, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+template <int DT, bool WRITE_DX>
+__global__ __launch_bounds__(kThreads) void fakequant_bwd_kernel(
+    const u32x4* __restrict__ x, const u32x4* dy, const float* __restrict__ s_ptr,
+    u32x4* dx, float* __restrict__ ds, uint32_t* __restrict__ ws_head,
+    double* __restrict__ partials, int64_t nvec, int64_t n, int bits)
+{
+    bwd_body<DT, WRITE_DX>(x, dy, s_ptr, dx, ds, ws_head, partials, nvec, n, bits, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// Batched backward: tensor k uses ticket word k of the workspace header and its own run of
+// kMaxReduceBlocks partials.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void fakequant_bwd_batch_kernel(
+    const FqBatch b, uint32_t* __restrict__ ws_head, double* __restrict__ partials, int bits)
+{
+    const int k = batch_item_of(b, (int)blockIdx.x);
+    const FqBatchItem& it = b.it[k];
+    const int block = (int)blockIdx.x - b.first_block[k], nblocks = b.first_block[k + 1] - b.first_block[k];
+    const int slot = b.index0 + k;
+    if (it.out) bwd_body<DT, true>(it.x, it.dy, it.s, it.out, it.ds, ws_head + slot, partials + slot * kMaxReduceBlocks, it.nvec, it.n, bits, block, nblocks);
+    else        bwd_body<DT, false>(it.x, it.dy, it.s, it.out, it.ds, ws_head + slot, partials + slot * kMaxReduceBlocks, it.nvec, it.n, bits, block, nblocks);
+}
+
+__global__ void scale_sgd_vec_kernel(float* s, const float* ds, int n, float lr)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        float step = lr * ds[i];
+        s[i] = s[i] - step;
     }
 }
 
@@ -325,5 +404,129 @@ extern "C" int sasq_scale_adamw(float* s, const float* ds, float* m, float* v, i
     scale_adamw_kernel<<<blocks, 256, 0, as_stream(stream)>>>(s, ds, m, v, n, (float)lr, (float)beta1, (float)beta2,
                                                               (float)(1.0 - beta1), (float)(1.0 - beta2), (float)eps,
                                                               (float)weight_decay, bc1, bc2);
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+// ---- batched entry points ---------------------------------------------------------------------
+namespace sasq {
+
+constexpr int kBatchFwdBlocks = 2048;
+constexpr int kBatchBwdBlocks = 512;
+// Tensors streamed concurrently by one launch: up to this many input bytes in all.  Beyond it the
+// launch is slower than one launch per tensor (measured: seven tensors of 134-470 MB in one launch
+// reach 5.0 TB/s, one after the other 6.1 TB/s; three tensors of 157 MB in all 5.8 against 5.1),
+// so a batch is cut, in order, into launches under the limit.
+constexpr int64_t kBatchLaunchBytes = INT64_C(192) << 20;
+
+static int check_items(const sasq_fq_item* items, int count, bool backward)
+{
+    if (!items) return SASQ_ERR_NULL;
+    if (count <= 0 || count > kMaxBatch) return SASQ_ERR_SHAPE;
+    for (int i = 0; i < count; ++i) {
+        const sasq_fq_item& it = items[i];
+        if (!it.x || !it.s || (backward ? (!it.dy || !it.ds) : !it.out)) return SASQ_ERR_NULL;
+        if (it.rows <= 0 || it.cols <= 0 || it.rows > (INT64_C(1) << 40) / it.cols) return SASQ_ERR_SHAPE;
+        if (!aligned16(it.x) || (it.out && !aligned16(it.out)) || (backward && !aligned16(it.dy))) return SASQ_ERR_ALIGN;
+    }
+    return SASQ_OK;
+}
+
+// Items [lo, hi) as one launch: `total_blocks` cut into one run per tensor, proportional to its
+// size, at least one block and at most `max_per_item` each.  A tensor keeps its index in the batch
+// (it selects the tensor's ticket word and partials).
+static void build_launch(const sasq_fq_item* items, int lo, int hi, int total_blocks, int max_per_item, FqBatch& b)
+{
+    int64_t total_vec = 0;
+    for (int i = lo; i < hi; ++i) {
+        const sasq_fq_item& it = items[i];
+        const int64_t n = it.rows * it.cols;
+        b.it[i - lo] = FqBatchItem{static_cast<const u32x4*>(it.x), static_cast<const u32x4*>(it.dy), it.s,
+                                   static_cast<u32x4*>(it.out), it.ds, n / 8, n};
+        total_vec += n / 8 + 1;
+    }
+    b.count = hi - lo;
+    b.index0 = lo;
+    b.first_block[0] = 0;
+    const int64_t per_block = (int64_t)kThreads * kUnroll;
+    for (int i = 0; i < b.count; ++i) {
+        const int64_t need = (b.it[i].nvec + per_block - 1) / per_block;            // blocks that would each have a full chunk
+        int64_t share = ((b.it[i].nvec + 1) * total_blocks + total_vec - 1) / total_vec;
+        if (share > need) share = need;
+        if (share > max_per_item) share = max_per_item;
+        if (share < 1) share = 1;
+        b.first_block[i + 1] = b.first_block[i] + (int)share;
+    }
+    for (int i = b.count; i < kMaxBatch; ++i) b.first_block[i + 1] = b.first_block[b.count];
+}
+
+// next launch: items [lo, return value)
+static int launch_end(const sasq_fq_item* items, int lo, int count)
+{
+    int64_t bytes = 0;
+    int hi = lo;
+    while (hi < count) {
+        const int64_t b = items[hi].rows * items[hi].cols * 2;
+        if (hi > lo && bytes + b > kBatchLaunchBytes) break;
+        bytes += b;
+        ++hi;
+    }
+    return hi;
+}
+
+}  // namespace sasq
+
+extern "C" int sasq_fakequant_fwd_batch(const sasq_fq_item* items, int count, int bits, sasq_dtype dt, void* stream)
+{
+    if (bits < 2 || bits > 8) return SASQ_ERR_UNSUPPORTED;
+    if (dt != SASQ_F16 && dt != SASQ_BF16) return SASQ_ERR_UNSUPPORTED;
+    const int rc = check_items(items, count, false);
+    if (rc) return rc;
+    for (int lo = 0; lo < count;) {
+        const int hi = launch_end(items, lo, count);
+        FqBatch b{};
+        build_launch(items, lo, hi, kBatchFwdBlocks, kBatchFwdBlocks, b);
+        const int grid = b.first_block[b.count];
+        if (dt == SASQ_F16) fakequant_fwd_batch_kernel<SASQ_F16><<<grid, kThreads, 0, as_stream(stream)>>>(b, bits);
+        else                fakequant_fwd_batch_kernel<SASQ_BF16><<<grid, kThreads, 0, as_stream(stream)>>>(b, bits);
+        lo = hi;
+    }
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+extern "C" size_t sasq_fakequant_bwd_batch_workspace(int count)
+{
+    if (count <= 0 || count > kMaxBatch) return 0;
+    return kWsHeaderBytes + sizeof(double) * kMaxReduceBlocks * (size_t)count;
+}
+
+extern "C" int sasq_fakequant_bwd_batch(const sasq_fq_item* items, int count, int bits, sasq_dtype dt,
+                                        void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (bits < 2 || bits > 8) return SASQ_ERR_UNSUPPORTED;
+    if (dt != SASQ_F16 && dt != SASQ_BF16) return SASQ_ERR_UNSUPPORTED;
+    const int rc = check_items(items, count, true);
+    if (rc) return rc;
+    if (!workspace || workspace_bytes < sasq_fakequant_bwd_batch_workspace(count)) return SASQ_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SASQ_ERR_ALIGN;
+    auto head = static_cast<uint32_t*>(workspace);
+    auto parts = reinterpret_cast<double*>(static_cast<char*>(workspace) + kWsHeaderBytes);
+    for (int lo = 0; lo < count;) {
+        const int hi = launch_end(items, lo, count);
+        FqBatch b{};
+        // a tensor alone in its launch gets what the single-tensor call gives it: one block per CU
+        build_launch(items, lo, hi, hi - lo == 1 ? kMaxReduceBlocks : kBatchBwdBlocks, kMaxReduceBlocks, b);
+        const int grid = b.first_block[b.count];
+        if (dt == SASQ_F16) fakequant_bwd_batch_kernel<SASQ_F16><<<grid, kThreads, 0, as_stream(stream)>>>(b, head, parts, bits);
+        else                fakequant_bwd_batch_kernel<SASQ_BF16><<<grid, kThreads, 0, as_stream(stream)>>>(b, head, parts, bits);
+        lo = hi;
+    }
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+extern "C" int sasq_scale_sgd_vec(float* s, const float* ds, int64_t n, float lr, void* stream)
+{
+    if (!s || !ds) return SASQ_ERR_NULL;
+    if (n <= 0 || n > (INT64_C(1) << 31) - 256) return SASQ_ERR_SHAPE;
+    scale_sgd_vec_kernel<<<(int)((n + 255) / 256), 256, 0, as_stream(stream)>>>(s, ds, (int)n, lr);
     return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
 }

@@ -1,0 +1,96 @@
+"""GPU parity of the batched fake-quant entry points: outputs bit-identical to the single-tensor
+calls (and so to the oracle), ds within the single-tensor tolerance of the oracle, deterministic."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2512_14481_amd import binding as B
+from paper_2512_14481_amd import workloads as wl
+from tests.gpu_util import TDT, dev_scalar, rel_err, to_bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [(1, 1), (3, 5), (17, 33), (64, 256), (257, 1031), (512, 4096), (1, 8192), (300, 7)]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("count", [1, 3, 8])
+def test_batch_matches_single_calls_and_oracle(dtype, count):
+    shapes = SHAPES[:count]
+    xs = [wl.random_bits(81, f"bx{sh}{dtype}", sh, dtype, gain=2.0) for sh in shapes]
+    dys = [wl.random_bits(81, f"bd{sh}{dtype}", sh, dtype, gain=1.0) for sh in shapes]
+    ss = [np.float32(oracle.absmax_scale(x, 8, dtype) / (2 + i)) for i, x in enumerate(xs)]
+    xd = [to_dev(x, dtype) for x in xs]
+    dyd = [to_dev(d, dtype) for d in dys]
+    sd = torch.tensor([float(s) for s in ss], dtype=torch.float32, device="cuda")
+    yd = [torch.empty_like(x) for x in xd]
+    dxd = [torch.empty_like(x) if i != 1 else None for i, x in enumerate(xd)]      # one item without dx
+    dsd = torch.full((count,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = B.new_workspace(B.sasq_fakequant_bwd_batch_workspace(count))
+    B.sasq_fakequant_fwd_batch([(xd[i], sd[i:i + 1], yd[i]) for i in range(count)], 8)
+    items = [(xd[i], dyd[i], sd[i:i + 1], dxd[i], dsd[i:i + 1]) for i in range(count)]
+    B.sasq_fakequant_bwd_batch(items, ws, 8)
+    ds1 = dsd.cpu().numpy().copy()
+    B.sasq_fakequant_bwd_batch(items, ws, 8)                                       # same workspace, second call
+    torch.cuda.synchronize()
+    assert np.array_equal(dsd.cpu().numpy(), ds1), "ds is deterministic and the tickets were reset"
+    for i in range(count):
+        y_ref, _ = oracle.fakequant_fwd(xs[i], ss[i], 8, dtype)
+        ref = oracle.fakequant_bwd(xs[i], dys[i], ss[i], 8, dtype)
+        assert np.array_equal(wl.storage_bits_to_f32(to_bits(yd[i]), dtype), wl.storage_bits_to_f32(y_ref, dtype)), i
+        if dxd[i] is not None:
+            assert np.array_equal(wl.storage_bits_to_f32(to_bits(dxd[i]), dtype), wl.storage_bits_to_f32(ref["dx"], dtype)), i
+        tol = 1e-4 * abs(ref["ds64"]) + 1e-7 * ref["sum_abs"] + 1e-30
+        assert abs(float(ds1[i]) - ref["ds64"]) <= tol, (i, ds1[i], ref["ds64"])
+
+
+def test_batch_sgd_vec_and_errors():
+    s = torch.tensor([0.5, 0.25, 2.0], dtype=torch.float32, device="cuda")
+    ds = torch.tensor([126.212890625, -3.0, 0.0], dtype=torch.float32, device="cuda")
+    B.sasq_scale_sgd_vec(s, ds, 2e-4)
+    ref = [oracle.scale_sgd(a, b, 2e-4) for a, b in ((0.5, 126.212890625), (0.25, -3.0), (2.0, 0.0))]
+    assert np.array_equal(s.cpu().numpy(), np.array(ref, dtype=np.float32))
+    x = torch.zeros((4, 8), dtype=torch.float16, device="cuda")
+    with pytest.raises(ValueError):
+        B.sasq_fakequant_fwd_batch([], 8)
+    arr, dt = B._fq_items([(x, s[:1], x)], False)
+    assert B._lib().sasq_fakequant_fwd_batch(arr, 0, 8, dt, None) == 2
+    assert B._lib().sasq_fakequant_fwd_batch(arr, 9, 8, dt, None) == 2
+    assert B._lib().sasq_fakequant_fwd_batch(arr, 1, 9, dt, None) == 4
+    assert B._lib().sasq_fakequant_bwd_batch(arr, 1, 8, dt, None, 0, None) == 1     # dy / ds missing
+
+
+def test_batch_larger_than_one_launch_matches_single_calls():
+    """Seven tensors of config 4's sizes (365 MB of inputs: the library cuts the batch into several
+    launches): outputs bit-identical to the single-tensor calls, ds equal to theirs within the
+    reduction-order tolerance, every item's ticket reset for the next call."""
+    dtype = "bf16"
+    shapes = [(4096, 5120)] * 6 + [(4096, 13824)]
+    g = torch.Generator(device="cuda").manual_seed(5)
+    xd = [(torch.randn(sh, device="cuda", generator=g) * 2).to(TDT[dtype]) for sh in shapes]
+    dyd = [torch.randn(sh, device="cuda", generator=g).to(TDT[dtype]) for sh in shapes]
+    sd = torch.tensor([0.02 + 0.01 * i for i in range(7)], dtype=torch.float32, device="cuda")
+    y_b = [torch.empty_like(x) for x in xd]
+    dx_b = [torch.empty_like(x) for x in xd]
+    ds_b = torch.zeros(7, dtype=torch.float32, device="cuda")
+    ws = B.new_workspace(B.sasq_fakequant_bwd_batch_workspace(7))
+    items = [(xd[i], dyd[i], sd[i:i + 1], dx_b[i], ds_b[i:i + 1]) for i in range(7)]
+    B.sasq_fakequant_fwd_batch([(xd[i], sd[i:i + 1], y_b[i]) for i in range(7)], 8)
+    B.sasq_fakequant_bwd_batch(items, ws, 8)
+    first = ds_b.clone()
+    B.sasq_fakequant_bwd_batch(items, ws, 8)
+    assert torch.equal(first, ds_b)
+    ws1 = B.new_workspace(B.sasq_fakequant_bwd_workspace(1, 1))
+    y1, dx1 = torch.empty_like(xd[6]), torch.empty_like(xd[6])
+    ds1 = torch.zeros(1, dtype=torch.float32, device="cuda")
+    for i in range(7):
+        y1, dx1 = torch.empty_like(xd[i]), torch.empty_like(xd[i])
+        B.sasq_fakequant_fwd(xd[i], sd[i:i + 1], y1, None, 8)
+        B.sasq_fakequant_bwd(xd[i], dyd[i], sd[i:i + 1], dx1, ds1, ws1, 8)
+        assert torch.equal(y1.view(torch.int16), y_b[i].view(torch.int16)), i
+        assert torch.equal(dx1.view(torch.int16), dx_b[i].view(torch.int16)), i
+        a, b = float(ds1.item()), float(first[i].item())
+        assert abs(a - b) <= 1e-4 * abs(a) + 1e-3, (i, a, b)
