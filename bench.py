@@ -92,6 +92,13 @@ class Layer:
         self.bwd_items = [(p.x, p.dy, p.s, p.dx, p.ds) for p in projs]
         self.ws_batch = B.new_workspace(B.sasq_fakequant_bwd_batch_workspace(n))
         self.fq_bytes = sum(p.fq_bytes for p in projs)
+        # the linears of the layer in one batched call (needs one weight format and K % 64 == 0 throughout)
+        self.wf = projs[0].wf
+        self.lin_items = [(p.x, p.s, p.wq, p.s_w, None, p.y) for p in projs]
+        self.lin_batched = all(p.wf == self.wf and p.K % 64 == 0 for p in projs)
+        if self.lin_batched:
+            self.ws_lin = B.new_workspace(B.sasq_static_linear_batch_workspace(self.lin_items, self.wf))
+        self.ops = sum(p.ops for p in projs)
 
 
 def step(layer, ev=None):
@@ -107,6 +114,15 @@ def step(layer, ev=None):
         e1.record()
         ev["fq"].append((e0, e1))
     B.sasq_scale_sgd_vec(layer.s_all, layer.ds_all, LR)
+    if layer.lin_batched:
+        if ev is not None:
+            e2, e3 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e2.record()
+        B.sasq_static_linear_batch(layer.lin_items, layer.wf, layer.ws_lin)
+        if ev is not None:
+            e3.record()
+            ev["lin_batch"].append((e2, e3))
+        return
     for p in layer.projs:
         if ev is not None:
             e2, e3 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -196,7 +212,7 @@ def main():
         run_step()
     layer.s_all.copy_(layer.s0_all)                   # every timed run starts from the same scales
     torch.cuda.synchronize()
-    ev = {"fq": [], "fq_each": [], "lin": []}
+    ev = {"fq": [], "fq_each": [], "lin": [], "lin_batch": []}
     t0 = time.perf_counter()
     for _ in range(a.steps):
         run_step(ev)
@@ -208,14 +224,20 @@ def main():
         for _ in range(3):
             step_unbatched(projs, ws_small, ev)
         torch.cuda.synchronize()
-        ev["lin"] = ev["lin"][:a.steps * len(projs)]
+        if not layer.lin_batched:
+            ev["lin"] = ev["lin"][:a.steps * len(projs)]
 
     ms_per_step = dt / a.steps * 1e3
     total_ops = sum(p.ops for p in projs)
     lin_ms = [(e0.elapsed_time(e1), p) for e0, e1, p in ev["lin"]]
     fq_ms = [(e0.elapsed_time(e1), p) for e0, e1, p in ev["fq_each"]]
-    lin_ops_per_call = total_ops / len(projs)         # the three linears are the same size
-    lin_avg_ms = sum(t for t, _ in lin_ms) / len(lin_ms)
+    if ev["lin_batch"]:
+        # the roofline figure is the batched call: the layer's activation pre-pass + one GEMM launch
+        lin_ops_per_call = total_ops
+        lin_avg_ms = sum(e0.elapsed_time(e1) for e0, e1 in ev["lin_batch"]) / len(ev["lin_batch"])
+    else:
+        lin_ops_per_call = total_ops / len(projs)     # average over the projections' calls
+        lin_avg_ms = sum(t for t, _ in lin_ms) / len(lin_ms)
     lin_tops = lin_ops_per_call / (lin_avg_ms * 1e-3) / 1e12
     if a.unbatched:
         fq_gbps = sum(p.fq_bytes for _, p in fq_ms) / (sum(t for t, _ in fq_ms) * 1e-3) / 1e9
@@ -325,13 +347,16 @@ def main():
                                "fp16 activations, int8 per-channel weights, per-tensor static scale; "
                                "step = fake-quant fwd + STE bwd + ds + SGD + static W8A8 linear per projection"
                    if cfg.name == "c3_mlp7b" else cfg.name},
-        "roofline": {"bound": "mfma", "kernel": "sasq_static_linear (activation quantize + int8 MFMA GEMM + dequant)",
+        "roofline": {"bound": "mfma",
+                     "kernel": ("sasq_static_linear_batch: all projections of the layer, one activation-quantize launch + one "
+                                "int8 MFMA GEMM launch with fused dequantize" if ev["lin_batch"] else
+                                "sasq_static_linear (activation quantize + int8 MFMA GEMM + dequant)"),
                      "achieved": round(lin_tops, 1), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": round(lin_tops / INT8_MFMA_PEAK_TOPS, 4),
-                     "traffic": C3_LINEAR_TRAFFIC_BYTES if cfg.name == "c3_mlp7b" else None,
+                     "traffic": (C3_LINEAR_TRAFFIC_BYTES * (len(projs) if ev["lin_batch"] else 1)) if cfg.name == "c3_mlp7b" else None,
                      "traffic_unit": "bytes per call (rocprofv3 FETCH_SIZE/WRITE_SIZE, copy-calibrated)",
                      "algorithmic_bytes": int(sum(3 * p.M * p.K + p.M * p.K + p.wq.numel() + 2 * p.M * p.N + 4 * p.N
-                                                  for p in projs) / len(projs)),
+                                                  for p in projs) / (1 if ev["lin_batch"] else len(projs))),
                      "avg_launch_us": round(lin_avg_ms * 1e3, 2)},
         "fakequant": {"bound": "hbm", "achieved": round(fq_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                       "frac": round(fq_gbps / HBM_PEAK_GBPS, 4),

@@ -62,6 +62,8 @@ typedef enum {                       /* frozen weight storage                   
     SASQ_W_INT4_BLOCKED = 3          /* output of sasq_pack_weight from SASQ_W_INT4_PACKED       */
 } sasq_wfmt;
 
+#define SASQ_MAX_BATCH 8                 /* tensors / projections per batched call                  */
+
 /* Human-readable name of a status code (static storage, host pointer). */
 const char* sasq_status_string(int status);
 
@@ -141,7 +143,6 @@ int sasq_fakequant_bwd_pc(const void* x, const void* dy, const float* s, void* d
  *   workspace (backward)  >= sasq_fakequant_bwd_batch_workspace(count) bytes, initialised once
  *           with sasq_workspace_init; not shared with an overlapping call.
  */
-#define SASQ_MAX_BATCH 8
 typedef struct {
     const void* x;      /* [rows, cols] device, 16-bit `dt`                      */
     const void* dy;     /* backward: [rows, cols] device, 16-bit `dt`            */
@@ -210,6 +211,30 @@ int sasq_static_linear(const void* x, const float* s, const void* wq, const floa
                        const float* bias, void* y, int32_t* acc_out, int8_t* xq_out,
                        int64_t M, int64_t N, int64_t K, int a_bits, sasq_wfmt wf, sasq_dtype dt,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The static linears of several projections (one decoder layer) in two launches: one activation
+ * pre-pass and one GEMM over the tiles of all projections, longest K first, so that the layer pays
+ * one launch ramp and one drain and the partly filled last round of a projection is filled by the
+ * next one's tiles.  Arithmetic and results of each item are exactly those of sasq_static_linear.
+ *   items   HOST array of `count` descriptors (1 <= count <= SASQ_MAX_BATCH), read before the call
+ *           returns; pointers inside are device pointers as in sasq_static_linear (bias may be NULL).
+ *           Every K must be a multiple of 64 (SASQ_ERR_SHAPE otherwise: use the single call).
+ *   a_bits, wf, dt   shared by all items.  No inspection outputs.
+ *   workspace >= sasq_static_linear_batch_workspace(items, count, wf) bytes.
+ */
+typedef struct {
+    const void* x;        /* [M, K] device, 16-bit `dt`                 */
+    const float* s;       /* device fp32 scalar                          */
+    const void* wq;       /* weights in format `wf`                      */
+    const float* s_w;     /* [N] device fp32                             */
+    const float* bias;    /* [N] device fp32 or NULL                     */
+    void* y;              /* [M, N] device, 16-bit `dt`, written         */
+    int64_t M, N, K;
+} sasq_linear_item;
+size_t sasq_static_linear_batch_workspace(const sasq_linear_item* items, int count, sasq_wfmt wf);
+int sasq_static_linear_batch(const sasq_linear_item* items, int count, int a_bits, sasq_wfmt wf,
+                             sasq_dtype dt, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Static-inference quantized linear with one activation factor per group of `group` consecutive

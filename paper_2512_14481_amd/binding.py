@@ -23,6 +23,12 @@ SASQ_MAX_BATCH = 8
 _DT = {torch.float16: SASQ_F16, torch.bfloat16: SASQ_BF16}
 
 
+class _LinItem(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("s", ctypes.c_void_p), ("wq", ctypes.c_void_p), ("s_w", ctypes.c_void_p),
+                ("bias", ctypes.c_void_p), ("y", ctypes.c_void_p), ("M", ctypes.c_int64), ("N", ctypes.c_int64),
+                ("K", ctypes.c_int64)]
+
+
 class _FqItem(ctypes.Structure):
     _fields_ = [("x", ctypes.c_void_p), ("dy", ctypes.c_void_p), ("s", ctypes.c_void_p), ("out", ctypes.c_void_p),
                 ("ds", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64)]
@@ -73,6 +79,9 @@ def _lib() -> ctypes.CDLL:
         L.sasq_dynamic_linear_workspace.restype = sz
         L.sasq_dynamic_linear_workspace.argtypes = [i64, i64, i64, i32]
         L.sasq_dynamic_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, vp, sz, vp]
+        L.sasq_static_linear_batch_workspace.restype = sz
+        L.sasq_static_linear_batch_workspace.argtypes = [ctypes.POINTER(_LinItem), i32, i32]
+        L.sasq_static_linear_batch.argtypes = [ctypes.POINTER(_LinItem), i32, i32, i32, i32, vp, sz, vp]
         L.sasq_quantize_weight.argtypes = [vp, vp, vp, i64, i64, i32, vp]
         L.sasq_packed_weight_bytes.restype = sz
         L.sasq_packed_weight_bytes.argtypes = [i64, i64, i32]
@@ -330,6 +339,44 @@ def sasq_dynamic_linear(x: torch.Tensor, wq: torch.Tensor, s_w: torch.Tensor, bi
     _check(_lib().sasq_dynamic_linear(_ptr(x), _ptr(wq), _ptr(s_w), _ptr(bias), _ptr(y), _ptr(acc_out), _ptr(xq_out),
                                       _ptr(s_row_out), M, N, K, a_bits, wf, _dt(x), _ptr(workspace), wsb, _stream()),
            "sasq_dynamic_linear")
+
+
+def _lin_items(items, wf: int):
+    """items: sequence of (x, s, wq, s_w, bias_or_None, y)."""
+    if not 1 <= len(items) <= SASQ_MAX_BATCH:
+        raise ValueError(f"a batch holds 1..{SASQ_MAX_BATCH} projections")
+    arr = (_LinItem * len(items))()
+    dt = None
+    for i, (x, s, wq, s_w, bias, y) in enumerate(items):
+        _want(s, torch.float32, "s"); _want(s_w, torch.float32, "s_w"); _want(bias, torch.float32, "bias")
+        M, K = x.shape
+        N = y.shape[1]
+        if wf in (SASQ_W_INT8_BLOCKED, SASQ_W_INT4_BLOCKED):
+            ok = wq.numel() == sasq_packed_weight_bytes(N, K, wf)
+        else:
+            ok = tuple(wq.shape) == (N, K if wf == SASQ_W_INT8 else K // 2)
+        if not ok or y.shape[0] != M or y.dtype != x.dtype or s_w.numel() != N or (bias is not None and bias.numel() != N):
+            raise ValueError(f"shape mismatch in batch item {i}")
+        if dt is None:
+            dt = _dt(x)
+        elif _dt(x) != dt:
+            raise TypeError("all projections of a batch must have the same activation dtype")
+        arr[i].x, arr[i].s, arr[i].wq, arr[i].s_w = _ptr(x).value, _ptr(s).value, _ptr(wq).value, _ptr(s_w).value
+        arr[i].bias, arr[i].y = (None if bias is None else _ptr(bias).value), _ptr(y).value
+        arr[i].M, arr[i].N, arr[i].K = M, N, K
+    return arr, dt
+
+
+def sasq_static_linear_batch_workspace(items, wf: int = SASQ_W_INT8) -> int:
+    arr, _ = _lin_items(items, wf)
+    return int(_lib().sasq_static_linear_batch_workspace(arr, len(items), wf))
+
+
+def sasq_static_linear_batch(items, wf: int, workspace: torch.Tensor, a_bits: int = 8) -> None:
+    arr, dt = _lin_items(items, wf)
+    _check(_lib().sasq_static_linear_batch(arr, len(items), a_bits, wf, dt, _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _stream()),
+           "sasq_static_linear_batch")
 
 
 def sasq_quantize_weight(w: torch.Tensor, wq: torch.Tensor, s_w: torch.Tensor, wf: int = SASQ_W_INT8) -> None:

@@ -28,14 +28,14 @@ constexpr int kWaitLgkm0 = 0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8);
 __device__ __forceinline__ int swz64(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
 
 template <int DT, bool PERM8, bool TILED>
-__global__ __launch_bounds__(256) void quantize_act_kernel(
+__device__ __forceinline__ void quantize_act_body(
     const u32x4* __restrict__ x, const float* __restrict__ s_ptr, u32x2* __restrict__ xq,
-    int64_t nvec, int64_t n, int K, int bits)
+    int64_t nvec, int64_t n, int K, int bits, int block, int nblocks)
 {
     using S = Store16<DT>;
     const QConst k = make_qconst(*s_ptr, bits);
     const int kvec = K >> 3;                      // 8-element vectors per row
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * 256) {
+    for (int64_t i = (int64_t)block * 256 + threadIdx.x; i < nvec; i += (int64_t)nblocks * 256) {
         u32x4 v = x[i];
         float c[8];
 #pragma unroll
@@ -57,11 +57,56 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(
             xq[i] = o;
         }
     }
-    if (!PERM8 && !TILED && blockIdx.x == 0 && threadIdx.x < (unsigned)(n - nvec * 8)) {
+    if (!PERM8 && !TILED && block == 0 && threadIdx.x < (unsigned)(n - nvec * 8)) {
         int64_t i = nvec * 8 + threadIdx.x;
         reinterpret_cast<int8_t*>(xq)[i] =
             (int8_t)code_of(quantize(S::one(reinterpret_cast<const uint16_t*>(x)[i]), k));
     }
+}
+
+template <int DT, bool PERM8, bool TILED>
+__global__ __launch_bounds__(256) void quantize_act_kernel(
+    const u32x4* __restrict__ x, const float* __restrict__ s_ptr, u32x2* __restrict__ xq,
+    int64_t nvec, int64_t n, int K, int bits)
+{
+    quantize_act_body<DT, PERM8, TILED>(x, s_ptr, xq, nvec, n, K, bits, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// The projections of one layer in one launch (their activation pre-passes, and below their GEMMs).
+constexpr int kMaxLinearBatch = SASQ_MAX_BATCH;
+struct LinItem {
+    const void* x;          // 16-bit activations
+    int8_t* xq;             // staged codes (workspace)
+    const float* s;
+    const uint8_t* wq;
+    const float* s_w;
+    const float* bias;
+    uint16_t* y;
+    int M, N, K, tiles_m, tiles_n;
+};
+struct LinBatch {
+    LinItem it[kMaxLinearBatch];
+    int first_block[kMaxLinearBatch + 1];
+    int count;
+};
+
+__device__ __forceinline__ int lin_item_of(const LinBatch& b, int block)
+{
+    int k = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxLinearBatch; ++i)
+        if (i < b.count && block >= b.first_block[i]) k = i;
+    return k;
+}
+
+template <int DT, bool PERM8>
+__global__ __launch_bounds__(256) void quantize_act_batch_kernel(const LinBatch b, int bits)
+{
+    const int k = lin_item_of(b, (int)blockIdx.x);
+    const LinItem& it = b.it[k];
+    const int64_t n = (int64_t)it.M * it.K;
+    quantize_act_body<DT, PERM8, true>(static_cast<const u32x4*>(it.x), it.s, reinterpret_cast<u32x2*>(it.xq), n / 8, n, it.K, bits,
+                                       (int)blockIdx.x - b.first_block[k], b.first_block[k + 1] - b.first_block[k]);
 }
 
 // Same pre-pass with one factor per group of `group` consecutive channels (Sec. 3, Eq. 3; Eq. 1
@@ -353,13 +398,12 @@ enum { W_I8 = 0, W_I4 = 1, W_I8B = 2, W_I4B = 3 };
 // ROWS: one activation factor per row of X (dynamic per-token quantization, the baseline of
 // Sec. 3 / Sec. 4.5): s_ptr points at the M factors and the epilogue uses fl32(s_m * s_w[n]).
 template <int DT, int XMODE, int WMODE, int BM, int BN, bool GROUPED = false, bool ROWS = false>
-__global__ __launch_bounds__(kGemmThreads)
-__attribute__((amdgpu_waves_per_eu(Tile<BM, BN>::kWavesPerSimd, Tile<BM, BN>::kWavesPerSimd)))
-void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict__ wq,
-                        const float* __restrict__ s_ptr, const float* __restrict__ s_w,
-                        const float* __restrict__ bias, uint16_t* __restrict__ y,
-                        int32_t* __restrict__ acc_out, int M, int N, int K, int a_bits,
-                        int tiles_m, int tiles_n, int group_tiles)
+__device__ __forceinline__
+void linear_mfma_body(const void* __restrict__ xin, const uint8_t* __restrict__ wq,
+                      const float* __restrict__ s_ptr, const float* __restrict__ s_w,
+                      const float* __restrict__ bias, uint16_t* __restrict__ y,
+                      int32_t* __restrict__ acc_out, int M, int N, int K, int a_bits,
+                      int tiles_m, int tiles_n, int group_tiles, int bid)
 {
     using S = Store16<DT>;
     using T = Tile<BM, BN>;
@@ -370,7 +414,7 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
     auto stage_ptr = [&](int st, int operand) -> char* { return &lds[st * T::kStageBytes + operand * T::kXBytes]; };
 
     int tm, tn;
-    if (!tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
+    if (!tile_of_block(bid, tiles_m, tiles_n, tm, tn)) return;
     const int m0 = tm * BM, n0 = tn * BN;
 
     const int tid = threadIdx.x;
@@ -749,6 +793,34 @@ void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict_
     }
 }
 
+template <int DT, int XMODE, int WMODE, int BM, int BN, bool GROUPED = false, bool ROWS = false>
+__global__ __launch_bounds__(kGemmThreads)
+__attribute__((amdgpu_waves_per_eu(Tile<BM, BN>::kWavesPerSimd, Tile<BM, BN>::kWavesPerSimd)))
+void linear_mfma_kernel(const void* __restrict__ xin, const uint8_t* __restrict__ wq,
+                        const float* __restrict__ s_ptr, const float* __restrict__ s_w,
+                        const float* __restrict__ bias, uint16_t* __restrict__ y,
+                        int32_t* __restrict__ acc_out, int M, int N, int K, int a_bits,
+                        int tiles_m, int tiles_n, int group_tiles)
+{
+    linear_mfma_body<DT, XMODE, WMODE, BM, BN, GROUPED, ROWS>(xin, wq, s_ptr, s_w, bias, y, acc_out, M, N, K, a_bits,
+                                                              tiles_m, tiles_n, group_tiles, (int)blockIdx.x);
+}
+
+// The GEMMs of several projections in one launch, 256x256 tiles.  Each projection owns a run of
+// workgroup ids (a multiple of 8, so the XCD-aware tile numbering holds inside it); the host puts
+// the projections with the longest K first, so that the dispatcher, which hands out workgroups in
+// id order as CUs fall free, ends the launch with the short tiles: one ramp and one drain for the
+// layer, and the partly filled last round of each projection is filled by the next one's tiles.
+template <int DT, int WMODE>
+__global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void linear_mfma_batch_kernel(const LinBatch b, int a_bits)
+{
+    const int k = lin_item_of(b, (int)blockIdx.x);
+    const LinItem& it = b.it[k];
+    linear_mfma_body<DT, X_PREQ, WMODE, 256, 256>(it.xq, it.wq, it.s, it.s_w, it.bias, it.y, nullptr, it.M, it.N, it.K, a_bits,
+                                                  it.tiles_m, it.tiles_n, 0, (int)blockIdx.x - b.first_block[k]);
+}
+
 static size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Which activation path the MFMA kernel takes: 0 = by shape, 1 = separate quantize pass,
@@ -1069,5 +1141,96 @@ extern "C" int sasq_dynamic_linear(const void* x, const void* wq, const float* s
                              : reinterpret_cast<float*>(static_cast<char*>(workspace) + sasq_static_linear_workspace(M, N, K, wf));
     if (dt == SASQ_F16) run_dynamic<SASQ_F16>(x, wq, s_w, bias, y, acc_out, xq_out, s_row, M, N, K, a_bits, wf, xq_ws, st);
     else                run_dynamic<SASQ_BF16>(x, wq, s_w, bias, y, acc_out, xq_out, s_row, M, N, K, a_bits, wf, xq_ws, st);
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+// ---- the linears of one layer in two launches ---------------------------------------------------
+extern "C" size_t sasq_static_linear_batch_workspace(const sasq_linear_item* items, int count, sasq_wfmt wf)
+{
+    if (!items || count <= 0 || count > kMaxLinearBatch) return 0;
+    size_t total = 0;
+    for (int i = 0; i < count; ++i) total += sasq_static_linear_workspace(items[i].M, items[i].N, items[i].K, wf);
+    return total;
+}
+
+extern "C" int sasq_static_linear_batch(const sasq_linear_item* items, int count, int a_bits, sasq_wfmt wf,
+                                        sasq_dtype dt, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!items) return SASQ_ERR_NULL;
+    if (count <= 0 || count > kMaxLinearBatch) return SASQ_ERR_SHAPE;
+    if (a_bits < 2 || a_bits > 8) return SASQ_ERR_UNSUPPORTED;
+    if (wf != SASQ_W_INT8 && wf != SASQ_W_INT4_PACKED && wf != SASQ_W_INT8_BLOCKED && wf != SASQ_W_INT4_BLOCKED)
+        return SASQ_ERR_UNSUPPORTED;
+    if (dt != SASQ_F16 && dt != SASQ_BF16) return SASQ_ERR_UNSUPPORTED;
+    const int64_t lim = INT64_C(1) << 40;
+    int64_t total_tiles = 0;
+    for (int i = 0; i < count; ++i) {
+        const sasq_linear_item& it = items[i];
+        if (!it.x || !it.s || !it.wq || !it.s_w || !it.y) return SASQ_ERR_NULL;
+        if (it.M <= 0 || it.N <= 0 || it.K <= 0 || (it.K % kBK)) return SASQ_ERR_SHAPE;      // MFMA shapes only
+        if (it.M > lim / it.K || it.N > lim / it.K || it.M > lim / it.N || it.K > 131071 || it.M > 0x7FFFFFFF || it.N > 0x7FFFFFFF)
+            return SASQ_ERR_SHAPE;
+        if (!aligned16(it.x) || !aligned16(it.wq) || !aligned16(it.y)) return SASQ_ERR_ALIGN;
+        total_tiles += ((it.M + 255) / 256) * ((it.N + 255) / 256) + 8;
+    }
+    if (total_tiles > 0x7FFFFFF0) return SASQ_ERR_SHAPE;
+    if (!workspace || workspace_bytes < sasq_static_linear_batch_workspace(items, count, wf)) return SASQ_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SASQ_ERR_ALIGN;
+
+    // longest K first (stable), see linear_mfma_batch_kernel
+    int order[kMaxLinearBatch];
+    for (int i = 0; i < count; ++i) order[i] = i;
+    for (int i = 1; i < count; ++i)
+        for (int j = i; j > 0 && items[order[j]].K > items[order[j - 1]].K; --j) { const int tmp = order[j]; order[j] = order[j - 1]; order[j - 1] = tmp; }
+
+    LinBatch q{}, g{};
+    char* ws = static_cast<char*>(workspace);
+    int64_t total_vec = 0;
+    for (int i = 0; i < count; ++i) total_vec += items[order[i]].M * items[order[i]].K / 8 + 1;
+    const int kQuantBlocks = 4096;
+    q.count = g.count = count;
+    q.first_block[0] = g.first_block[0] = 0;
+    for (int i = 0; i < count; ++i) {
+        const sasq_linear_item& src = items[order[i]];
+        LinItem li;
+        li.x = src.x;
+        li.xq = reinterpret_cast<int8_t*>(ws);
+        ws += sasq_static_linear_workspace(src.M, src.N, src.K, wf);
+        li.s = src.s;
+        li.wq = static_cast<const uint8_t*>(src.wq);
+        li.s_w = src.s_w;
+        li.bias = src.bias;
+        li.y = static_cast<uint16_t*>(src.y);
+        li.M = (int)src.M; li.N = (int)src.N; li.K = (int)src.K;
+        li.tiles_m = (int)((src.M + 255) / 256);
+        li.tiles_n = (int)((src.N + 255) / 256);
+        q.it[i] = g.it[i] = li;
+        const int64_t nvec = src.M * src.K / 8;
+        int64_t share = ((nvec + 1) * kQuantBlocks + total_vec - 1) / total_vec;
+        const int64_t need = (nvec + 255) / 256;
+        if (share > need) share = need;
+        if (share < 1) share = 1;
+        q.first_block[i + 1] = q.first_block[i] + (int)share;
+        g.first_block[i + 1] = g.first_block[i] + ((li.tiles_m * li.tiles_n + 7) / 8) * 8;
+    }
+    for (int i = count; i < kMaxLinearBatch; ++i) { q.first_block[i + 1] = q.first_block[count]; g.first_block[i + 1] = g.first_block[count]; }
+
+    hipStream_t st = as_stream(stream);
+    const int qgrid = q.first_block[count], ggrid = g.first_block[count];
+    const bool perm8 = wf == SASQ_W_INT4_PACKED;      // row-major packed int4 unpacks in (0,2,4,6,1,3,5,7) order
+#define SASQ_LAUNCH_BATCH(DTV)                                                                                          \
+    do {                                                                                                                \
+        if (perm8) quantize_act_batch_kernel<DTV, true><<<qgrid, 256, 0, st>>>(q, a_bits);                              \
+        else       quantize_act_batch_kernel<DTV, false><<<qgrid, 256, 0, st>>>(q, a_bits);                             \
+        switch (wf) {                                                                                                   \
+            case SASQ_W_INT8:         linear_mfma_batch_kernel<DTV, W_I8><<<ggrid, kGemmThreads, 0, st>>>(g, a_bits); break;   \
+            case SASQ_W_INT4_PACKED:  linear_mfma_batch_kernel<DTV, W_I4><<<ggrid, kGemmThreads, 0, st>>>(g, a_bits); break;   \
+            case SASQ_W_INT8_BLOCKED: linear_mfma_batch_kernel<DTV, W_I8B><<<ggrid, kGemmThreads, 0, st>>>(g, a_bits); break;  \
+            default:                  linear_mfma_batch_kernel<DTV, W_I4B><<<ggrid, kGemmThreads, 0, st>>>(g, a_bits); break;  \
+        }                                                                                                               \
+    } while (0)
+    if (dt == SASQ_F16) SASQ_LAUNCH_BATCH(SASQ_F16);
+    else                SASQ_LAUNCH_BATCH(SASQ_BF16);
+#undef SASQ_LAUNCH_BATCH
     return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
 }

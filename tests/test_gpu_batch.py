@@ -94,3 +94,51 @@ def test_batch_larger_than_one_launch_matches_single_calls():
         assert torch.equal(dx1.view(torch.int16), dx_b[i].view(torch.int16)), i
         a, b = float(ds1.item()), float(first[i].item())
         assert abs(a - b) <= 1e-4 * abs(a) + 1e-3, (i, a, b)
+
+
+# ---------------------------------------------------------------- batched static linear
+from tests.test_gpu_grouped_linear import WF, device_weights  # noqa: E402
+from tests.gpu_util import assert_same_values  # noqa: E402
+
+LIN_BATCHES = [
+    [(33, 47, 128)],
+    [(300, 520, 384), (300, 260, 1024), (300, 520, 64)],
+    [(257, 255, 1024), (40, 300, 64), (512, 768, 512), (64, 256, 256), (1, 1, 128), (260, 70, 192), (130, 700, 512), (256, 256, 128)],
+]
+
+
+@pytest.mark.parametrize("blocked", [False, True])
+@pytest.mark.parametrize("dtype,fmt", [("f16", "int8"), ("bf16", "int4")])
+@pytest.mark.parametrize("batch", LIN_BATCHES, ids=["one", "three", "eight"])
+def test_linear_batch_matches_oracle(batch, dtype, fmt, blocked):
+    wf = WF[(fmt, blocked)]
+    items, refs = [], []
+    for j, (M, N, K) in enumerate(batch):
+        xb = wl.random_bits(91, f"lbx{j}{(M, N, K)}{dtype}", (M, K), dtype, gain=2.0)
+        w = wl.random_f32(91, f"lbw{j}{(M, N, K)}", (N, K), 0.02)
+        wq, s_w = oracle.quantize_weight(w, fmt)
+        bias = wl.random_f32(91, f"lbb{j}", (N,), 0.3) if j % 2 else None
+        s = np.float32(oracle.absmax_scale(xb, 8, dtype) / 3)
+        refs.append(oracle.static_linear(xb, s, wq, s_w, bias, 8, fmt, dtype, want_acc=False, want_xq=False)["y"])
+        y = torch.full((M, N), float("nan"), dtype=TDT[dtype], device="cuda")
+        items.append((to_dev(xb, dtype), dev_scalar(s), device_weights(wq, fmt, blocked), torch.from_numpy(s_w).cuda(),
+                      None if bias is None else torch.from_numpy(bias).cuda(), y))
+    ws = B.new_workspace(B.sasq_static_linear_batch_workspace(items, wf))
+    B.sasq_static_linear_batch(items, wf, ws)
+    torch.cuda.synchronize()
+    for j, it in enumerate(items):
+        assert_same_values(to_bits(it[5]), refs[j], dtype, f"Y of item {j}")
+
+
+def test_linear_batch_rejects():
+    x = torch.zeros((4, 96), dtype=torch.float16, device="cuda")
+    y = torch.zeros((4, 4), dtype=torch.float16, device="cuda")
+    wq = torch.zeros((4, 96), dtype=torch.int8, device="cuda")
+    one = torch.ones(4, dtype=torch.float32, device="cuda")
+    arr, dt = B._lin_items([(x, one[:1], wq, one, None, y)], B.SASQ_W_INT8)
+    ws = B.new_workspace(4096)
+    call = lambda count, bits, wf: B._lib().sasq_static_linear_batch(arr, count, bits, wf, dt, B._ptr(ws), ws.numel(), None)
+    assert call(1, 8, 0) == 2            # K not a multiple of 64
+    assert call(0, 8, 0) == 2
+    assert call(1, 9, 0) == 4
+    assert call(1, 8, 5) == 4
