@@ -34,7 +34,8 @@ INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8, published
 # HBM-side bytes per sasq_static_linear call (both kernels), averaged over gate/up/down of config 3:
 # rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a plain 1 GiB copy), see
 # profiles/bench_c3_mlp7b_counters.txt.  Algorithmic bytes are 221.2 MB.
-C3_LINEAR_TRAFFIC_BYTES = 450721 * 1024
+C3_LINEAR_TRAFFIC_BYTES = 450654 * 1024          # one call per projection, average
+C3_LINEAR_BATCH_TRAFFIC_BYTES = 1389273 * 1024   # the batched call (all three projections)
 HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published
 LR = 2e-4
 TDT = {"f16": torch.float16, "bf16": torch.bfloat16}
@@ -353,7 +354,7 @@ def main():
                                 "sasq_static_linear (activation quantize + int8 MFMA GEMM + dequant)"),
                      "achieved": round(lin_tops, 1), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": round(lin_tops / INT8_MFMA_PEAK_TOPS, 4),
-                     "traffic": (C3_LINEAR_TRAFFIC_BYTES * (len(projs) if ev["lin_batch"] else 1)) if cfg.name == "c3_mlp7b" else None,
+                     "traffic": (C3_LINEAR_BATCH_TRAFFIC_BYTES if ev["lin_batch"] else C3_LINEAR_TRAFFIC_BYTES) if cfg.name == "c3_mlp7b" else None,
                      "traffic_unit": "bytes per call (rocprofv3 FETCH_SIZE/WRITE_SIZE, copy-calibrated)",
                      "algorithmic_bytes": int(sum(3 * p.M * p.K + p.M * p.K + p.wq.numel() + 2 * p.M * p.N + 4 * p.N
                                                   for p in projs) / (1 if ev["lin_batch"] else len(projs))),
