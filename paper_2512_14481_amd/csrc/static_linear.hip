@@ -561,12 +561,8 @@ void linear_mfma_body(const void* __restrict__ xin, const uint8_t* __restrict__ 
         for (int b = 0; b < (GROUPED ? MF : 1); ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) fsum[a][b][v] = 0.0f;
-#pragma unroll
-    for (int a = 0; a < NF; ++a)
-#pragma unroll
-        for (int b = 0; b < MF; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
+    // acc is first written by the MFMAs of K tile 0, which multiply into a zero accumulator operand
+    // (clearing 256 registers per lane first would cost a microsecond per tile)
 
     // ---- K pipeline ----
     // Iteration i consumes K tile i in two phases (K-substeps of 32), each NF groups of MF MFMAs.
@@ -697,15 +693,18 @@ void linear_mfma_body(const void* __restrict__ xin, const uint8_t* __restrict__ 
             ++group_idx;
         }
     };
-    int it = 0;
+    // K tile 0 (there always is one) opens the accumulators; the rest in threes for the register sets
+    if (GROUPED) step(0, R0{});
+    else         iteration(0, Open{}, R0{});
+    int it = 1;
 #pragma unroll 1
     for (; it + 2 < KT; it += 3) {
-        step(it, R0{});
-        step(it + 1, R1{});
-        step(it + 2, R2{});
+        step(it, R1{});
+        step(it + 1, R2{});
+        step(it + 2, R0{});
     }
-    if (it < KT) step(it, R0{});
-    if (it + 1 < KT) step(it + 1, R1{});
+    if (it < KT) step(it, R1{});
+    if (it + 1 < KT) step(it + 1, R2{});
     // drain the tail loads and the last fragment reads before LDS is reused
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0 & waitcnt_vm(0));
     __builtin_amdgcn_s_barrier();
@@ -719,56 +718,53 @@ void linear_mfma_body(const void* __restrict__ xin, const uint8_t* __restrict__ 
     char* epi = &lds[wave * T::kEpiBytes];
     const int wn0 = n0 + wn * (BN / 2), wm0 = m0 + wm * (BM / 2);
     constexpr int kAccShift = (WMODE == W_I4 || WMODE == W_I4B) ? 4 : 0;
+    // The nest
+    // below is straight-line code over all 256 accumulators; what the common call does not need
+    // (bias, inspection outputs) is kept out of it: the epilogue is bound by instruction issue and
+    // fetch (measured: 9 us of a 60 us tile at K = 4096).
+    float srow[MF];                                            // ROWS: the factor of each row this lane holds
 #pragma unroll
-    for (int a = 0; a < NF; ++a) {
+    for (int b = 0; b < MF; ++b) srow[b] = ROWS ? s_ptr[min(wm0 + b * 32 + frow, M - 1)] : 1.0f;
+    auto write_tile = [&](auto bias_tag) {
+        constexpr bool BIAS = decltype(bias_tag)::value;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int nl = a * 32 + 8 * g + 4 * fgrp;          // column within the wave's block
-            float c[4], bz[4];
+        for (int a = 0; a < NF; ++a) {
+            // this column tile's factors, requested together.  (All 64 up front would save three
+            // memory latencies per tile but spill registers to scratch: 15 -> 27 us on a one-iteration tile.)
+            float cs[4][4], bs[4][4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int ne = min(wn0 + nl + e, N - 1);
-                c[e] = (GROUPED || ROWS) ? s_w[ne] : s * s_w[ne];
-                bz[e] = has_bias ? bias[ne] : 0.0f;
-            }
+            for (int g = 0; g < 4; ++g)
 #pragma unroll
-            for (int b = 0; b < MF; ++b) {
-                const int ml = b * 32 + frow;
-                int av[4];
-                u32x2 pk;
-                if (GROUPED) {
-                    // Y = fl32(f * s_w[n]) (+ bias); the debug output is f itself
-                    float fv[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        fv[e] = fsum[GROUPED ? a : 0][GROUPED ? b : 0][4 * g + e];
-                        av[e] = __float_as_int(fv[e]);
-                        fv[e] = fv[e] * c[e];
-                        if (has_bias) fv[e] = fv[e] + bz[e];
-                    }
-                    pk[0] = S::pack(fv[0], fv[1]);
-                    pk[1] = S::pack(fv[2], fv[3]);
-                } else {
-                    float cc[4];
-                    const float sr = ROWS ? s_ptr[min(wm0 + ml, M - 1)] : 1.0f;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        av[e] = acc[a][b][4 * g + e] >> kAccShift;
-                        cc[e] = ROWS ? sr * c[e] : c[e];
-                    }
-                    pk[0] = S::pack(dequant(av[0], cc[0], bz[0], has_bias), dequant(av[1], cc[1], bz[1], has_bias));
-                    pk[1] = S::pack(dequant(av[2], cc[2], bz[2], has_bias), dequant(av[3], cc[3], bz[3], has_bias));
+                for (int e = 0; e < 4; ++e) {
+                    const int ne = min(wn0 + a * 32 + 8 * g + 4 * fgrp + e, N - 1);
+                    cs[g][e] = (GROUPED || ROWS) ? s_w[ne] : s * s_w[ne];
+                    bs[g][e] = BIAS ? bias[ne] : 0.0f;
                 }
-                *reinterpret_cast<u32x2*>(epi + ml * T::kEpiStride + nl * 2) = pk;
-                if (acc_out) {
-                    const int m = wm0 + ml, n = wn0 + nl;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (m < M && n + e < N) acc_out[(int64_t)m * N + n + e] = av[e];
+            for (int g = 0; g < 4; ++g) {
+                const int nl = a * 32 + 8 * g + 4 * fgrp;      // column within the wave's block
+#pragma unroll
+                for (int b = 0; b < MF; ++b) {
+                    const int ml = b * 32 + frow;
+                    float yv[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (GROUPED) {
+                            yv[e] = fsum[GROUPED ? a : 0][GROUPED ? b : 0][4 * g + e] * cs[g][e];      // Y = fl32(f * s_w[n])
+                            if (BIAS) yv[e] = yv[e] + bs[g][e];
+                        } else {
+                            const float cc = ROWS ? srow[b] * cs[g][e] : cs[g][e];
+                            yv[e] = dequant(acc[a][b][4 * g + e] >> kAccShift, cc, bs[g][e], BIAS);
+                        }
+                    }
+                    u32x2 pk = {S::pack(yv[0], yv[1]), S::pack(yv[2], yv[3])};
+                    *reinterpret_cast<u32x2*>(epi + ml * T::kEpiStride + nl * 2) = pk;
                 }
             }
         }
-    }
+    };
+    if (has_bias) write_tile(std::true_type{});
+    else          write_tile(std::false_type{});
     // each wave reads back only what it wrote itself: no workgroup barrier needed
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
@@ -790,6 +786,24 @@ void linear_mfma_body(const void* __restrict__ xin, const uint8_t* __restrict__ 
             for (int e = 0; e < 8; ++e)
                 if (n + e < N) dst[e] = (uint16_t)(v[e >> 1] >> (16 * (e & 1)));
         }
+    }
+    // inspection output (int32 accumulators, or the fp32 group sums): straight from the registers,
+    // after and apart from the common path
+    if (acc_out) {
+#pragma unroll
+        for (int a = 0; a < NF; ++a)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int b = 0; b < MF; ++b) {
+                    const int m = wm0 + b * 32 + frow, n = wn0 + a * 32 + 8 * g + 4 * fgrp;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int v = GROUPED ? __float_as_int(fsum[GROUPED ? a : 0][GROUPED ? b : 0][4 * g + e])
+                                              : (acc[a][b][4 * g + e] >> kAccShift);
+                        if (m < M && n + e < N) acc_out[(int64_t)m * N + n + e] = v;
+                    }
+                }
     }
 }
 
