@@ -725,6 +725,8 @@ void linear_mfma_body(const void* __restrict__ xin, const uint8_t* __restrict__ 
     float srow[MF];                                            // ROWS: the factor of each row this lane holds
 #pragma unroll
     for (int b = 0; b < MF; ++b) srow[b] = ROWS ? s_ptr[min(wm0 + b * 32 + frow, M - 1)] : 1.0f;
+    const bool cols_inside = wn0 + BN / 2 <= N && (reinterpret_cast<uintptr_t>(s_w) & 15u) == 0 &&
+                             (bias == nullptr || (reinterpret_cast<uintptr_t>(bias) & 15u) == 0);
     auto write_tile = [&](auto bias_tag) {
         constexpr bool BIAS = decltype(bias_tag)::value;
 #pragma unroll
@@ -732,14 +734,30 @@ void linear_mfma_body(const void* __restrict__ xin, const uint8_t* __restrict__ 
             // this column tile's factors, requested together.  (All 64 up front would save three
             // memory latencies per tile but spill registers to scratch: 15 -> 27 us on a one-iteration tile.)
             float cs[4][4], bs[4][4];
+            if (cols_inside) {
+                // whole block inside N and 16-byte aligned factor arrays: one 128-bit load per four columns
 #pragma unroll
-            for (int g = 0; g < 4; ++g)
+                for (int g = 0; g < 4; ++g) {
+                    const int nb = wn0 + a * 32 + 8 * g + 4 * fgrp;
+                    const f32x4 sv = *reinterpret_cast<const f32x4*>(s_w + nb);
+                    f32x4 bv = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if (BIAS) bv = *reinterpret_cast<const f32x4*>(bias + nb);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int ne = min(wn0 + a * 32 + 8 * g + 4 * fgrp + e, N - 1);
-                    cs[g][e] = (GROUPED || ROWS) ? s_w[ne] : s * s_w[ne];
-                    bs[g][e] = BIAS ? bias[ne] : 0.0f;
+                    for (int e = 0; e < 4; ++e) {
+                        cs[g][e] = (GROUPED || ROWS) ? sv[e] : s * sv[e];
+                        bs[g][e] = bv[e];
+                    }
                 }
+            } else {
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int ne = min(wn0 + a * 32 + 8 * g + 4 * fgrp + e, N - 1);
+                        cs[g][e] = (GROUPED || ROWS) ? s_w[ne] : s * s_w[ne];
+                        bs[g][e] = BIAS ? bias[ne] : 0.0f;
+                    }
+            }
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int nl = a * 32 + 8 * g + 4 * fgrp;      // column within the wave's block
@@ -772,6 +790,21 @@ void linear_mfma_body(const void* __restrict__ xin, const uint8_t* __restrict__ 
     constexpr int kChunksPerRow = BN / 16;                      // 16-byte chunks in a wave-block row
     constexpr int kRowsPerPass = 64 / kChunksPerRow;
     const int crow = lane / kChunksPerRow, cchunk = lane % kChunksPerRow;
+    if (vec_ok && wm0 + BM / 2 <= M && wn0 + BN / 2 <= N) {
+        // block inside the matrix: no bounds, eight LDS reads in flight, then their eight stores
+        const char* src = epi + crow * T::kEpiStride + cchunk * 16;
+        char* dst = reinterpret_cast<char*>(y + (int64_t)(wm0 + crow) * N + wn0 + cchunk * 8);
+        const int64_t row_step = (int64_t)kRowsPerPass * N * 2;
+        constexpr int kPasses = (BM / 2) / kRowsPerPass;
+#pragma unroll
+        for (int p0 = 0; p0 < kPasses; p0 += 8) {
+            u32x4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = *reinterpret_cast<const u32x4*>(src + (p0 + j) * kRowsPerPass * T::kEpiStride);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x4*>(dst + (p0 + j) * row_step) = v[j];
+        }
+    } else
 #pragma unroll 4
     for (int p = 0; p < (BM / 2) / kRowsPerPass; ++p) {
         const int ml = p * kRowsPerPass + crow;
