@@ -162,3 +162,66 @@ def test_static_linear_full_size(cfg_name, proj_name, ws):
     assert np.array_equal(acc[:, ci].cpu().numpy(), ref_c["acc"]), "int32 accumulators (columns)"
     assert_same_values(to_bits(y[:, ci].contiguous()), ref_c["y"], dtype, "Y columns (exact)")
     assert torch.isfinite(y.float()).all()
+
+
+@pytest.mark.parametrize("cfg_name", ["c2_attn7b", "c3_mlp7b", "c4_w4a8_13b", "c5_layer70b"])
+def test_batched_layer_calls_match_single_calls_full_size(cfg_name):
+    """The launch configuration the benchmark times: every projection of the config through the
+    batched fake-quant and batched linear entry points, against the single-tensor calls (which the
+    tests above tie to the oracle): y, dx and Y bit-identical, ds within the reduction-order tolerance."""
+    cfg = wl.CONFIGS[cfg_name]
+    dt = TDT[cfg.dtype]
+    wf_rm = B.SASQ_W_INT8 if cfg.w_fmt == "int8" else B.SASQ_W_INT4_PACKED
+    wf = B.SASQ_W_INT8_BLOCKED if cfg.w_fmt == "int8" else B.SASQ_W_INT4_BLOCKED
+    g = torch.Generator(device="cuda").manual_seed(17)
+    M = cfg.M
+    fq_fwd, fq_bwd, lin, singles = [], [], [], []
+    n = len(cfg.projs)
+    s_all = torch.empty(n, dtype=torch.float32, device="cuda")
+    ds_all = torch.zeros(n, dtype=torch.float32, device="cuda")
+    for i, p in enumerate(cfg.projs):
+        K, N = cfg.K_of(p), p.N
+        x = (torch.randn((M, K), device="cuda", generator=g) * 1.5).to(dt)
+        x[:, 7] *= 30                                   # an outlier channel that clips
+        dy = torch.randn((M, K), device="cuda", generator=g).to(dt)
+        s_all[i] = float(x.abs().max()) / 127 / 3
+        if cfg.w_fmt == "int8":
+            wq = torch.randint(-127, 128, (N, K), device="cuda", generator=g, dtype=torch.int8)
+        else:
+            wq = torch.randint(0, 256, (N, K // 2), device="cuda", generator=g, dtype=torch.uint8)
+        pk = torch.empty(B.sasq_packed_weight_bytes(N, K, wf), dtype=torch.uint8, device="cuda")
+        B.sasq_pack_weight(wq, pk, N, K, wf_rm)
+        del wq
+        s_w = torch.rand(N, device="cuda", generator=g) * 1e-3 + 1e-4
+        y_b, dx_b = torch.empty_like(x), torch.empty_like(x)
+        Y_b = torch.empty((M, N), dtype=dt, device="cuda")
+        fq_fwd.append((x, s_all[i:i + 1], y_b))
+        fq_bwd.append((x, dy, s_all[i:i + 1], dx_b, ds_all[i:i + 1]))
+        lin.append((x, s_all[i:i + 1], pk, s_w, None, Y_b))
+    ws_b = B.new_workspace(B.sasq_fakequant_bwd_batch_workspace(n))
+    ws_l = B.new_workspace(B.sasq_static_linear_batch_workspace(lin, wf))
+    B.sasq_fakequant_fwd_batch(fq_fwd, 8)
+    B.sasq_fakequant_bwd_batch(fq_bwd, ws_b, 8)
+    B.sasq_static_linear_batch(lin, wf, ws_l)
+    torch.cuda.synchronize()
+    ws1 = B.new_workspace(B.sasq_fakequant_bwd_workspace(1, 1))
+    ds1 = torch.zeros(1, dtype=torch.float32, device="cuda")
+    for i, p in enumerate(cfg.projs):
+        x, s, y_b = fq_fwd[i]
+        _, dy, _, dx_b, _ = fq_bwd[i]
+        y1, dx1 = torch.empty_like(x), torch.empty_like(x)
+        B.sasq_fakequant_fwd(x, s, y1, None, 8)
+        B.sasq_fakequant_bwd(x, dy, s, dx1, ds1, ws1, 8)
+        assert torch.equal(y1.view(torch.int16), y_b.view(torch.int16)), (p.name, "y")
+        assert torch.equal(dx1.view(torch.int16), dx_b.view(torch.int16)), (p.name, "dx")
+        a, b = float(ds1.item()), float(ds_all[i].item())
+        assert abs(a - b) <= 1e-4 * abs(a) + 1e-2, (p.name, a, b)
+        del y1, dx1
+        _, _, pk, s_w, _, Y_b = lin[i]
+        Y1 = torch.empty_like(Y_b)
+        wsl = B.new_workspace(B.sasq_static_linear_workspace(M, p.N, cfg.K_of(p), wf))
+        B.sasq_static_linear(x, s, pk, s_w, None, Y1, wf, wsl)
+        torch.cuda.synchronize()
+        assert torch.equal(Y1.view(torch.int16), Y_b.view(torch.int16)), (p.name, "Y")
+        assert torch.isfinite(Y_b.float()).all()
+        del Y1, wsl
