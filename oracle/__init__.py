@@ -203,6 +203,27 @@ def dynamic_linear(x: np.ndarray, wq: np.ndarray, s_w: np.ndarray, bias: Optiona
     return {"y": y, "acc": acc, "xq": xq, "s_row": s_row}
 
 
+def linear_bwd_input(dy: np.ndarray, wq: np.ndarray, s_w: np.ndarray, w_fmt: str, dtype: str):
+    """dX = dY . Wq with Wq the dequantized frozen weight in the 16-bit type.
+    Returns dict(dx=uint16 [M,K], wq16=uint16 [N,K], sum_abs=float64 [M,K], exact=float64 [M,K])."""
+    dy = _u16(dy)
+    M, N = dy.shape
+    wq = np.ascontiguousarray(wq)
+    assert wq.dtype in (np.int8, np.uint8) and wq.shape[0] == N
+    K = wq.shape[1] * (1 if w_fmt == "int8" else 2)
+    s_w = np.ascontiguousarray(s_w, dtype=np.float32)
+    assert s_w.shape == (N,)
+    dx = np.empty((M, K), dtype=np.uint16)
+    w16 = np.empty((N, K), dtype=np.uint16)
+    sabs = np.empty((M, K), dtype=np.float64)
+    exact = np.empty((M, K), dtype=np.float64)
+    rc = lib().sasq_oracle_linear_bwd_input(_p(dy), _p(wq), _p(s_w), _p(dx), _p(w16), _p(sabs), _p(exact),
+                                            ctypes.c_int64(M), ctypes.c_int64(N), ctypes.c_int64(K),
+                                            WF[w_fmt], DT[dtype])
+    _check(rc, "linear_bwd_input")
+    return {"dx": dx, "wq16": w16, "sum_abs": sabs, "exact": exact}
+
+
 def quantize_weight(w: np.ndarray, w_fmt: str) -> Tuple[np.ndarray, np.ndarray]:
     """w: fp32 [N,K] -> (wq int8 [N,K] | uint8 [N,K/2], s_w fp32 [N])."""
     w = np.ascontiguousarray(w, dtype=np.float32)

@@ -438,6 +438,58 @@ int sasq_oracle_dynamic_linear(const uint16_t* x, const uint8_t* wq, const float
 }
 
 /*
+ * Backward of the training-time linear with respect to its (fake-quantized) input: the step that
+ * hands the fake-quant operator its upstream gradient during scale training (Sec. 4.2: gradients
+ * flow back through the frozen, quantized linear layers to the quantization factors).  The frozen
+ * weight takes part as the dequantized tensor held in the model's 16-bit type (Eq. 2's
+ * W_int * S_w, one factor per output channel; reading: rounded once to the storage type, as a
+ * framework holding the fake-quantized weight would):
+ *     Wq[n,k]  = round16(fl32(fl32(W_int[n,k]) * s_w[n]))
+ *     dX[m,k]  = round16(sum_n dY[m,n] * Wq[n,k])        (sum in fp64 here; products are exact)
+ * wq16_out (optional) receives Wq as 16-bit patterns, sum_abs_out (optional) sum_n |dY*Wq| per
+ * output (the scale of the fp32 accumulation error a GPU kernel is allowed).
+ */
+int sasq_oracle_linear_bwd_input(const uint16_t* dy, const uint8_t* wq, const float* s_w, uint16_t* dx,
+                                 uint16_t* wq16_out, double* sum_abs_out, double* exact_out,
+                                 int64_t M, int64_t N, int64_t K, int wf, int dt)
+{
+    if (dt != DT_F16 && dt != DT_BF16) return ERR_ARG;
+    if (wf != WF_INT8 && wf != WF_INT4_PACKED) return ERR_ARG;
+    if (wf == WF_INT4_PACKED && (K & 1)) return ERR_ARG;
+    uint16_t* w16 = (uint16_t*)malloc(sizeof(uint16_t) * (size_t)(N * K > 0 ? N * K : 1));
+    if (!w16) return ERR_NOMEM;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            int w;
+            if (wf == WF_INT8) w = (int8_t)wq[n * K + k];
+            else {
+                uint8_t byte = wq[n * (K / 2) + k / 2];
+                w = nibble_to_int((k & 1) ? (byte >> 4) : (byte & 15u));
+            }
+            volatile float wf32 = (float)w;
+            volatile float prod = wf32 * s_w[n];
+            w16[n * K + k] = store16(prod, dt);
+        }
+    if (wq16_out) memcpy(wq16_out, w16, sizeof(uint16_t) * (size_t)(N * K));
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            double acc = 0.0, sabs = 0.0;
+            for (int64_t n = 0; n < N; ++n) {
+                const double t = load16(dy, m * N + n, dt) * load16(w16, n * K + k, dt);
+                acc += t;
+                sabs += fabs(t);
+            }
+            if (dx) dx[m * K + k] = store16((float)acc, dt);
+            if (sum_abs_out) sum_abs_out[m * K + k] = sabs;
+            if (exact_out) exact_out[m * K + k] = acc;
+        }
+    free(w16);
+    return OK;
+}
+
+/*
  * Frozen-weight quantization, symmetric, one scale per output channel (row of W[N,K])
  * (Sec. 3, Eq. 1 applied per row; Sec. 5.1 fixes weights to one factor per output channel):
  *   s_w[n] = fl32(max_k |W[n,k]| / Qp)   (1 if the row is all zero)

@@ -47,13 +47,17 @@ MUTATIONS = [
     ("dynamic_factor_divides_by_128", "volatile float den = (float)Qp;\n        volatile float sm = num / den;",
      "volatile float den = (float)(Qp + 1);\n        volatile float sm = num / den;"),
     ("dynamic_zero_row_unhandled", "if (amax == 0.0) sm = 1.0f;", ""),
+    ("bwd_linear_transposed_weight", "load16(w16, n * K + k, dt);", "load16(w16, (k % N) * K + (n % K), dt);"),
+    ("bwd_linear_weight_factor_dropped", "volatile float prod = wf32 * s_w[n];", "volatile float prod = wf32;"),
+    ("bwd_linear_weight_factor_first_channel", "volatile float prod = wf32 * s_w[n];", "volatile float prod = wf32 * s_w[0];"),
+    ("bwd_linear_dy_row_stride", "load16(dy, m * N + n, dt) *", "load16(dy, (m * K + n) % (M * N), dt) *"),
     ("sgd_plus", "volatile float out = s - step;", "volatile float out = s + step;"),
 ]
 
 PIN_FILES = ["tests/test_oracle_pins.py", "tests/test_oracle_pins_pc.py", "tests/test_oracle_pins_grouped.py",
-             "tests/test_oracle_pins_dynamic.py"]
+             "tests/test_oracle_pins_dynamic.py", "tests/test_oracle_pins_bwd_linear.py"]
 SELECT = ("hand_table or closed_forms or autograd or static_linear or int4 or weight_quantizer or scale_sgd "
-          "or encode or decode or per_channel or ds_terms or reciprocal or epilogue or grouped or dynamic")
+          "or encode or decode or per_channel or ds_terms or reciprocal or epilogue or grouped or dynamic or bwd_linear")
 
 
 def run_pins(src_path: str) -> int:
