@@ -309,6 +309,36 @@ int sasq_quantize_weight(const float* w, void* wq, float* s_w, int64_t N, int64_
 size_t sasq_packed_weight_bytes(int64_t N, int64_t K, sasq_wfmt wf);
 int sasq_pack_weight(const void* wq, void* packed, int64_t N, int64_t K, sasq_wfmt wf_src, void* stream);
 
+/*
+ * Backward of the frozen quantized linear with respect to its input: the step that hands each
+ * fake-quant operator its upstream gradient during scale training (Sec. 4.2; the weight is
+ * Eq. 2's W_int * S_w, frozen):
+ *     Wq[n,k] = round16(fl32(fl32(W_int[n,k]) * s_w[n]))        (prepared once)
+ *     dX[m,k] = round16(sum_n dY[m,n] * Wq[n,k])                 (16-bit MFMA, fp32 accumulation)
+ * The sum's rounding order is the matrix unit's: dX agrees with the exactly rounded result within
+ * the fp32 accumulation bound N * 2^-24 * sum_n |dY[m,n] * Wq[n,k]| plus one 16-bit rounding.
+ *
+ * sasq_prepare_bwd_weight writes Wq transposed and cut into the GEMM's operand blocks:
+ *   B[k][n] = Wq[n][k]; 1 KB blocks of 16 rows (k) x 32 columns (n), block (k/16, n/32) at
+ *   ((k/16) * N/32 + n/32) * 1024; inside, the 16-byte chunk c (8 columns) of row r at
+ *   16 * (4r + (c ^ ((r >> 1) & 3) ^ ((r >> 3) & 1))).  Rows past K in the last block are zero.
+ *   wq       device, row-major codes [N,K], SASQ_W_INT8 or SASQ_W_INT4_PACKED
+ *   s_w      device, N floats
+ *   wt       device, sasq_bwd_weight_bytes(N, K) bytes, 16-byte aligned, written
+ *   N        multiple of 32 (SASQ_ERR_SHAPE otherwise; sasq_bwd_weight_bytes then returns 0)
+ * sasq_linear_bwd_input:
+ *   dy       device, [M,N] row-major 16-bit, 16-byte aligned, read only
+ *   wt       device, as prepared for the same N, K and dt
+ *   dx       device, [M,K] row-major 16-bit, 16-byte aligned, written; must not alias dy
+ *   acc_out  device, optional (NULL to skip): [M,K] floats, the fp32 sums before the 16-bit rounding
+ * sasq_bwd_weight_bytes is a pure host function.
+ */
+size_t sasq_bwd_weight_bytes(int64_t N, int64_t K);
+int sasq_prepare_bwd_weight(const void* wq, const float* s_w, void* wt, int64_t N, int64_t K,
+                            sasq_wfmt wf, sasq_dtype dt, void* stream);
+int sasq_linear_bwd_input(const void* dy, const void* wt, void* dx, float* acc_out,
+                          int64_t M, int64_t N, int64_t K, sasq_dtype dt, void* stream);
+
 /* Bytes of workspace sasq_absmax_scale needs (pure function, host only). */
 size_t sasq_absmax_scale_workspace(int64_t rows, int64_t cols);
 

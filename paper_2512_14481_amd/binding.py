@@ -86,6 +86,10 @@ def _lib() -> ctypes.CDLL:
         L.sasq_packed_weight_bytes.restype = sz
         L.sasq_packed_weight_bytes.argtypes = [i64, i64, i32]
         L.sasq_pack_weight.argtypes = [vp, vp, i64, i64, i32, vp]
+        L.sasq_bwd_weight_bytes.restype = sz
+        L.sasq_bwd_weight_bytes.argtypes = [i64, i64]
+        L.sasq_prepare_bwd_weight.argtypes = [vp, vp, vp, i64, i64, i32, i32, vp]
+        L.sasq_linear_bwd_input.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp]
         L.sasq_absmax_scale_workspace.restype = sz
         L.sasq_absmax_scale_workspace.argtypes = [i64, i64]
         L.sasq_absmax_scale.argtypes = [vp, vp, i64, i64, i32, i32, vp, sz, vp]
@@ -396,6 +400,39 @@ def sasq_pack_weight(wq: torch.Tensor, packed: torch.Tensor, N: int, K: int, wf_
     if packed.numel() * packed.element_size() != sasq_packed_weight_bytes(N, K, blocked):
         raise ValueError("packed must have sasq_packed_weight_bytes(N, K, blocked format) bytes")
     _check(_lib().sasq_pack_weight(_ptr(wq), _ptr(packed), N, K, wf_src, _stream()), "sasq_pack_weight")
+
+
+def sasq_bwd_weight_bytes(N: int, K: int) -> int:
+    return int(_lib().sasq_bwd_weight_bytes(N, K))
+
+
+def sasq_prepare_bwd_weight(wq: torch.Tensor, s_w: torch.Tensor, wt: torch.Tensor, N: int, K: int,
+                            wf: int, dtype: torch.dtype) -> None:
+    _want(s_w, torch.float32, "s_w")
+    if dtype not in _DT:
+        raise TypeError("dtype must be float16 or bfloat16")
+    if wq.numel() * wq.element_size() != (N * K if wf == SASQ_W_INT8 else N * (K // 2)):
+        raise ValueError("wq does not hold N x K codes in the row-major format wf")
+    if s_w.numel() != N:
+        raise ValueError("s_w must hold N factors")
+    if wt.numel() * wt.element_size() != sasq_bwd_weight_bytes(N, K):
+        raise ValueError("wt must have sasq_bwd_weight_bytes(N, K) bytes")
+    _check(_lib().sasq_prepare_bwd_weight(_ptr(wq), _ptr(s_w), _ptr(wt), N, K, wf, _DT[dtype], _stream()),
+           "sasq_prepare_bwd_weight")
+
+
+def sasq_linear_bwd_input(dy: torch.Tensor, wt: torch.Tensor, dx: torch.Tensor, K: int,
+                          acc_out: Optional[torch.Tensor] = None) -> None:
+    M, N = dy.shape
+    _want(acc_out, torch.float32, "acc_out")
+    if acc_out is not None and tuple(acc_out.shape) != (M, K):
+        raise ValueError("acc_out must be [M, K]")
+    if dx.dtype != dy.dtype or tuple(dx.shape) != (M, K):
+        raise ValueError("dx must be [M, K] of dy's dtype")
+    if wt.numel() * wt.element_size() != sasq_bwd_weight_bytes(N, K):
+        raise ValueError("wt must have sasq_bwd_weight_bytes(N, K) bytes")
+    _check(_lib().sasq_linear_bwd_input(_ptr(dy), _ptr(wt), _ptr(dx), _ptr(acc_out), M, N, K, _dt(dy), _stream()),
+           "sasq_linear_bwd_input")
 
 
 def sasq_absmax_scale_workspace(rows: int, cols: int) -> int:

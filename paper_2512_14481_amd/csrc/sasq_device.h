@@ -64,11 +64,22 @@ __device__ __forceinline__ bool unclipped(const QElem& e) { return e.f == e.c; }
 // ---- 16-bit storage types -------------------------------------------------------------------
 template <int DT> struct Store16;
 
+// An fp32 value whose rounding to fp32 is part of the numerical contract, made opaque to the
+// compiler before it is narrowed to 16 bits.  Without this, clang folds "multiply, then convert
+// to half" into v_fma_mixlo_f16, which rounds the exact product once; the contract (and the plain
+// two-step code) rounds to fp32 first, and the two differ when the fp32 product lands on a
+// half-precision tie.
+__device__ __forceinline__ float rounded_f32(float f)
+{
+    asm("" : "+v"(f));
+    return f;
+}
+
 template <> struct Store16<SASQ_F16> {
     static __device__ __forceinline__ float lo(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xFFFFu)); }
     static __device__ __forceinline__ float hi(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)); }
     static __device__ __forceinline__ float one(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
-    static __device__ __forceinline__ uint16_t enc(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
+    static __device__ __forceinline__ uint16_t enc(float f) { return __builtin_bit_cast(uint16_t, (_Float16)rounded_f32(f)); }
     static __device__ __forceinline__ uint32_t pack(float a, float b)
     {
         typedef _Float16 h2 __attribute__((ext_vector_type(2)));

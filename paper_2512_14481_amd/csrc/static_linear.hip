@@ -1,19 +1,12 @@
 // Static-inference quantized linear (Sec. 3, Eq. 2) for gfx950: activation quantize with the
 // fixed scale, int8 MFMA GEMM against frozen per-output-channel weights, dequantizing epilogue.
 #include "sasq_device.h"
+#include "gemm_tile.h"
 #include <cstdlib>
 #include <cstring>
 #include <type_traits>
 
 namespace sasq {
-
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
-typedef const __attribute__((address_space(1))) void* glb_ptr_t;
-
-// s_waitcnt immediates (gfx9 encoding): vmcnt split over bits [3:0] and [15:14]; expcnt and
-// lgkmcnt left at "no wait".
-constexpr int waitcnt_vm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8); }
-constexpr int kWaitLgkm0 = 0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8);
 
 // ---------------------------------------------------------------------------------------------
 // Activation quantize pre-pass: xq[m,k] = clamp(round(X[m,k]/s))  (Sec. 3, Eq. 1), int8.
@@ -25,7 +18,6 @@ constexpr int kWaitLgkm0 = 0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8);
 // wave's direct-to-LDS load deposits, so the GEMM fetches each block as one contiguous 1 KB read
 // (full cache lines) instead of sixteen 64-byte row pieces.  Needs K % 64 == 0.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ int swz64(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
 
 template <int DT, bool PERM8, bool TILED>
 __device__ __forceinline__ void quantize_act_body(
@@ -324,45 +316,8 @@ __global__ __launch_bounds__(256) void linear_grouped_scalar_kernel(
 // Epilogue: each wave dequantizes its 128x128 block, stages it through its own LDS region as
 // 16-bit values in [m][n] order and writes Y with 128-bit stores, 256 contiguous bytes per row.
 // ---------------------------------------------------------------------------------------------
-constexpr int kBK = 64;
-constexpr int kStages = 4;
-constexpr int kGemmThreads = 256;
 constexpr int64_t kFusedMaxN = 0;                   // quantize-on-load when N has at most this many columns
 constexpr double kCost128x256 = 1.28, kCost128x128 = 1.42;   // time per output element relative to 256x256 tiles
-
-// Tile geometry.  BM x BN is the workgroup tile (256x256, 128x256 or 128x128); the four waves
-// form a 2x2 grid, each owning (BM/2) x (BN/2) as MF x NF tiles of 32x32.
-template <int BM, int BN>
-struct Tile {
-    static_assert((BM == 128 || BM == 256) && (BN == 128 || BN == 256) && BM <= BN, "unsupported tile");
-    static constexpr int MF = BM / 64, NF = BN / 64;                    // 32x32 tiles per wave along m, n
-    static constexpr int XS = BM / 64, WS = BN / 64;                    // 1 KB slabs per wave per stage
-    static constexpr int kXBytes = BM * kBK, kWBytes = BN * kBK;        // per stage
-    static constexpr int kStageBytes = kXBytes + kWBytes;
-    static constexpr int kEpiStride = BN + 16;                          // bytes per staged output row (+16: bank spread)
-    static constexpr int kEpiBytes = (BM / 2) * kEpiStride;             // per wave
-    static constexpr int kLds = 4 * kEpiBytes > kStages * kStageBytes ? 4 * kEpiBytes : kStages * kStageBytes;
-    static constexpr int kWavesPerSimd = (MF * NF * 16 <= 64) ? 2 : 1;  // 128x128 tiles: two workgroups per CU
-};
-
-// XCD-aware tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2:
-// give every XCD a contiguous range of logical tile ids, and number the tiles so that 32
-// consecutive ids (what one XCD's 32 CUs hold at a time) form an 8 (m) x 4 (n) block that shares
-// 8 activation row-panels and 4 weight row-panels in that L2.
-__device__ __forceinline__ bool tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn)
-{
-    constexpr int PN = 4;                              // n-tiles per panel (2..8 measured within noise of each other)
-    const int total = tiles_m * tiles_n;
-    const int per = (total + 7) >> 3;
-    const int logical = (bid & 7) * per + (bid >> 3);
-    if (logical >= total) return false;
-    const int panel = logical / (tiles_m * PN);
-    const int in = logical - panel * tiles_m * PN;
-    const int width = min(PN, tiles_n - panel * PN);   // last panel may be narrower
-    tm = in / width;
-    tn = panel * PN + in % width;
-    return true;
-}
 
 // Operand paths of the GEMM kernel.
 //   XMODE 0: activations were quantized by a separate pass; int8 tile goes L2 -> LDS directly.

@@ -105,6 +105,55 @@ def test_fakequant_shapes(dtype, shape, ws):
         assert ds_nodx == ds
 
 
+def _half_tie_cases(count=6):
+    """(s, q) pairs for which the fp32 product q*s is exactly halfway between two fp16 values while
+    the exact product is not: rounding the exact product once and rounding fl32(q*s) differ there."""
+    from fractions import Fraction
+    rng = np.random.default_rng(20250607)
+    out = []
+    while len(out) < count:
+        s = np.float32(rng.uniform(0.01, 0.1))
+        for q in range(3, 128):
+            p32 = np.float32(q) * s                                  # numpy: one fp32 rounding
+            lo = np.float16(p32)
+            if float(lo) == float(p32):
+                continue
+            other = np.nextafter(lo, np.float16(np.inf) if float(p32) > float(lo) else np.float16(-np.inf))
+            if Fraction(float(lo)) + Fraction(float(other)) != 2 * Fraction(float(p32)):
+                continue                                             # not a tie
+            exact = float(Fraction(q) * Fraction(float(s)))          # at most 31 significant bits: exact in a double
+            if np.float16(exact) == lo:
+                continue                                             # one rounding of the exact product agrees
+            out.append((s, q))
+            break
+    return out
+
+
+@pytest.mark.parametrize("shape", [(1, 7), (3, 5), (1, 8), (9, 1031), (64, 256)])
+def test_fakequant_fp16_output_rounds_the_fp32_product(shape):
+    """Y = round16(fl32(q * s)): the fp32 rounding comes first.  Inputs are chosen so that a fused
+    multiply-and-narrow (one rounding of the exact product) would give the other neighbour; they are
+    placed everywhere, so both the vector body and the scalar tail of the kernels meet them."""
+    for s, q in _half_tie_cases():
+        xv = np.full(shape, np.float32(q) * s, dtype=np.float32)
+        xv[::2, ::3] *= -1
+        x = wl.f32_to_storage_bits(xv, "f16")
+        y_ref, c_ref = oracle.fakequant_fwd(x, s, 8, "f16")
+        assert np.abs(c_ref).min() == q and np.abs(c_ref).max() == q
+        y, c = run_fwd(x, s, 8, "f16")
+        assert np.array_equal(c, c_ref)
+        assert_same_values(y, y_ref, "f16", f"y s={s} q={q}")
+        # per-channel factors: the same case in every column
+        s_pc = np.full((shape[1],), s, dtype=np.float32)
+        y_ref_pc, _ = oracle.fakequant_fwd_pc(x, s_pc, 8, "f16")
+        assert np.array_equal(y_ref_pc, y_ref)
+        xd = to_dev(x, "f16")
+        yd = torch.empty_like(xd)
+        B.sasq_fakequant_fwd_pc(xd, torch.from_numpy(s_pc).cuda(), yd, None, 8)
+        torch.cuda.synchronize()
+        assert_same_values(to_bits(yd), y_ref, "f16", f"per-channel y s={s} q={q}")
+
+
 def test_fakequant_in_place_and_determinism(ws):
     dtype = "f16"
     xb = wl.random_bits(8, "inplace", (300, 1000), dtype, gain=2.0)
