@@ -31,6 +31,7 @@ from paper_2512_14481_amd import binding as B          # noqa: E402
 from paper_2512_14481_amd import workloads as wl       # noqa: E402
 
 INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8, published
+F16_MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense fp16 / bf16, published
 # HBM-side bytes per sasq_static_linear call (both kernels), averaged over gate/up/down of config 3:
 # rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a plain 1 GiB copy), see
 # profiles/bench_c3_mlp7b_counters.txt.  Algorithmic bytes are 221.2 MB.
@@ -57,6 +58,11 @@ class Projection:
         self.s_w = torch.empty(self.N, dtype=torch.float32, device="cuda")
         B.sasq_quantize_weight(w, self.wq, self.s_w, wf)
         del w
+        # the dequantized weight for the backward GEMM, prepared once from the row-major codes
+        self.wt_bwd = None
+        if self.N % 32 == 0:
+            self.wt_bwd = torch.empty(B.sasq_bwd_weight_bytes(self.N, self.K), dtype=torch.uint8, device="cuda")
+            B.sasq_prepare_bwd_weight(self.wq, self.s_w, self.wt_bwd, self.N, self.K, wf, x.dtype)
         # frozen weights are re-arranged once at set-up into the GEMM's blocked format (SASQ_BENCH_ROWMAJOR=1
         # keeps the row-major interchange format instead)
         if self.K % 64 == 0 and not os.environ.get("SASQ_BENCH_ROWMAJOR"):
@@ -337,6 +343,37 @@ def main():
         dynamic["unit"] = "TOP/s"
         dynamic["note"] = "sasq_dynamic_linear vs sasq_static_linear, same tensors, warm repeat of 5 each"
 
+    # backward of the frozen linear w.r.t. its input (16-bit MFMA GEMM against the prepared dequantized
+    # weight): the step that produces each fake-quant operator's upstream gradient during scale training
+    bwd_lin = None
+    if cfg.name == "c3_mlp7b":
+        bwd_lin = {}
+        tot_flops, tot_ms = 0.0, 0.0
+        gen = torch.Generator(device="cuda").manual_seed(cfg.seed + 11)
+        for p in projs:
+            if p.wt_bwd is None:
+                continue
+            dy_out = (torch.randn((p.M, p.N), device="cuda", generator=gen) * 0.01).to(p.x.dtype)
+            dx_lin = torch.empty_like(p.x)
+            for _ in range(2):
+                B.sasq_linear_bwd_input(dy_out, p.wt_bwd, dx_lin, p.K)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                B.sasq_linear_bwd_input(dy_out, p.wt_bwd, dx_lin, p.K)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 5
+            bwd_lin[p.name] = {"us": round(1e3 * ms, 1), "tflops": round(p.ops / (ms * 1e-3) / 1e12, 1)}
+            tot_ms += ms
+            tot_flops += p.ops
+            del dy_out, dx_lin
+        bwd_lin["achieved"] = round(tot_flops / (tot_ms * 1e-3) / 1e12, 1)
+        bwd_lin["peak"] = F16_MFMA_PEAK_TFLOPS
+        bwd_lin["unit"] = "TFLOP/s"
+        bwd_lin["frac"] = round(bwd_lin["achieved"] / F16_MFMA_PEAK_TFLOPS, 4)
+        bwd_lin["note"] = f"sasq_linear_bwd_input, {cfg.dtype} MFMA with fp32 accumulation, warm repeat of 5 per projection"
+
     out = {
         "metric": "static-scale W8A8 linear TOPS (% int8 MFMA peak); fake-quant fwd+bwd GB/s",
         "value": round(total_ops / (ms_per_step * 1e-3) / 1e12, 2),
@@ -370,6 +407,7 @@ def main():
         "fakequant_per_channel": pc,
         "static_linear_grouped": grouped,
         "dynamic_linear": dynamic,
+        "linear_bwd_input": bwd_lin,
     }
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, a.cpu_rows)

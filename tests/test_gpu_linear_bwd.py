@@ -40,16 +40,19 @@ def prepare(wq, s_w, fmt, dtype):
     return wt, K
 
 
-def run_bwd(dyb, wt, K, dtype, tile=None):
+def run_bwd(dyb, wt, K, dtype, tile=None, want_acc=False):
     if tile is None:
         os.environ.pop("SASQ_LINEAR_BWD_TILE", None)
     else:
         os.environ["SASQ_LINEAR_BWD_TILE"] = tile
     M = dyb.shape[0]
     dx = torch.empty((M, K), dtype=TDT[dtype], device="cuda")
-    B.sasq_linear_bwd_input(to_dev(dyb, dtype), wt, dx, K)
+    acc = torch.empty((M, K), dtype=torch.float32, device="cuda") if want_acc else None
+    B.sasq_linear_bwd_input(to_dev(dyb, dtype), wt, dx, K, acc)
     torch.cuda.synchronize()
     os.environ.pop("SASQ_LINEAR_BWD_TILE", None)
+    if want_acc:
+        return to_bits(dx), acc.cpu().numpy()
     return to_bits(dx)
 
 
@@ -104,8 +107,14 @@ def test_linear_bwd_matches_oracle(shape, dtype, fmt, tile):
     dyb, wq, s_w = problem(82, shape, dtype, fmt)
     wt, K = prepare(wq, s_w, fmt, dtype)
     ref = oracle.linear_bwd_input(dyb, wq, s_w, fmt, dtype)
-    got = run_bwd(dyb, wt, K, dtype, tile)
+    got, acc = run_bwd(dyb, wt, K, dtype, tile, want_acc=True)
     check_dx(got, ref, dtype, shape[1], f"{shape} {dtype} {fmt} tile {tile}")
+    # the fp32 sums before the 16-bit rounding: N fp32 additions in any order
+    err = np.abs(acc.astype(np.float64) - ref["exact"])
+    assert (err <= shape[1] * 2.0 ** -24 * ref["sum_abs"] + 1e-45).all(), err.max()
+    # and dX is the rounding of exactly those sums
+    assert np.array_equal(got, wl.f32_to_storage_bits(acc, dtype))
+    assert np.array_equal(run_bwd(dyb, wt, K, dtype, tile), got)          # same without the inspection output
 
 
 def test_linear_bwd_exact_on_small_integers():
