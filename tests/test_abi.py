@@ -134,6 +134,22 @@ def test_host_side_validation(lib):
     assert lib.sasq_packed_weight_bytes(i64(33), i64(128), 3) == 64 * 64
     assert lib.sasq_packed_weight_bytes(i64(17), i64(100), 2) == 0
     assert lib.sasq_packed_weight_bytes(i64(17), i64(128), 0) == 0
+    lib.sasq_bwd_weight_bytes.restype = ctypes.c_size_t
+    assert lib.sasq_bwd_weight_bytes(i64(64), i64(17)) == 32 * 64 * 2          # K rows padded to 16
+    assert lib.sasq_bwd_weight_bytes(i64(48), i64(16)) == 0                    # N % 32
+    pb = lib.sasq_prepare_bwd_weight
+    assert pb(None, good, good, i64(32), i64(16), 0, 0, None) == 1
+    assert pb(good, good, good, i64(48), i64(16), 0, 0, None) == 2
+    assert pb(good, good, good, i64(32), i64(15), 1, 0, None) == 2             # packed int4 needs even K
+    assert pb(good, good, good, i64(32), i64(16), 2, 0, None) == 4             # row-major codes only
+    assert pb(good, good, good, i64(32), i64(16), 0, 5, None) == 4
+    assert pb(good, good, odd, i64(32), i64(16), 0, 0, None) == 3
+    bl = lib.sasq_linear_bwd_input
+    assert bl(good, good, None, None, i64(4), i64(32), i64(16), 0, None) == 1
+    assert bl(good, good, good, None, i64(0), i64(32), i64(16), 0, None) == 2
+    assert bl(good, good, good, None, i64(4), i64(40), i64(16), 0, None) == 2
+    assert bl(good, good, good, None, i64(4), i64(32), i64(16), 3, None) == 4
+    assert bl(odd, good, good, None, i64(4), i64(32), i64(16), 0, None) == 3
     am = lib.sasq_absmax_scale
     assert am(good, None, i64(4), i64(4), 8, 0, good, big, None) == 1
     assert am(good, good, i64(4), i64(4), 8, 0, None, ctypes.c_size_t(0), None) == 5
