@@ -69,6 +69,7 @@ template <int DT> struct Store16;
 // to half" into v_fma_mixlo_f16, which rounds the exact product once; the contract (and the plain
 // two-step code) rounds to fp32 first, and the two differ when the fp32 product lands on a
 // half-precision tie.
+// (The paired conversion in pack() compiles to v_cvt_pk_f16_f32, which has no fused form.)
 __device__ __forceinline__ float rounded_f32(float f)
 {
     asm("" : "+v"(f));
