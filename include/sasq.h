@@ -320,12 +320,12 @@ int sasq_pack_weight(const void* wq, void* packed, int64_t N, int64_t K, sasq_wf
  *
  * sasq_prepare_bwd_weight writes Wq transposed and cut into the GEMM's operand blocks:
  *   B[k][n] = Wq[n][k]; 1 KB blocks of 16 rows (k) x 32 columns (n), block (k/16, n/32) at
- *   ((k/16) * N/32 + n/32) * 1024; inside, the 16-byte chunk c (8 columns) of row r at
- *   16 * (4r + (c ^ ((r >> 1) & 3) ^ ((r >> 3) & 1))).  Rows past K in the last block are zero.
+ *   ((k/16) * ceil(N/32) + n/32) * 1024; inside, the 16-byte chunk c (8 columns) of row r at
+ *   16 * (4r + (c ^ ((r >> 1) & 3) ^ ((r >> 3) & 1))).  Rows past K and columns past N are zero.
  *   wq       device, row-major codes [N,K], SASQ_W_INT8 or SASQ_W_INT4_PACKED
  *   s_w      device, N floats
  *   wt       device, sasq_bwd_weight_bytes(N, K) bytes, 16-byte aligned, written
- *   N        multiple of 32 (SASQ_ERR_SHAPE otherwise; sasq_bwd_weight_bytes then returns 0)
+ *   N        any; the MFMA kernel runs when N is a multiple of 32, a scalar kernel otherwise
  * sasq_linear_bwd_input:
  *   dy       device, [M,N] row-major 16-bit, 16-byte aligned, read only
  *   wt       device, as prepared for the same N, K and dt

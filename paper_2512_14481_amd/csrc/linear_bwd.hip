@@ -17,26 +17,34 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kBwdCols = kBK / 2;                  // contraction elements per stage row (16-bit)
 
-// Prepared weight layout: the matrix B[k][n] = Wq[n][k] (K rows, N 16-bit columns, N % 32 == 0)
-// cut into 1 KB blocks of 16 rows x 32 columns, block (kb, nb) at (kb * N/32 + nb) * 1024, the
-// 16-byte chunk c (8 columns) of row r at 16 * (4r + (c ^ swz64(r))): what one wave's direct
-// load deposits in an LDS stage.  Rows past K in the last block are zero.
+// Prepared weight layout: the matrix B[k][n] = Wq[n][k] (K rows, N 16-bit columns; rows padded
+// to a multiple of 16 and columns to a multiple of 32 with zeros) cut into 1 KB blocks of 16 rows
+// x 32 columns, block (kb, nb) at (kb * Npad/32 + nb) * 1024, the 16-byte chunk c (8 columns) of
+// row r at 16 * (4r + (c ^ swz64(r))): what one wave's direct load deposits in an LDS stage.
 // One thread per chunk; consecutive lanes take consecutive k so the byte reads of W rows coalesce.
+__device__ __forceinline__ int64_t bwd_weight_offset(int64_t k, int64_t n, int64_t Npad)
+{
+    const int r = (int)(k & 15), c = (int)((n >> 3) & 3);
+    return ((k >> 4) * (Npad / kBwdCols) + (n >> 5)) * 1024 + ((4 * r + (c ^ swz64(r))) << 4) + ((n & 7) << 1);
+}
+
 template <int DT, bool INT4>
 __global__ __launch_bounds__(256) void prepare_bwd_weight_kernel(
     const uint8_t* __restrict__ wq, const float* __restrict__ s_w, uint8_t* __restrict__ out,
-    int64_t N, int64_t K, int64_t Kpad)
+    int64_t N, int64_t K, int64_t Npad, int64_t Kpad)
 {
     using S = Store16<DT>;
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t k = t % Kpad, nc = t / Kpad;     // nc: chunk of 8 contraction columns
-    if (nc >= N / 8) return;
+    if (nc >= Npad / 8) return;
     uint32_t o[4] = {0u, 0u, 0u, 0u};
     if (k < K) {
         uint16_t h[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int64_t n = nc * 8 + e;
+            h[e] = 0;
+            if (n >= N) continue;
             int w;
             if (INT4) {
                 const uint32_t byte = wq[n * (K / 2) + k / 2];
@@ -50,10 +58,27 @@ __global__ __launch_bounds__(256) void prepare_bwd_weight_kernel(
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[e] = (uint32_t)h[2 * e] | ((uint32_t)h[2 * e + 1] << 16);
     }
-    const int64_t kb = k >> 4, nb = nc >> 2;
-    const int r = (int)(k & 15), c = (int)(nc & 3);
-    const int64_t off = (kb * (N / kBwdCols) + nb) * 1024 + ((4 * r + (c ^ swz64(r))) << 4);
-    *reinterpret_cast<u32x4*>(out + off) = u32x4{o[0], o[1], o[2], o[3]};
+    *reinterpret_cast<u32x4*>(out + bwd_weight_offset(k, nc * 8, Npad)) = u32x4{o[0], o[1], o[2], o[3]};
+}
+
+// Any-shape fallback (contraction length not a multiple of 32, or unaligned rows): one thread per
+// output, fp32 accumulation in ascending n.
+template <int DT>
+__global__ __launch_bounds__(256) void linear_bwd_scalar_kernel(
+    const uint16_t* __restrict__ dy, const uint8_t* __restrict__ wt, uint16_t* __restrict__ dx,
+    float* __restrict__ acc_out, int64_t M, int64_t N, int64_t K, int64_t Npad)
+{
+    using S = Store16<DT>;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= M * K) return;
+    const int64_t m = idx / K, k = idx - m * K;
+    float acc = 0.0f;
+    for (int64_t n = 0; n < N; ++n) {
+        const float w = S::one(*reinterpret_cast<const uint16_t*>(wt + bwd_weight_offset(k, n, Npad)));
+        acc = acc + S::one(dy[m * N + n]) * w;
+    }
+    if (acc_out) acc_out[idx] = acc;
+    dx[idx] = S::enc(acc);
 }
 
 template <int DT> struct Mfma16;
@@ -289,6 +314,8 @@ static bool bwd_small_tiles(int64_t M, int64_t K)
 }
 
 static int64_t bwd_kpad(int64_t K) { return (K + 15) / 16 * 16; }
+static int64_t bwd_npad(int64_t N) { return (N + kBwdCols - 1) / kBwdCols * kBwdCols; }
+constexpr int64_t kBwdMaxProduct = INT64_C(1) << 40;    // elements of any operand or of the output
 
 }  // namespace sasq
 
@@ -296,33 +323,33 @@ using namespace sasq;
 
 extern "C" size_t sasq_bwd_weight_bytes(int64_t N, int64_t K)
 {
-    if (N <= 0 || K <= 0 || (N % kBwdCols)) return 0;
-    return (size_t)bwd_kpad(K) * (size_t)N * 2;
+    if (N <= 0 || K <= 0 || N > 0x3FFFFFFF || K > 0x7FFFFFFF || N > kBwdMaxProduct / K) return 0;
+    return (size_t)bwd_kpad(K) * (size_t)bwd_npad(N) * 2;
 }
 
 extern "C" int sasq_prepare_bwd_weight(const void* wq, const float* s_w, void* wt, int64_t N, int64_t K,
                                        sasq_wfmt wf, sasq_dtype dt, void* stream)
 {
     if (!wq || !s_w || !wt) return SASQ_ERR_NULL;
-    if (N <= 0 || K <= 0 || (N % kBwdCols) || N > 0x7FFFFFFF || K > 0x7FFFFFFF) return SASQ_ERR_SHAPE;
+    if (N <= 0 || K <= 0 || N > 0x3FFFFFFF || K > 0x7FFFFFFF || N > kBwdMaxProduct / K) return SASQ_ERR_SHAPE;
     if (wf != SASQ_W_INT8 && wf != SASQ_W_INT4_PACKED) return SASQ_ERR_UNSUPPORTED;
     if (wf == SASQ_W_INT4_PACKED && (K & 1)) return SASQ_ERR_SHAPE;
     if (dt != SASQ_F16 && dt != SASQ_BF16) return SASQ_ERR_UNSUPPORTED;
     if (!aligned16(wt)) return SASQ_ERR_ALIGN;
     hipStream_t st = as_stream(stream);
-    const int64_t Kpad = bwd_kpad(K);
-    const int64_t threads = Kpad * (N / 8);
+    const int64_t Kpad = bwd_kpad(K), Npad = bwd_npad(N);
+    const int64_t threads = Kpad * (Npad / 8);
     const int64_t grid = (threads + 255) / 256;
     if (grid > 0x7FFFFFFF) return SASQ_ERR_SHAPE;
     const auto* W = static_cast<const uint8_t*>(wq);
     auto* O = static_cast<uint8_t*>(wt);
     const bool i4 = wf == SASQ_W_INT4_PACKED;
     if (dt == SASQ_F16) {
-        if (i4) prepare_bwd_weight_kernel<SASQ_F16, true><<<(int)grid, 256, 0, st>>>(W, s_w, O, N, K, Kpad);
-        else    prepare_bwd_weight_kernel<SASQ_F16, false><<<(int)grid, 256, 0, st>>>(W, s_w, O, N, K, Kpad);
+        if (i4) prepare_bwd_weight_kernel<SASQ_F16, true><<<(int)grid, 256, 0, st>>>(W, s_w, O, N, K, Npad, Kpad);
+        else    prepare_bwd_weight_kernel<SASQ_F16, false><<<(int)grid, 256, 0, st>>>(W, s_w, O, N, K, Npad, Kpad);
     } else {
-        if (i4) prepare_bwd_weight_kernel<SASQ_BF16, true><<<(int)grid, 256, 0, st>>>(W, s_w, O, N, K, Kpad);
-        else    prepare_bwd_weight_kernel<SASQ_BF16, false><<<(int)grid, 256, 0, st>>>(W, s_w, O, N, K, Kpad);
+        if (i4) prepare_bwd_weight_kernel<SASQ_BF16, true><<<(int)grid, 256, 0, st>>>(W, s_w, O, N, K, Npad, Kpad);
+        else    prepare_bwd_weight_kernel<SASQ_BF16, false><<<(int)grid, 256, 0, st>>>(W, s_w, O, N, K, Npad, Kpad);
     }
     return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
 }
@@ -331,11 +358,23 @@ extern "C" int sasq_linear_bwd_input(const void* dy, const void* wt, void* dx, f
                                      int64_t M, int64_t N, int64_t K, sasq_dtype dt, void* stream)
 {
     if (!dy || !wt || !dx) return SASQ_ERR_NULL;
-    if (M <= 0 || N <= 0 || K <= 0 || (N % kBwdCols)) return SASQ_ERR_SHAPE;
+    if (M <= 0 || N <= 0 || K <= 0) return SASQ_ERR_SHAPE;
     if (M > 0x7FFFFFFF || N > 0x3FFFFFFF || K > 0x7FFFFFFF) return SASQ_ERR_SHAPE;
+    if (M > kBwdMaxProduct / N || M > kBwdMaxProduct / K || N > kBwdMaxProduct / K) return SASQ_ERR_SHAPE;
     if (dt != SASQ_F16 && dt != SASQ_BF16) return SASQ_ERR_UNSUPPORTED;
     if (!aligned16(dy) || !aligned16(wt) || !aligned16(dx)) return SASQ_ERR_ALIGN;
     hipStream_t st = as_stream(stream);
+    if (N % kBwdCols) {
+        // rows of dY are not whole 64-byte stage rows: scalar kernel
+        const int64_t grid = (M * K + 255) / 256;
+        if (grid > 0x7FFFFFFF) return SASQ_ERR_SHAPE;
+        auto* DY = static_cast<const uint16_t*>(dy);
+        auto* WT = static_cast<const uint8_t*>(wt);
+        auto* DX = static_cast<uint16_t*>(dx);
+        if (dt == SASQ_F16) linear_bwd_scalar_kernel<SASQ_F16><<<(int)grid, 256, 0, st>>>(DY, WT, DX, acc_out, M, N, K, bwd_npad(N));
+        else                linear_bwd_scalar_kernel<SASQ_BF16><<<(int)grid, 256, 0, st>>>(DY, WT, DX, acc_out, M, N, K, bwd_npad(N));
+        return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+    }
     const bool small = bwd_small_tiles(M, K);
     if (dt == SASQ_F16) {
         if (small) launch_bwd<SASQ_F16, 128, 128>(dy, wt, dx, acc_out, M, N, K, st);

@@ -136,10 +136,11 @@ def test_host_side_validation(lib):
     assert lib.sasq_packed_weight_bytes(i64(17), i64(128), 0) == 0
     lib.sasq_bwd_weight_bytes.restype = ctypes.c_size_t
     assert lib.sasq_bwd_weight_bytes(i64(64), i64(17)) == 32 * 64 * 2          # K rows padded to 16
-    assert lib.sasq_bwd_weight_bytes(i64(48), i64(16)) == 0                    # N % 32
+    assert lib.sasq_bwd_weight_bytes(i64(48), i64(16)) == 16 * 64 * 2          # N columns padded to 32
+    assert lib.sasq_bwd_weight_bytes(i64(1 << 30), i64(16)) == 0
     pb = lib.sasq_prepare_bwd_weight
     assert pb(None, good, good, i64(32), i64(16), 0, 0, None) == 1
-    assert pb(good, good, good, i64(48), i64(16), 0, 0, None) == 2
+    assert pb(good, good, good, i64(1 << 30), i64(16), 0, 0, None) == 2
     assert pb(good, good, good, i64(32), i64(15), 1, 0, None) == 2             # packed int4 needs even K
     assert pb(good, good, good, i64(32), i64(16), 2, 0, None) == 4             # row-major codes only
     assert pb(good, good, good, i64(32), i64(16), 0, 5, None) == 4
@@ -147,7 +148,8 @@ def test_host_side_validation(lib):
     bl = lib.sasq_linear_bwd_input
     assert bl(good, good, None, None, i64(4), i64(32), i64(16), 0, None) == 1
     assert bl(good, good, good, None, i64(0), i64(32), i64(16), 0, None) == 2
-    assert bl(good, good, good, None, i64(4), i64(40), i64(16), 0, None) == 2
+    assert bl(good, good, good, None, i64(4), i64(1 << 30), i64(16), 0, None) == 2
+    assert bl(good, good, good, None, i64(1 << 21), i64(1 << 20), i64(16), 0, None) == 2
     assert bl(good, good, good, None, i64(4), i64(32), i64(16), 3, None) == 4
     assert bl(odd, good, good, None, i64(4), i64(32), i64(16), 0, None) == 3
     am = lib.sasq_absmax_scale
