@@ -283,7 +283,28 @@ def main():
             tot_b += p.fq_bytes
         pc = {"achieved": round(tot_b / (tot_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
               "frac": round(tot_b / (tot_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-              "note": "per-channel fwd+bwd on x_mlp and x_down, warm repeat of 5"}
+              "note": "per-channel fwd+bwd on x_mlp and x_down, one launch per tensor, warm repeat of 5"}
+        # the same for all three projection inputs of the layer in one launch each way
+        svs = [p.s.expand(p.K).contiguous() for p in projs]
+        dsvs = [torch.zeros(p.K, dtype=torch.float32, device="cuda") for p in projs]
+        fwd_items = [(p.x, svs[i], p.xhat) for i, p in enumerate(projs)]
+        bwd_items = [(p.x, p.dy, svs[i], p.dx, dsvs[i]) for i, p in enumerate(projs)]
+        wsb = B.new_workspace(B.sasq_fakequant_bwd_pc_batch_workspace(bwd_items))
+        for _ in range(2):
+            B.sasq_fakequant_fwd_pc_batch(fwd_items, 8)
+            B.sasq_fakequant_bwd_pc_batch(bwd_items, wsb, 8)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            B.sasq_fakequant_fwd_pc_batch(fwd_items, 8)
+            B.sasq_fakequant_bwd_pc_batch(bwd_items, wsb, 8)
+        e1.record()
+        torch.cuda.synchronize()
+        bms = e0.elapsed_time(e1) / 5
+        bb = sum(p.fq_bytes for p in projs)
+        pc["batched"] = {"achieved": round(bb / (bms * 1e-3) / 1e9, 1), "unit": "GB/s",
+                         "frac": round(bb / (bms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                         "note": "sasq_fakequant_fwd_pc_batch + sasq_fakequant_bwd_pc_batch over the three projection inputs"}
 
     # static linear with one activation factor per group of 128 / 512 input channels (the grouped form
     # the paper gives for per-channel activation factors), measured after the timed region

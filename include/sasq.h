@@ -156,6 +156,21 @@ size_t sasq_fakequant_bwd_batch_workspace(int count);
 int sasq_fakequant_bwd_batch(const sasq_fq_item* items, int count, int bits, sasq_dtype dt,
                              void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * The same for per-channel factors (one factor per activation column, Sec. 4; Fig. 2(b)): each
+ * item is a sasq_fakequant_fwd_pc / sasq_fakequant_bwd_pc call, `s` and `ds` pointing at `cols`
+ * floats.  Outputs are bit-identical to the single-tensor calls (the column reduction of an item
+ * does not depend on the batch).  Every item needs cols % 8 == 0 (SASQ_ERR_SHAPE otherwise: such
+ * tensors take the single-tensor call), and the items of one backward call at most 256 column
+ * blocks of 512 columns in all (SASQ_ERR_SHAPE; the workspace query then returns 0).
+ *   workspace (backward)  >= sasq_fakequant_bwd_pc_batch_workspace(items, count) bytes, initialised
+ *           once with sasq_workspace_init.
+ */
+int sasq_fakequant_fwd_pc_batch(const sasq_fq_item* items, int count, int bits, sasq_dtype dt, void* stream);
+size_t sasq_fakequant_bwd_pc_batch_workspace(const sasq_fq_item* items, int count);
+int sasq_fakequant_bwd_pc_batch(const sasq_fq_item* items, int count, int bits, sasq_dtype dt,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
 /* SGD step of sasq_scale_sgd on a vector of n scales (the scales of one layer in one launch). */
 int sasq_scale_sgd_vec(float* s, const float* ds, int64_t n, float lr, void* stream);
 

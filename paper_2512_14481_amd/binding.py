@@ -67,6 +67,10 @@ def _lib() -> ctypes.CDLL:
         L.sasq_fakequant_bwd_batch_workspace.restype = sz
         L.sasq_fakequant_bwd_batch_workspace.argtypes = [i32]
         L.sasq_fakequant_bwd_batch.argtypes = [ctypes.POINTER(_FqItem), i32, i32, i32, vp, sz, vp]
+        L.sasq_fakequant_fwd_pc_batch.argtypes = [ctypes.POINTER(_FqItem), i32, i32, i32, vp]
+        L.sasq_fakequant_bwd_pc_batch_workspace.restype = sz
+        L.sasq_fakequant_bwd_pc_batch_workspace.argtypes = [ctypes.POINTER(_FqItem), i32]
+        L.sasq_fakequant_bwd_pc_batch.argtypes = [ctypes.POINTER(_FqItem), i32, i32, i32, vp, sz, vp]
         L.sasq_scale_adamw.argtypes = [vp, vp, vp, vp, i64, i64] + [ctypes.c_double] * 5 + [vp]
         L.sasq_fakequant_fwd_pc.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp]
         L.sasq_fakequant_bwd_pc_workspace.restype = sz
@@ -237,6 +241,35 @@ def sasq_fakequant_bwd_batch(items, workspace: torch.Tensor, bits: int = 8) -> N
     _check(_lib().sasq_fakequant_bwd_batch(arr, len(items), bits, dt, _ptr(workspace),
                                            workspace.numel() * workspace.element_size(), _stream()),
            "sasq_fakequant_bwd_batch")
+
+
+def _pc_check(items, backward: bool) -> None:
+    for it in items:
+        x, s = it[0], (it[2] if backward else it[1])
+        if s.numel() != x.shape[1] or (backward and it[4].numel() != x.shape[1]):
+            raise ValueError("per-channel s and ds hold one element per column of x")
+
+
+def sasq_fakequant_fwd_pc_batch(items, bits: int = 8) -> None:
+    """items: sequence of (x, s[cols], y)."""
+    _pc_check(items, False)
+    arr, dt = _fq_items(items, False)
+    _check(_lib().sasq_fakequant_fwd_pc_batch(arr, len(items), bits, dt, _stream()), "sasq_fakequant_fwd_pc_batch")
+
+
+def sasq_fakequant_bwd_pc_batch_workspace(items) -> int:
+    """items as for sasq_fakequant_bwd_pc_batch (only the shapes are read)."""
+    arr, _ = _fq_items(items, True)
+    return int(_lib().sasq_fakequant_bwd_pc_batch_workspace(arr, len(items)))
+
+
+def sasq_fakequant_bwd_pc_batch(items, workspace: torch.Tensor, bits: int = 8) -> None:
+    """items: sequence of (x, dy, s[cols], dx_or_None, ds[cols])."""
+    _pc_check(items, True)
+    arr, dt = _fq_items(items, True)
+    _check(_lib().sasq_fakequant_bwd_pc_batch(arr, len(items), bits, dt, _ptr(workspace),
+                                              workspace.numel() * workspace.element_size(), _stream()),
+           "sasq_fakequant_bwd_pc_batch")
 
 
 def sasq_scale_sgd_vec(s: torch.Tensor, ds: torch.Tensor, lr: float) -> None:

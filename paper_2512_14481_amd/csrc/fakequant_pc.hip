@@ -9,6 +9,7 @@
 // row (1 KB, fully coalesced); the 4 waves of a block take rows r, r+1, r+2, r+3 of the block's
 // row chunk.  Grid = column chunks x row chunks.
 #include "sasq_device.h"
+#include <cstring>
 
 namespace sasq {
 
@@ -47,16 +48,19 @@ __device__ __forceinline__ QElem quantize_pc(float x, float inv_s, const PcConst
     return e;
 }
 
+// The block (col_block, row_chunk) of one tensor's grid: the kernels below pass their block
+// indices, or (batched) the position inside the tensor's run of blocks.
 template <int DT, bool CODES>
-__global__ __launch_bounds__(kPcThreads) void fakequant_fwd_pc_kernel(
+__device__ __forceinline__ void fwd_pc_body(
     const uint16_t* __restrict__ x, const float* __restrict__ s, uint16_t* __restrict__ y,
-    int8_t* __restrict__ codes, int64_t rows, int64_t cols, int64_t rows_per_chunk, int bits)
+    int8_t* __restrict__ codes, int64_t rows, int64_t cols, int64_t rows_per_chunk, int bits,
+    int col_block, int row_chunk)
 {
     using S = Store16<DT>;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t col0 = (int64_t)blockIdx.x * kPcColsPerBlock + lane * 8;
+    const int64_t col0 = (int64_t)col_block * kPcColsPerBlock + lane * 8;
     if (col0 >= cols) return;
-    const int64_t r_begin = (int64_t)blockIdx.y * rows_per_chunk;
+    const int64_t r_begin = (int64_t)row_chunk * rows_per_chunk;
     const int64_t r_end = min(rows, r_begin + rows_per_chunk);
     // Groups of kPcRowUnroll rows per wave, double-buffered: the next group's loads are in flight
     // while the current one is computed, and the first group's loads are issued before the
@@ -111,22 +115,29 @@ __global__ __launch_bounds__(kPcThreads) void fakequant_fwd_pc_kernel(
         one_row(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(x + r * cols + col0)), r);
 }
 
+template <int DT, bool CODES>
+__global__ __launch_bounds__(kPcThreads) void fakequant_fwd_pc_kernel(
+    const uint16_t* __restrict__ x, const float* __restrict__ s, uint16_t* __restrict__ y,
+    int8_t* __restrict__ codes, int64_t rows, int64_t cols, int64_t rows_per_chunk, int bits)
+{
+    fwd_pc_body<DT, CODES>(x, s, y, codes, rows, cols, rows_per_chunk, bits, (int)blockIdx.x, (int)blockIdx.y);
+}
+
 template <int DT, bool WRITE_DX>
-__global__ __launch_bounds__(kPcThreads) void fakequant_bwd_pc_kernel(
+__device__ __forceinline__ void bwd_pc_body(
     const uint16_t* __restrict__ x, const uint16_t* dy, const float* __restrict__ s,
     uint16_t* dx, float* __restrict__ ds, uint32_t* __restrict__ tickets, float* __restrict__ partials,
-    int64_t rows, int64_t cols, int64_t rows_per_chunk, int bits)
+    int64_t rows, int64_t cols, int64_t rows_per_chunk, int bits,
+    int col_block, int row_chunk, int nchunks, float (&red)[kPcWaves][kPcColsPerBlock], bool& is_last)
 {
     using S = Store16<DT>;
-    __shared__ float red[kPcWaves][kPcColsPerBlock];
-    __shared__ bool is_last;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t cbase = (int64_t)blockIdx.x * kPcColsPerBlock;
+    const int64_t cbase = (int64_t)col_block * kPcColsPerBlock;
     const int64_t col0 = cbase + lane * 8;
     const bool active = col0 < cols;
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (active) {
-        const int64_t r_begin = (int64_t)blockIdx.y * rows_per_chunk;
+        const int64_t r_begin = (int64_t)row_chunk * rows_per_chunk;
         const int64_t r_end = min(rows, r_begin + rows_per_chunk);
         // same double-buffered traversal as the forward kernel, two input streams
         constexpr int64_t kStep = kPcWaves * kPcRowUnroll;
@@ -183,7 +194,6 @@ __global__ __launch_bounds__(kPcThreads) void fakequant_bwd_pc_kernel(
 #pragma unroll
     for (int e = 0; e < 8; ++e) red[wave][lane * 8 + e] = acc[e];
     __syncthreads();
-    const int nchunks = gridDim.y;
     // One 128-bit store per 4 columns, with the agent-scope cache policy the compiler gives its own
     // agent-scope atomic stores (sc1): 4-byte stores of the same data are four times as many
     // write-through transactions, and every block waits for their acknowledgement below.
@@ -198,7 +208,7 @@ __global__ __launch_bounds__(kPcThreads) void fakequant_bwd_pc_kernel(
             v[e] = a;
         }
         if (cbase + c4 < cols) {        // cols is a multiple of 8: a group of 4 is all in or all out
-            float* dst = &partials[(int64_t)blockIdx.y * cols + cbase + c4];
+            float* dst = &partials[(int64_t)row_chunk * cols + cbase + c4];
             asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(dst), "v"(v) : "memory");
         }
     }
@@ -206,7 +216,7 @@ __global__ __launch_bounds__(kPcThreads) void fakequant_bwd_pc_kernel(
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
-        const uint32_t ticket = __hip_atomic_fetch_add(&tickets[blockIdx.x], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t ticket = __hip_atomic_fetch_add(&tickets[col_block], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         is_last = (ticket == (uint32_t)nchunks - 1);
         if (ticket >= (uint32_t)nchunks) ds[cbase < cols ? cbase : 0] = __uint_as_float(0x7FC00000u);   // uninitialised workspace
     }
@@ -243,7 +253,72 @@ __global__ __launch_bounds__(kPcThreads) void fakequant_bwd_pc_kernel(
         if (ok[0]) ds[colv[0]] = (float)t0;
         if (ok[1]) ds[colv[1]] = (float)t1;
     }
-    if (threadIdx.x == 0) __hip_atomic_store(&tickets[blockIdx.x], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x == 0) __hip_atomic_store(&tickets[col_block], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int DT, bool WRITE_DX>
+__global__ __launch_bounds__(kPcThreads) void fakequant_bwd_pc_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* dy, const float* __restrict__ s,
+    uint16_t* dx, float* __restrict__ ds, uint32_t* __restrict__ tickets, float* __restrict__ partials,
+    int64_t rows, int64_t cols, int64_t rows_per_chunk, int bits)
+{
+    __shared__ float red[kPcWaves][kPcColsPerBlock];
+    __shared__ bool is_last;
+    bwd_pc_body<DT, WRITE_DX>(x, dy, s, dx, ds, tickets, partials, rows, cols, rows_per_chunk, bits,
+                              (int)blockIdx.x, (int)blockIdx.y, (int)gridDim.y, red, is_last);
+}
+
+// ---- several tensors in one launch -------------------------------------------------------------
+// Each tensor owns a run of consecutive block ids, column block fastest (the order a 2-D grid
+// dispatches in); one launch for the fake-quant operators of a layer pays one ramp and one drain.
+struct PcItem {
+    const uint16_t* x;
+    const uint16_t* dy;
+    const float* s;
+    uint16_t* out;        // y (forward) or dx (backward, may be null)
+    float* ds;
+    uint32_t* tickets;
+    float* partials;
+    int64_t rows, cols, rpc;
+    int col_blocks, chunks;
+};
+struct PcBatch {
+    PcItem it[SASQ_MAX_BATCH];
+    int first_block[SASQ_MAX_BATCH + 1];
+    int count;
+};
+
+__device__ __forceinline__ int pc_item_of(const PcBatch& b, int bid)
+{
+    int k = 0;
+#pragma unroll
+    for (int i = 1; i < SASQ_MAX_BATCH; ++i)
+        if (i < b.count && bid >= b.first_block[i]) k = i;
+    return k;
+}
+
+template <int DT>
+__global__ __launch_bounds__(kPcThreads) void fakequant_fwd_pc_batch_kernel(const PcBatch b, int bits)
+{
+    const int k = pc_item_of(b, (int)blockIdx.x);
+    const PcItem& it = b.it[k];
+    const int lb = (int)blockIdx.x - b.first_block[k];
+    fwd_pc_body<DT, false>(it.x, it.s, it.out, nullptr, it.rows, it.cols, it.rpc, bits, lb % it.col_blocks, lb / it.col_blocks);
+}
+
+template <int DT>
+__global__ __launch_bounds__(kPcThreads) void fakequant_bwd_pc_batch_kernel(const PcBatch b, int bits)
+{
+    __shared__ float red[kPcWaves][kPcColsPerBlock];
+    __shared__ bool is_last;
+    const int k = pc_item_of(b, (int)blockIdx.x);
+    const PcItem& it = b.it[k];
+    const int lb = (int)blockIdx.x - b.first_block[k];
+    const int cb = lb % it.col_blocks, rc = lb / it.col_blocks;
+    if (it.out) bwd_pc_body<DT, true>(it.x, it.dy, it.s, it.out, it.ds, it.tickets, it.partials, it.rows, it.cols, it.rpc, bits,
+                                      cb, rc, it.chunks, red, is_last);
+    else        bwd_pc_body<DT, false>(it.x, it.dy, it.s, nullptr, it.ds, it.tickets, it.partials, it.rows, it.cols, it.rpc, bits,
+                                       cb, rc, it.chunks, red, is_last);
 }
 
 // cols not a multiple of 8: one thread per column walks the rows (rarely used, kept simple)
@@ -286,6 +361,15 @@ static int pc_row_chunks(int64_t rows, int64_t col_blocks)
     return (int)rc;
 }
 
+// rows per chunk: a multiple of 16 (whole unpredicated groups in every chunk but the last)
+static void pc_geometry(int64_t rows, int64_t cols, int64_t& col_blocks, int64_t& rpc, int& chunks)
+{
+    col_blocks = (cols + kPcColsPerBlock - 1) / kPcColsPerBlock;
+    const int want = pc_row_chunks(rows, col_blocks);
+    rpc = ((rows + want - 1) / want + 15) / 16 * 16;
+    chunks = (int)((rows + rpc - 1) / rpc);
+}
+
 static int check_pc(int64_t rows, int64_t cols, int bits, int dt)
 {
     if (rows <= 0 || cols <= 0) return SASQ_ERR_SHAPE;
@@ -316,10 +400,9 @@ extern "C" int sasq_fakequant_fwd_pc(const void* x, const float* s, void* y, int
         else                fakequant_pc_scalar_kernel<SASQ_BF16><<<blocks, 256, 0, st>>>(X, nullptr, s, Y, codes, nullptr, nullptr, rows, cols, bits, 0);
         return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
     }
-    const int64_t col_blocks = (cols + kPcColsPerBlock - 1) / kPcColsPerBlock;
-    // rows per chunk: a multiple of 16 (whole unpredicated groups in every chunk but the last)
-    const int64_t rpc = ((rows + pc_row_chunks(rows, col_blocks) - 1) / pc_row_chunks(rows, col_blocks) + 15) / 16 * 16;
-    const int chunks = (int)((rows + rpc - 1) / rpc);
+    int64_t col_blocks, rpc;
+    int chunks;
+    pc_geometry(rows, cols, col_blocks, rpc, chunks);
     dim3 grid((unsigned)col_blocks, (unsigned)chunks);
     if (dt == SASQ_F16) {
         if (codes) fakequant_fwd_pc_kernel<SASQ_F16, true><<<grid, kPcThreads, 0, st>>>(X, s, Y, codes, rows, cols, rpc, bits);
@@ -358,10 +441,9 @@ extern "C" int sasq_fakequant_bwd_pc(const void* x, const void* dy, const float*
     }
     if (!workspace || workspace_bytes < sasq_fakequant_bwd_pc_workspace(rows, cols)) return SASQ_ERR_WORKSPACE;
     if (!aligned16(workspace)) return SASQ_ERR_ALIGN;
-    const int64_t col_blocks = (cols + kPcColsPerBlock - 1) / kPcColsPerBlock;
-    // rows per chunk: a multiple of 16 (whole unpredicated groups in every chunk but the last)
-    const int64_t rpc = ((rows + pc_row_chunks(rows, col_blocks) - 1) / pc_row_chunks(rows, col_blocks) + 15) / 16 * 16;
-    const int chunks = (int)((rows + rpc - 1) / rpc);
+    int64_t col_blocks, rpc;
+    int chunks;
+    pc_geometry(rows, cols, col_blocks, rpc, chunks);
     dim3 grid((unsigned)col_blocks, (unsigned)chunks);
     auto tickets = static_cast<uint32_t*>(workspace);
     auto parts = reinterpret_cast<float*>(static_cast<char*>(workspace) + kWsHeaderBytes);
@@ -373,4 +455,140 @@ extern "C" int sasq_fakequant_bwd_pc(const void* x, const void* dy, const float*
         else    fakequant_bwd_pc_kernel<SASQ_BF16, false><<<grid, kPcThreads, 0, st>>>(X, G, s, DX, ds, tickets, parts, rows, cols, rpc, bits);
     }
     return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+// ---- batched entry points ----------------------------------------------------------------------
+namespace sasq {
+
+constexpr size_t kPcBatchLaunchBytes = (size_t)192 << 20;   // input bytes per launch: more concurrent streams run slower
+
+static int check_pc_items(const sasq_fq_item* items, int count, int bits, sasq_dtype dt, bool backward)
+{
+    if (!items) return SASQ_ERR_NULL;
+    if (count < 1 || count > SASQ_MAX_BATCH) return SASQ_ERR_SHAPE;
+    for (int i = 0; i < count; ++i) {
+        const sasq_fq_item& it = items[i];
+        if (!it.x || !it.s || (backward ? (!it.dy || !it.ds) : !it.out)) return SASQ_ERR_NULL;
+        int rc = check_pc(it.rows, it.cols, bits, (int)dt);
+        if (rc) return rc;
+        if (it.cols % 8) return SASQ_ERR_SHAPE;              // such tensors take the single-tensor call
+        if (!aligned16(it.x) || (it.out && !aligned16(it.out)) || (backward && !aligned16(it.dy))) return SASQ_ERR_ALIGN;
+    }
+    return SASQ_OK;
+}
+
+// Workspace of a batch: the 1 KB header holds the tickets of all items back to back (one word per
+// column block; sasq_workspace_init clears exactly that header), each item's partials follow.
+struct PcBatchLayout {
+    size_t ticket_word[SASQ_MAX_BATCH];
+    size_t partials_off[SASQ_MAX_BATCH];
+    size_t total;
+    bool fits;
+};
+
+static PcBatchLayout pc_batch_layout(const sasq_fq_item* items, int count)
+{
+    PcBatchLayout L;
+    size_t words = 0, off = kWsHeaderBytes;
+    for (int i = 0; i < count; ++i) {
+        L.ticket_word[i] = words;
+        L.partials_off[i] = off;
+        const int64_t cols = items[i].cols > 0 ? items[i].cols : 0;
+        words += (size_t)((cols + kPcColsPerBlock - 1) / kPcColsPerBlock);
+        off += sizeof(float) * (size_t)kPcMaxRowChunks * (size_t)cols;
+    }
+    L.total = off;
+    L.fits = words <= kWsHeaderBytes / 4;
+    return L;
+}
+
+// Launches items [i0, i1) as one grid.
+template <bool BACKWARD>
+static int launch_pc_batch(const sasq_fq_item* items, int i0, int i1, int bits, sasq_dtype dt, char* ws,
+                           const PcBatchLayout* L, hipStream_t st)
+{
+    PcBatch b;
+    memset(&b, 0, sizeof(b));
+    int64_t blocks = 0;
+    for (int i = i0; i < i1; ++i) {
+        const sasq_fq_item& src = items[i];
+        PcItem& it = b.it[i - i0];
+        int64_t col_blocks;
+        pc_geometry(src.rows, src.cols, col_blocks, it.rpc, it.chunks);
+        it.col_blocks = (int)col_blocks;
+        it.x = static_cast<const uint16_t*>(src.x);
+        it.dy = static_cast<const uint16_t*>(src.dy);
+        it.s = src.s;
+        it.out = static_cast<uint16_t*>(src.out);
+        it.ds = src.ds;
+        it.rows = src.rows;
+        it.cols = src.cols;
+        if (BACKWARD) {
+            it.tickets = reinterpret_cast<uint32_t*>(ws) + L->ticket_word[i];
+            it.partials = reinterpret_cast<float*>(ws + L->partials_off[i]);
+        }
+        b.first_block[i - i0] = (int)blocks;
+        blocks += col_blocks * it.chunks;
+        if (blocks > 0x7FFFFFFF) return SASQ_ERR_SHAPE;
+    }
+    b.count = i1 - i0;
+    b.first_block[b.count] = (int)blocks;
+    if (BACKWARD) {
+        if (dt == SASQ_F16) fakequant_bwd_pc_batch_kernel<SASQ_F16><<<(int)blocks, kPcThreads, 0, st>>>(b, bits);
+        else                fakequant_bwd_pc_batch_kernel<SASQ_BF16><<<(int)blocks, kPcThreads, 0, st>>>(b, bits);
+    } else {
+        if (dt == SASQ_F16) fakequant_fwd_pc_batch_kernel<SASQ_F16><<<(int)blocks, kPcThreads, 0, st>>>(b, bits);
+        else                fakequant_fwd_pc_batch_kernel<SASQ_BF16><<<(int)blocks, kPcThreads, 0, st>>>(b, bits);
+    }
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+template <bool BACKWARD>
+static int run_pc_batch(const sasq_fq_item* items, int count, int bits, sasq_dtype dt, char* ws, const PcBatchLayout* L,
+                        hipStream_t st)
+{
+    // consecutive items share a launch while their input stays under the per-launch cap
+    int i0 = 0;
+    while (i0 < count) {
+        size_t bytes = 0;
+        int i1 = i0;
+        while (i1 < count) {
+            const size_t add = (size_t)items[i1].rows * (size_t)items[i1].cols * (BACKWARD ? 4 : 2);
+            if (i1 > i0 && bytes + add > kPcBatchLaunchBytes) break;
+            bytes += add;
+            ++i1;
+        }
+        int rc = launch_pc_batch<BACKWARD>(items, i0, i1, bits, dt, ws, L, st);
+        if (rc) return rc;
+        i0 = i1;
+    }
+    return SASQ_OK;
+}
+
+}  // namespace sasq
+
+extern "C" int sasq_fakequant_fwd_pc_batch(const sasq_fq_item* items, int count, int bits, sasq_dtype dt, void* stream)
+{
+    int rc = check_pc_items(items, count, bits, dt, false);
+    if (rc) return rc;
+    return run_pc_batch<false>(items, count, bits, dt, nullptr, nullptr, as_stream(stream));
+}
+
+extern "C" size_t sasq_fakequant_bwd_pc_batch_workspace(const sasq_fq_item* items, int count)
+{
+    if (!items || count < 1 || count > SASQ_MAX_BATCH) return 0;
+    const PcBatchLayout L = pc_batch_layout(items, count);
+    return L.fits ? L.total : 0;
+}
+
+extern "C" int sasq_fakequant_bwd_pc_batch(const sasq_fq_item* items, int count, int bits, sasq_dtype dt,
+                                           void* workspace, size_t workspace_bytes, void* stream)
+{
+    int rc = check_pc_items(items, count, bits, dt, true);
+    if (rc) return rc;
+    const PcBatchLayout L = pc_batch_layout(items, count);
+    if (!L.fits) return SASQ_ERR_SHAPE;                      // more than 256 column blocks in all
+    if (!workspace || workspace_bytes < L.total) return SASQ_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SASQ_ERR_ALIGN;
+    return run_pc_batch<true>(items, count, bits, dt, static_cast<char*>(workspace), &L, as_stream(stream));
 }

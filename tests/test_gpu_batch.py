@@ -142,3 +142,84 @@ def test_linear_batch_rejects():
     assert call(0, 8, 0) == 2
     assert call(1, 9, 0) == 4
     assert call(1, 8, 5) == 4
+
+
+# ------------------------------------------------------------------ per-channel factors, batched
+PC_SHAPES = [(1, 8), (3, 16), (17, 40), (64, 256), (257, 1032), (512, 4096), (5, 8192), (300, 520)]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("count", [1, 3, 8])
+def test_pc_batch_matches_single_calls_and_oracle(dtype, count):
+    shapes = PC_SHAPES[:count]
+    xs = [wl.random_bits(85, f"px{sh}{dtype}", sh, dtype, gain=2.0) for sh in shapes]
+    dys = [wl.random_bits(85, f"pd{sh}{dtype}", sh, dtype, gain=1.0) for sh in shapes]
+    ss = [(np.abs(wl.random_f32(85, f"ps{sh}", (sh[1],), 0.02)) + np.float32(0.005)).astype(np.float32) for sh in shapes]
+    xd = [to_dev(x, dtype) for x in xs]
+    dyd = [to_dev(d, dtype) for d in dys]
+    sd = [torch.from_numpy(s).cuda() for s in ss]
+    yd = [torch.empty_like(x) for x in xd]
+    dxd = [torch.empty_like(x) if i != 1 else None for i, x in enumerate(xd)]      # one item without dx
+    dsd = [torch.full((sh[1],), float("nan"), dtype=torch.float32, device="cuda") for sh in shapes]
+    B.sasq_fakequant_fwd_pc_batch([(xd[i], sd[i], yd[i]) for i in range(count)], 8)
+    items = [(xd[i], dyd[i], sd[i], dxd[i], dsd[i]) for i in range(count)]
+    ws = B.new_workspace(B.sasq_fakequant_bwd_pc_batch_workspace(items))
+    B.sasq_fakequant_bwd_pc_batch(items, ws, 8)
+    ds1 = [d.cpu().numpy().copy() for d in dsd]
+    B.sasq_fakequant_bwd_pc_batch(items, ws, 8)                                    # same workspace, second call
+    torch.cuda.synchronize()
+    for i in range(count):
+        assert np.array_equal(dsd[i].cpu().numpy(), ds1[i]), "ds is deterministic and the tickets were reset"
+        # single-tensor calls: everything bit-identical (an item's reduction does not depend on the batch)
+        y1 = torch.empty_like(xd[i])
+        dx1 = torch.empty_like(xd[i])
+        ds_single = torch.empty_like(dsd[i])
+        ws1 = B.new_workspace(B.sasq_fakequant_bwd_pc_workspace(*shapes[i]))
+        B.sasq_fakequant_fwd_pc(xd[i], sd[i], y1, None, 8)
+        B.sasq_fakequant_bwd_pc(xd[i], dyd[i], sd[i], dx1, ds_single, ws1, 8)
+        torch.cuda.synchronize()
+        assert torch.equal(y1.view(torch.int16), yd[i].view(torch.int16)), i
+        if dxd[i] is not None:
+            assert torch.equal(dx1.view(torch.int16), dxd[i].view(torch.int16)), i
+        assert np.array_equal(ds_single.cpu().numpy(), ds1[i]), i
+        # and the oracle
+        y_ref, _ = oracle.fakequant_fwd_pc(xs[i], ss[i], 8, dtype)
+        ref = oracle.fakequant_bwd_pc(xs[i], dys[i], ss[i], 8, dtype)
+        assert np.array_equal(wl.storage_bits_to_f32(to_bits(yd[i]), dtype), wl.storage_bits_to_f32(y_ref, dtype)), i
+        if dxd[i] is not None:
+            assert np.array_equal(wl.storage_bits_to_f32(to_bits(dxd[i]), dtype), wl.storage_bits_to_f32(ref["dx"], dtype)), i
+        tol = 1e-4 * np.abs(ref["ds64"]) + 1e-6 * ref["sum_abs"] + 1e-30
+        assert (np.abs(ds1[i].astype(np.float64) - ref["ds64"]) <= tol).all(), i
+
+
+def test_pc_batch_errors_and_layer_sizes():
+    x = torch.zeros((4, 12), dtype=torch.float16, device="cuda")          # cols % 8 != 0
+    s = torch.ones(12, dtype=torch.float32, device="cuda")
+    arr, dt = B._fq_items([(x, s, x)], False)
+    assert B._lib().sasq_fakequant_fwd_pc_batch(arr, 1, 8, dt, None) == 2
+    assert B._lib().sasq_fakequant_fwd_pc_batch(arr, 0, 8, dt, None) == 2
+    # the four activation tensors of config 3 / a LLaMA-2-7B layer (x_qkv, x_o, x_mlp, x_down), batched,
+    # against the single-tensor calls
+    dtype = "f16"
+    shapes = [(2048, 4096)] * 3 + [(2048, 11008)]
+    g = torch.Generator(device="cuda").manual_seed(6)
+    xd = [(torch.randn(sh, device="cuda", generator=g) * 2).to(TDT[dtype]) for sh in shapes]
+    dyd = [torch.randn(sh, device="cuda", generator=g).to(TDT[dtype]) for sh in shapes]
+    sd = [torch.rand(sh[1], device="cuda", generator=g) * 0.05 + 0.01 for sh in shapes]
+    yb = [torch.empty_like(t) for t in xd]
+    dxb = [torch.empty_like(t) for t in xd]
+    dsb = [torch.empty(sh[1], dtype=torch.float32, device="cuda") for sh in shapes]
+    items = [(xd[i], dyd[i], sd[i], dxb[i], dsb[i]) for i in range(4)]
+    ws = B.new_workspace(B.sasq_fakequant_bwd_pc_batch_workspace(items))
+    B.sasq_fakequant_fwd_pc_batch([(xd[i], sd[i], yb[i]) for i in range(4)], 8)
+    B.sasq_fakequant_bwd_pc_batch(items, ws, 8)
+    torch.cuda.synchronize()
+    for i in range(4):
+        y1, dx1, ds1 = torch.empty_like(xd[i]), torch.empty_like(xd[i]), torch.empty_like(dsb[i])
+        ws1 = B.new_workspace(B.sasq_fakequant_bwd_pc_workspace(*shapes[i]))
+        B.sasq_fakequant_fwd_pc(xd[i], sd[i], y1, None, 8)
+        B.sasq_fakequant_bwd_pc(xd[i], dyd[i], sd[i], dx1, ds1, ws1, 8)
+        torch.cuda.synchronize()
+        assert torch.equal(y1.view(torch.int16), yb[i].view(torch.int16)), i
+        assert torch.equal(dx1.view(torch.int16), dxb[i].view(torch.int16)), i
+        assert torch.equal(ds1, dsb[i]), i
