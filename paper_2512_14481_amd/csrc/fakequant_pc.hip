@@ -222,36 +222,49 @@ __device__ __forceinline__ void bwd_pc_body(
     }
     __syncthreads();
     if (!is_last) return;
-    // last block of this column chunk: row chunks summed in ascending order, in fp64.  A thread
-    // takes columns tid and tid + 256 and keeps 2 x 32 partial loads in flight (loading them a
-    // few at a time leaves the whole grid's tail waiting on a chain of memory latencies).
+    // last block of this column chunk: row chunks summed in ascending order, in fp64.  The
+    // acquire fence makes the other blocks' write-through partials visible to ordinary loads.  A
+    // thread takes four adjacent columns (one 128-bit load per row chunk) of one half of the row
+    // chunks and keeps 32 loads in flight (loading them a few at a time leaves the whole grid's
+    // tail waiting on a chain of memory latencies); the halves meet in LDS, lower half first.
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     {
         constexpr int kBatch = 32;
-        int64_t colv[2];
-        bool ok[2];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int64_t cc = cbase + threadIdx.x + h * kPcThreads;
-            ok[h] = cc < cols;
-            colv[h] = ok[h] ? cc : cols - 1;
-        }
-        double t0 = 0.0, t1 = 0.0;
-        for (int rc0 = 0; rc0 < nchunks; rc0 += kBatch) {
-            float pv[2][kBatch];
+        const int half = threadIdx.x >> 7;                               // 0: first half of the chunks, 1: second
+        const int c4 = (threadIdx.x & 127) * 4;
+        const bool ok = cbase + c4 < cols;                               // cols is a multiple of 8
+        const uint32_t colv = ok ? (uint32_t)c4 : 0u;
+        const int split = (nchunks + 1) >> 1;
+        const int rc_begin = half ? split : 0, rc_end = half ? nchunks : split;
+        double t[4] = {0.0, 0.0, 0.0, 0.0};
+        for (int rc0 = rc_begin; rc0 < rc_end; rc0 += kBatch) {
+            f32x4 pv[kBatch];
 #pragma unroll
             for (int j = 0; j < kBatch; ++j) {
-                const int rc = rc0 + j < nchunks ? rc0 + j : nchunks - 1;
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    pv[h][j] = __hip_atomic_load(&partials[(int64_t)rc * cols + colv[h]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const int rc = rc0 + j < rc_end ? rc0 + j : nchunks - 1;
+                const float* rowp = partials + (int64_t)rc * cols + cbase;  // uniform: scalar base, lane offset
+                pv[j] = *reinterpret_cast<const f32x4*>(rowp + colv);
             }
 #pragma unroll
             for (int j = 0; j < kBatch; ++j)
-                if (rc0 + j < nchunks) { t0 += (double)pv[0][j]; t1 += (double)pv[1][j]; }
+                if (rc0 + j < rc_end) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) t[e] += (double)pv[j][e];
+                }
         }
-        if (ok[0]) ds[colv[0]] = (float)t0;
-        if (ok[1]) ds[colv[1]] = (float)t1;
+        double* meet = reinterpret_cast<double*>(&red[0][0]);            // 512 doubles of the 8 KB
+        __syncthreads();                                                 // red's earlier contents are consumed
+        if (half) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) meet[c4 + e] = t[e];
+        }
+        __syncthreads();
+        if (!half && ok) {
+            f32x4 out;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) out[e] = (float)(t[e] + meet[c4 + e]);
+            *reinterpret_cast<f32x4*>(&ds[cbase + c4]) = out;
+        }
     }
     if (threadIdx.x == 0) __hip_atomic_store(&tickets[col_block], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }

@@ -74,3 +74,21 @@ def test_per_channel_full_size(cfg_name, act_name):
     proj = next(p for p in cfg.projs if p.x == act_name)
     dyb = wl.upstream_grad(cfg, proj.name)
     check(xb, dyb, col_absmax_scales(xb, cfg.dtype, 4.0), cfg.dtype)
+
+
+def test_pc_backward_workspace_reuse_with_different_data():
+    """A second call on the same workspace with other data must not see the first call's partials."""
+    dtype = "f16"
+    shape = (700, 1032)
+    ws = B.new_workspace(B.sasq_fakequant_bwd_pc_workspace(*shape))
+    s = (np.abs(wl.random_f32(77, "rs", (shape[1],), 0.02)) + np.float32(0.004)).astype(np.float32)
+    sd = torch.from_numpy(s).cuda()
+    for rep in range(3):
+        xb = wl.random_bits(77 + rep, f"rx{rep}", shape, dtype, gain=2.0)
+        dyb = wl.random_bits(77 + rep, f"rd{rep}", shape, dtype, gain=1.0 + rep)
+        ds = torch.empty(shape[1], dtype=torch.float32, device="cuda")
+        B.sasq_fakequant_bwd_pc(to_dev(xb, dtype), to_dev(dyb, dtype), sd, None, ds, ws, 8)
+        torch.cuda.synchronize()
+        ref = oracle.fakequant_bwd_pc(xb, dyb, s, 8, dtype)
+        err = np.abs(ds.cpu().numpy().astype(np.float64) - ref["ds64"])
+        assert (err <= 1e-4 * np.abs(ref["ds64"]) + 1e-6 * ref["sum_abs"]).all(), rep
