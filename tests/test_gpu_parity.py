@@ -414,6 +414,38 @@ def test_static_linear_extreme_codes():
     assert_same_values(y, ref4["y"], "bf16", "Y int4 blocked")
 
 
+@pytest.mark.parametrize("K", [131008, 131070, 131071])
+def test_static_linear_maximum_K(K):
+    """The longest contraction the library accepts (K <= 131071 keeps K * 128 * 128 inside int32),
+    all codes at the extremes: 131008 runs the MFMA kernels (and the x16 in-register form of int4
+    weights ends 1 MiB short of 2^31), 131070 / 131071 the scalar kernel.  One more is refused."""
+    xv = np.tile(np.array([[-128.0], [127.0]], dtype=np.float32), (1, K))
+    xb = wl.f32_to_storage_bits(xv, "f16")
+    ones = np.ones(2, np.float32)
+    wq = np.stack([np.full(K, -128), np.full(K, 127)]).astype(np.int8)
+    ref = oracle.static_linear(xb, np.float32(1.0), wq, ones, None, 8, "int8", "f16")
+    assert ref["acc"][0, 0] == 128 * 128 * K and ref["acc"][0, 0] < 2 ** 31
+    variants = [dict(path="twopass"), dict(path="fused")] + ([dict(blocked=True)] if K % 64 == 0 else [])
+    for kw in variants:
+        y, acc, xq = run_linear(xb, np.float32(1.0), wq, ones, None, "int8", "f16", **kw)
+        assert np.array_equal(acc, ref["acc"]) and np.array_equal(xq, ref["xq"]), kw
+        assert_same_values(y, ref["y"], "f16", f"Y {kw}")
+    if K % 2 == 0:
+        w4 = np.stack([np.full(K // 2, 0x88), np.full(K // 2, 0x77)]).astype(np.uint8)
+        ref4 = oracle.static_linear(xb, np.float32(1.0), w4, ones, None, 8, "int4", "f16")
+        assert ref4["acc"][0, 0] == 128 * 8 * K
+        for kw in variants:
+            y, acc, _ = run_linear(xb, np.float32(1.0), w4, ones, None, "int4", "f16", **kw)
+            assert np.array_equal(acc, ref4["acc"]), kw
+            assert_same_values(y, ref4["y"], "f16", f"Y int4 {kw}")
+    x = to_dev(xb, "f16")
+    ws = B.new_workspace(1 << 20)
+    with pytest.raises(B.SasqError) as e:
+        B._check(B._lib().sasq_static_linear(B._ptr(x), B._ptr(dev_scalar(1.0)), B._ptr(x), B._ptr(x), None, B._ptr(x), None, None,
+                                             2, 2, 131072, 8, 0, 0, B._ptr(ws), 1 << 20, None), "K too long")
+    assert e.value.status == 2
+
+
 def test_cross_export_identity():
     """xq of the linear == codes of fake-quant, and Y ~ fakequant(x) . (Wq*s_w)^T (Eq. 2 <=> Eq. 5)."""
     dtype = "f16"
