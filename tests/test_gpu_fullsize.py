@@ -225,3 +225,65 @@ def test_batched_layer_calls_match_single_calls_full_size(cfg_name):
         assert torch.equal(Y1.view(torch.int16), Y_b.view(torch.int16)), (p.name, "Y")
         assert torch.isfinite(Y_b.float()).all()
         del Y1, wsl
+
+
+@pytest.mark.parametrize("per_channel", [False, True])
+def test_fakequant_beyond_2_31_elements(per_channel, ws):
+    """A tensor of 2.6e9 elements (flat indices beyond 2^31): forward and dx against the oracle on
+    row slices at the start, across the 2^31-element boundary and at the end; ds against the sum
+    of the same operator over eight row blocks (each below 2^31 elements)."""
+    dtype = "bf16"
+    rows, cols = 40000, 65544
+    assert rows * cols > 2 ** 31
+    g = torch.Generator(device="cuda").manual_seed(17)
+    x = torch.empty((rows, cols), dtype=TDT[dtype], device="cuda")
+    dy = torch.empty((rows, cols), dtype=TDT[dtype], device="cuda")
+    step = 5000
+    for r in range(0, rows, step):                     # filled block-wise: no fp32 copy of the whole tensor
+        x[r:r + step] = (torch.randn((step, cols), device="cuda", generator=g) * 2).to(TDT[dtype])
+        dy[r:r + step] = torch.randn((step, cols), device="cuda", generator=g).to(TDT[dtype])
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    if per_channel:
+        s_np = (np.abs(wl.random_f32(17, "bigs", (cols,), 0.02)) + np.float32(0.02)).astype(np.float32)
+        s = torch.from_numpy(s_np).cuda()
+        ds = torch.empty(cols, dtype=torch.float32, device="cuda")
+        wsp = B.new_workspace(B.sasq_fakequant_bwd_pc_workspace(rows, cols))
+        B.sasq_fakequant_fwd_pc(x, s, y, None, 8)
+        B.sasq_fakequant_bwd_pc(x, dy, s, dx, ds, wsp, 8)
+    else:
+        s_np = np.float32(0.03)
+        s = dev_scalar(s_np)
+        ds = torch.empty(1, dtype=torch.float32, device="cuda")
+        B.sasq_fakequant_fwd(x, s, y, None, 8)
+        B.sasq_fakequant_bwd(x, dy, s, dx, ds, ws, 8)
+    torch.cuda.synchronize()
+    edge = 2 ** 31 // cols                              # the row that holds flat index 2^31
+    for r0 in (0, edge - 1, 2 ** 32 // cols // 2, rows - 3):
+        sl = slice(r0, r0 + 3)
+        xb, dyb = to_bits(x[sl]), to_bits(dy[sl])
+        if per_channel:
+            y_ref, _ = oracle.fakequant_fwd_pc(xb, s_np, 8, dtype)
+            ref = oracle.fakequant_bwd_pc(xb, dyb, s_np, 8, dtype)
+        else:
+            y_ref, _ = oracle.fakequant_fwd(xb, s_np, 8, dtype)
+            ref = oracle.fakequant_bwd(xb, dyb, s_np, 8, dtype)
+        assert_same_values(to_bits(y[sl]), y_ref, dtype, f"y rows {r0}")
+        assert_same_values(to_bits(dx[sl]), ref["dx"], dtype, f"dx rows {r0}")
+    # ds: the whole-tensor reduction against eight separate reductions over row blocks
+    total = np.zeros(ds.numel(), dtype=np.float64)
+    for r in range(0, rows, step):
+        part = torch.empty_like(ds)
+        if per_channel:
+            B.sasq_fakequant_bwd_pc(x[r:r + step], dy[r:r + step], s, None, part, wsp, 8)
+        else:
+            B.sasq_fakequant_bwd(x[r:r + step], dy[r:r + step], s, None, part, ws, 8)
+        torch.cuda.synchronize()
+        total += part.cpu().numpy().astype(np.float64)
+    got = ds.cpu().numpy().astype(np.float64)
+    # the two differ by summation order only: 1e-4 relative plus fp32 rounding noise scaled by an upper
+    # bound of the sum of |terms| (every term is at most 128 |dy|); an indexing mistake is off by ~|ds|
+    abs_dy = torch.zeros(cols, dtype=torch.float64, device="cuda")
+    for r in range(0, rows, step):
+        abs_dy += dy[r:r + step].abs().sum(dim=0, dtype=torch.float64)
+    bound = 128.0 * (abs_dy.cpu().numpy() if per_channel else float(abs_dy.sum().item()))
+    assert (np.abs(got - total) <= 1e-4 * np.abs(total) + 1e-6 * bound).all(), (np.abs(got - total).max(), np.abs(total).min())
