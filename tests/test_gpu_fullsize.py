@@ -287,3 +287,31 @@ def test_fakequant_beyond_2_31_elements(per_channel, ws):
         abs_dy += dy[r:r + step].abs().sum(dim=0, dtype=torch.float64)
     bound = 128.0 * (abs_dy.cpu().numpy() if per_channel else float(abs_dy.sum().item()))
     assert (np.abs(got - total) <= 1e-4 * np.abs(total) + 1e-6 * bound).all(), (np.abs(got - total).max(), np.abs(total).min())
+
+
+@pytest.mark.parametrize("blocked", [False, True])
+def test_static_linear_output_beyond_2_31_elements(blocked):
+    """Y with 2.3e9 elements (flat output indices beyond 2^31), short K: sampled token rows on both
+    sides of the 32-bit boundary against the oracle."""
+    dtype = "f16"
+    M, N, K = 70000, 32768, 64
+    assert M * N > 2 ** 31
+    xb = wl.random_bits(19, "bigx", (M, K), dtype, gain=2.0)
+    wq, s_w = oracle.quantize_weight(wl.random_f32(19, "bigw", (N, K), 0.02), "int8")
+    bias = wl.random_f32(19, "bigb", (N,), 0.3)
+    s = np.float32(0.04)
+    wf = B.SASQ_W_INT8
+    wd = torch.from_numpy(wq).cuda()
+    if blocked:
+        packed = torch.empty(B.sasq_packed_weight_bytes(N, K, B.SASQ_W_INT8_BLOCKED), dtype=torch.uint8, device="cuda")
+        B.sasq_pack_weight(wd, packed, N, K, B.SASQ_W_INT8)
+        wd, wf = packed, B.SASQ_W_INT8_BLOCKED
+    y = torch.empty((M, N), dtype=TDT[dtype], device="cuda")
+    wsl = B.new_workspace(B.sasq_static_linear_workspace(M, N, K, wf))
+    B.sasq_static_linear(to_dev(xb, dtype), dev_scalar(s), wd, torch.from_numpy(s_w).cuda(), torch.from_numpy(bias).cuda(),
+                         y, wf, wsl)
+    torch.cuda.synchronize()
+    edge = 2 ** 31 // N
+    rows = np.array([0, 1, edge - 1, edge, edge + 1, M - 2, M - 1])
+    ref = oracle.static_linear(xb[rows], s, wq, s_w, bias, 8, "int8", dtype)
+    assert_same_values(to_bits(y[torch.from_numpy(rows).cuda()]), ref["y"], dtype, "Y rows")
