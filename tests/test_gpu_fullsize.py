@@ -315,3 +315,35 @@ def test_static_linear_output_beyond_2_31_elements(blocked):
     rows = np.array([0, 1, edge - 1, edge, edge + 1, M - 2, M - 1])
     ref = oracle.static_linear(xb[rows], s, wq, s_w, bias, 8, "int8", dtype)
     assert_same_values(to_bits(y[torch.from_numpy(rows).cuda()]), ref["y"], dtype, "Y rows")
+
+
+@pytest.mark.parametrize("blocked", [False, True])
+def test_static_linear_activations_beyond_2_31_elements(blocked):
+    """X (and the library's staged int8 copy of it) with 2.3e9 elements, few output channels: sampled
+    token rows on both sides of the 32-bit boundary against the oracle."""
+    dtype = "bf16"
+    M, N, K = 70000, 64, 32768
+    assert M * K > 2 ** 31
+    g = torch.Generator(device="cuda").manual_seed(23)
+    x = torch.empty((M, K), dtype=TDT[dtype], device="cuda")
+    for r in range(0, M, 10000):
+        x[r:r + 10000] = (torch.randn((10000, K), device="cuda", generator=g) * 2).to(TDT[dtype])
+    wq, s_w = oracle.quantize_weight(wl.random_f32(23, "bigw2", (N, K), 0.02), "int8")
+    s = np.float32(0.05)
+    wf = B.SASQ_W_INT8
+    wd = torch.from_numpy(wq).cuda()
+    if blocked:
+        packed = torch.empty(B.sasq_packed_weight_bytes(N, K, B.SASQ_W_INT8_BLOCKED), dtype=torch.uint8, device="cuda")
+        B.sasq_pack_weight(wd, packed, N, K, B.SASQ_W_INT8)
+        wd, wf = packed, B.SASQ_W_INT8_BLOCKED
+    y = torch.empty((M, N), dtype=TDT[dtype], device="cuda")
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    wsl = B.new_workspace(B.sasq_static_linear_workspace(M, N, K, wf))
+    B.sasq_static_linear(x, dev_scalar(s), wd, torch.from_numpy(s_w).cuda(), None, y, wf, wsl, acc, None)
+    torch.cuda.synchronize()
+    edge = 2 ** 31 // K
+    rows = np.array([0, 1, edge - 1, edge, edge + 1, M - 2, M - 1])
+    idx = torch.from_numpy(rows).cuda()
+    ref = oracle.static_linear(to_bits(x[idx]), s, wq, s_w, None, 8, "int8", dtype)
+    assert np.array_equal(acc[idx].cpu().numpy(), ref["acc"])
+    assert_same_values(to_bits(y[idx]), ref["y"], dtype, "Y rows")
