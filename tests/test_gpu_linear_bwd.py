@@ -149,3 +149,21 @@ def test_linear_bwd_full_size_sampled_rows(cfg_name, proj):
     rows = np.array([0, 1, 255, 256, M // 2 + 1, M - 129, M - 2, M - 1])
     ref = oracle.linear_bwd_input(dyb[rows], wq, s_w, fmt, dtype)
     check_dx(got[rows], ref, dtype, N, f"{cfg_name}/{proj}")
+
+
+def test_linear_bwd_output_beyond_2_31_elements():
+    """dX with 2.3e9 elements (flat indices beyond 2^31), short contraction: sampled token rows on
+    both sides of the 32-bit boundary against the oracle."""
+    dtype, fmt = "bf16", "int8"
+    M, N, K = 70000, 32, 32768
+    assert M * K > 2 ** 31
+    dyb = wl.random_bits(29, "bigdy", (M, N), dtype, gain=0.02)
+    wq, s_w = oracle.quantize_weight(wl.random_f32(29, "bigwb", (N, K), 0.02), fmt)
+    wt, _ = prepare(wq, s_w, fmt, dtype)
+    dx = torch.empty((M, K), dtype=TDT[dtype], device="cuda")
+    B.sasq_linear_bwd_input(to_dev(dyb, dtype), wt, dx, K)
+    torch.cuda.synchronize()
+    edge = 2 ** 31 // K
+    rows = np.array([0, 1, edge - 1, edge, edge + 1, M - 2, M - 1])
+    ref = oracle.linear_bwd_input(dyb[rows], wq, s_w, fmt, dtype)
+    check_dx(to_bits(dx[torch.from_numpy(rows).cuda()]), ref, dtype, N, "rows across the boundary")
