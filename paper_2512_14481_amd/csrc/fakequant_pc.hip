@@ -473,7 +473,7 @@ extern "C" int sasq_fakequant_bwd_pc(const void* x, const void* dy, const float*
 // ---- batched entry points ----------------------------------------------------------------------
 namespace sasq {
 
-constexpr size_t kPcBatchLaunchBytes = (size_t)192 << 20;   // input bytes per launch: more concurrent streams run slower
+constexpr size_t kPcBatchLaunchBytes = (size_t)192 << 20;   // bytes of x per launch: more concurrent streams run slower
 
 static int check_pc_items(const sasq_fq_item* items, int count, int bits, sasq_dtype dt, bool backward)
 {
@@ -566,7 +566,7 @@ static int run_pc_batch(const sasq_fq_item* items, int count, int bits, sasq_dty
         size_t bytes = 0;
         int i1 = i0;
         while (i1 < count) {
-            const size_t add = (size_t)items[i1].rows * (size_t)items[i1].cols * (BACKWARD ? 4 : 2);
+            const size_t add = (size_t)items[i1].rows * (size_t)items[i1].cols * 2;      // bytes of x, as the per-tensor batch counts
             if (i1 > i0 && bytes + add > kPcBatchLaunchBytes) break;
             bytes += add;
             ++i1;
