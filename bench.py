@@ -185,8 +185,8 @@ def cpu_baseline(cfg, rows: int):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", default="c3_mlp7b")
     ap.add_argument("--cpu-rows", type=int, default=4096)
     ap.add_argument("--no-cpu", action="store_true")
@@ -246,6 +246,10 @@ def main():
         lin_ops_per_call = total_ops / len(projs)     # average over the projections' calls
         lin_avg_ms = sum(t for t, _ in lin_ms) / len(lin_ms)
     lin_tops = lin_ops_per_call / (lin_avg_ms * 1e-3) / 1e12
+    # spread over the timed steps (median and fastest call)
+    lin_all = sorted(e0.elapsed_time(e1) for e0, e1 in ev["lin_batch"]) if ev["lin_batch"] else sorted(t for t, _ in lin_ms)
+    fq_all = sorted(e0.elapsed_time(e1) for e0, e1 in ev["fq"]) if ev["fq"] else []
+    med = lambda v: v[len(v) // 2] if v else None
     if a.unbatched:
         fq_gbps = sum(p.fq_bytes for _, p in fq_ms) / (sum(t for t, _ in fq_ms) * 1e-3) / 1e9
     else:
@@ -416,10 +420,13 @@ def main():
                      "traffic_unit": "bytes per call (rocprofv3 FETCH_SIZE/WRITE_SIZE, copy-calibrated)",
                      "algorithmic_bytes": int(sum(3 * p.M * p.K + p.M * p.K + p.wq.numel() + 2 * p.M * p.N + 4 * p.N
                                                   for p in projs) / (1 if ev["lin_batch"] else len(projs))),
-                     "avg_launch_us": round(lin_avg_ms * 1e3, 2)},
+                     "avg_launch_us": round(lin_avg_ms * 1e3, 2),
+                     "median_launch_us": round(med(lin_all) * 1e3, 2), "min_launch_us": round(lin_all[0] * 1e3, 2)},
         "fakequant": {"bound": "hbm", "achieved": round(fq_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                       "frac": round(fq_gbps / HBM_PEAK_GBPS, 4),
                       "bytes_per_element": 10,
+                      "median_us": round(med(fq_all) * 1e3, 2) if fq_all else None,
+                      "min_us": round(fq_all[0] * 1e3, 2) if fq_all else None,
                       "note": ("fwd (2+2 B/el) + bwd (2+2+2 B/el); " +
                                ("events around each tensor's pair of launches" if a.unbatched else
                                 "one batched launch each for all projection inputs of the layer, events around the two launches; "
