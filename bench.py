@@ -32,6 +32,9 @@ from paper_2512_14481_amd import workloads as wl       # noqa: E402
 
 INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8, published
 F16_MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense fp16 / bf16, published
+# what a register-only v_mfma_i32_32x32x32_i8 loop sustains on this part with GEMM-like operand codes (the part is
+# power-limited under MFMA load; profiles/mfma_peak_and_clock.txt) -- context for `frac`, not the roofline's peak
+INT8_MFMA_SUSTAINED_TOPS = 3750.0
 # HBM-side bytes per sasq_static_linear call (both kernels), averaged over gate/up/down of config 3:
 # rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a plain 1 GiB copy), see
 # profiles/bench_c3_mlp7b_counters.txt.  Algorithmic bytes are 221.2 MB.
@@ -416,6 +419,8 @@ def main():
                                 "sasq_static_linear (activation quantize + int8 MFMA GEMM + dequant)"),
                      "achieved": round(lin_tops, 1), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": round(lin_tops / INT8_MFMA_PEAK_TOPS, 4),
+                     "sustained_mfma_only": INT8_MFMA_SUSTAINED_TOPS,
+                     "frac_of_sustained": round(lin_tops / INT8_MFMA_SUSTAINED_TOPS, 4),
                      "traffic": (C3_LINEAR_BATCH_TRAFFIC_BYTES if ev["lin_batch"] else C3_LINEAR_TRAFFIC_BYTES) if cfg.name == "c3_mlp7b" else None,
                      "traffic_unit": "bytes per call (rocprofv3 FETCH_SIZE/WRITE_SIZE, copy-calibrated)",
                      "algorithmic_bytes": int(sum(3 * p.M * p.K + p.M * p.K + p.wq.numel() + 2 * p.M * p.N + 4 * p.N
