@@ -92,19 +92,23 @@ __global__ __launch_bounds__(kThreads) void fakequant_fwd_kernel(
 // Several tensors in one launch (the fake-quant operators of one decoder layer): the grid is cut
 // into one run of blocks per tensor, sized by the host in proportion to the tensor.
 constexpr int kMaxBatch = SASQ_MAX_BATCH;
+// Operators that read the same x (the fake-quant operators in front of q/k/v, or gate/up: one input,
+// one factor each) form one entry: its blocks load x once and apply every member's factor.
+constexpr int kMaxShare = 3;
 struct FqBatchItem {
     const u32x4* x;
-    const u32x4* dy;
-    const float* s;
-    u32x4* out;
-    float* ds;
     int64_t nvec, n;
+    int ns;                           // members (1 = an operator alone on its x)
+    const float* s[kMaxShare];
+    const u32x4* dy[kMaxShare];
+    u32x4* out[kMaxShare];
+    float* ds[kMaxShare];
+    int slot[kMaxShare];              // index in the caller's batch: selects the ticket word and the partials
 };
 struct FqBatch {
     FqBatchItem it[kMaxBatch];
     int first_block[kMaxBatch + 1];
     int count;
-    int index0;      // index in the caller's batch of it[0]
 };
 
 __device__ __forceinline__ int batch_item_of(const FqBatch& b, int block)
@@ -116,13 +120,65 @@ __device__ __forceinline__ int batch_item_of(const FqBatch& b, int block)
     return k;
 }
 
-template <int DT>
+// Forward of NS operators on one x: same traversal as fwd_body, one load of x per NS stores.
+template <int DT, int NS>
+__device__ __forceinline__ void fwd_body_shared(const FqBatchItem& it, int bits, int block, int nblocks)
+{
+    using S = Store16<DT>;
+    const u32x4* __restrict__ x = it.x;
+    const int64_t nvec = it.nvec, n = it.n;
+    QConst k[NS];
+#pragma unroll
+    for (int j = 0; j < NS; ++j) k[j] = make_qconst(*it.s[j], bits);
+    constexpr int64_t kChunk = (int64_t)kThreads * kUnroll;
+    const int64_t full_end = nvec / kChunk * kChunk;
+    for (int64_t base = (int64_t)block * kChunk; base < full_end; base += (int64_t)nblocks * kChunk) {
+        u32x4 in[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) in[u] = __builtin_nontemporal_load(&x[base + u * kThreads + threadIdx.x]);
+#pragma unroll
+        for (int j = 0; j < NS; ++j)
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                u32x4 out;
+                u32x2 cw;
+                fwd_vec<DT, false>(in[u], k[j], out, cw);
+                __builtin_nontemporal_store(out, &it.out[j][base + u * kThreads + threadIdx.x]);
+            }
+    }
+    if (block != 0) return;
+    for (int64_t i = full_end + threadIdx.x; i < nvec; i += kThreads) {
+        const u32x4 in = x[i];
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            u32x4 out;
+            u32x2 cw;
+            fwd_vec<DT, false>(in, k[j], out, cw);
+            it.out[j][i] = out;
+        }
+    }
+    if (threadIdx.x < (unsigned)(n - nvec * 8)) {
+        const int64_t i = nvec * 8 + threadIdx.x;
+        const float xv = S::one(reinterpret_cast<const uint16_t*>(x)[i]);
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            QElem e = quantize(xv, k[j]);
+            reinterpret_cast<uint16_t*>(it.out[j])[i] = S::enc(codef_of(e) * k[j].s);
+        }
+    }
+}
+
+// SHARED: some entry of the launch has more than one member (a launch without any keeps the leaner
+// kernel: the shared bodies cost registers that lower its occupancy).
+template <int DT, bool SHARED>
 __global__ __launch_bounds__(kThreads) void fakequant_fwd_batch_kernel(const FqBatch b, int bits)
 {
     const int k = batch_item_of(b, (int)blockIdx.x);
     const FqBatchItem& it = b.it[k];
-    fwd_body<DT, false>(it.x, it.s, it.out, nullptr, it.nvec, it.n, bits,
-                        (int)blockIdx.x - b.first_block[k], b.first_block[k + 1] - b.first_block[k]);
+    const int block = (int)blockIdx.x - b.first_block[k], nblocks = b.first_block[k + 1] - b.first_block[k];
+    if (SHARED && it.ns == 2)      fwd_body_shared<DT, 2>(it, bits, block, nblocks);
+    else if (SHARED && it.ns == 3) fwd_body_shared<DT, 3>(it, bits, block, nblocks);
+    else                           fwd_body<DT, false>(it.x, it.s[0], it.out[0], nullptr, it.nvec, it.n, bits, block, nblocks);
 }
 
 // Per-element backward term.  For an unclipped element q == round(p), and fma(-x, inv_s, q)
@@ -152,6 +208,70 @@ __device__ __forceinline__ float bwd_vec(const u32x4& xin, const u32x4& gin, con
         out[w] = gin[w] & ((ka ? 0x0000FFFFu : 0u) | (kb ? 0xFFFF0000u : 0u));
     }
     return part;
+}
+
+__device__ __forceinline__ void final_reduce(float* __restrict__ ds, uint32_t* __restrict__ ticket_word,
+                                             double* __restrict__ partials, int nblocks);
+
+// The grid-wide part of the ds reduction for one tensor: this block's lane sums -> one fp64
+// partial, published; the last block to arrive sums all partials in a fixed order.
+__device__ __forceinline__ void publish_and_reduce(double acc, float* __restrict__ ds, uint32_t* __restrict__ ticket_word,
+                                                   double* __restrict__ partials, int block, int nblocks)
+{
+    // block partial: lanes -> wave (shuffles) -> block (LDS), fixed order
+    __shared__ double wave_part[kThreads / kWave];
+    __shared__ bool is_last;
+    double w = wave_sum(acc);
+    const int lane = threadIdx.x % kWave, wid = threadIdx.x / kWave;
+    if (lane == 0) wave_part[wid] = w;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double b = 0.0;
+#pragma unroll
+        for (int i = 0; i < kThreads / kWave; ++i) b += wave_part[i];
+        __hip_atomic_store(&partials[block], b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // The partial went out as an agent-scope atomic store (written through to where every XCD
+        // sees it); waiting for its acknowledgement orders it before the ticket.  A release fence
+        // here would instead write back this XCD's whole L2 once per block.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        uint32_t ticket = __hip_atomic_fetch_add(ticket_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        is_last = (ticket == kTicketBase + (uint32_t)nblocks - 1);
+        if (ticket - kTicketBase >= (uint32_t)nblocks)      // workspace was never initialised: fail loudly
+            *ds = __uint_as_float(0x7FC00000u);
+    }
+    __syncthreads();
+    if (!is_last) return;
+    final_reduce(ds, ticket_word, partials, nblocks);
+}
+
+// Deterministic second pass by the last block to arrive: fixed strided order, fp64.
+__device__ __forceinline__ void final_reduce(float* __restrict__ ds, uint32_t* __restrict__ ticket_word,
+                                             double* __restrict__ partials, int nblocks)
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    // all of a thread's partials are requested before the first is used (one memory latency, not
+    // one per partial); the summation order stays fixed
+    constexpr int kPer = kMaxReduceBlocks / kThreads;
+    double pv[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int i = j * kThreads + threadIdx.x;
+        pv[j] = __hip_atomic_load(&partials[i < nblocks ? i : 0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    double t = 0.0;
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) t += (j * kThreads + (int)threadIdx.x < nblocks) ? pv[j] : 0.0;
+    __shared__ double tree[kThreads];
+    tree[threadIdx.x] = t;
+    __syncthreads();
+    for (int off = kThreads / 2; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) tree[threadIdx.x] += tree[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        *ds = (float)tree[0];
+        __hip_atomic_store(ticket_word, kTicketBase, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 // Backward over one tensor by block `block` of the `nblocks` (<= kMaxReduceBlocks) that share it;
@@ -199,55 +319,7 @@ __device__ __forceinline__ void bwd_body(
         }
     }
 
-    // block partial: lanes -> wave (shuffles) -> block (LDS), fixed order
-    __shared__ double wave_part[kThreads / kWave];
-    __shared__ bool is_last;
-    double w = wave_sum(acc);
-    const int lane = threadIdx.x % kWave, wid = threadIdx.x / kWave;
-    if (lane == 0) wave_part[wid] = w;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        double b = 0.0;
-#pragma unroll
-        for (int i = 0; i < kThreads / kWave; ++i) b += wave_part[i];
-        __hip_atomic_store(&partials[block], b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // The partial went out as an agent-scope atomic store (written through to where every XCD
-        // sees it); waiting for its acknowledgement orders it before the ticket.  A release fence
-        // here would instead write back this XCD's whole L2 once per block.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        uint32_t ticket = __hip_atomic_fetch_add(ticket_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        is_last = (ticket == kTicketBase + (uint32_t)nblocks - 1);
-        if (ticket - kTicketBase >= (uint32_t)nblocks)      // workspace was never initialised: fail loudly
-            *ds = __uint_as_float(0x7FC00000u);
-    }
-    __syncthreads();
-    if (!is_last) return;
-
-    // deterministic second pass by the last block to arrive: fixed strided order, fp64
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    // all of a thread's partials are requested before the first is used (one memory latency, not
-    // one per partial); the summation order stays fixed
-    constexpr int kPer = kMaxReduceBlocks / kThreads;
-    double pv[kPer];
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-        const int i = j * kThreads + threadIdx.x;
-        pv[j] = __hip_atomic_load(&partials[i < nblocks ? i : 0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    double t = 0.0;
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) t += (j * kThreads + (int)threadIdx.x < nblocks) ? pv[j] : 0.0;
-    __shared__ double tree[kThreads];
-    tree[threadIdx.x] = t;
-    __syncthreads();
-    for (int off = kThreads / 2; off > 0; off >>= 1) {
-        if ((int)threadIdx.x < off) tree[threadIdx.x] += tree[threadIdx.x + off];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) {
-        *ds = (float)tree[0];
-        __hip_atomic_store(ticket_word, kTicketBase, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+    publish_and_reduce(acc, ds, ticket_word, partials, block, nblocks);
 }
 
 template <int DT, bool WRITE_DX>
@@ -261,16 +333,116 @@ __global__ __launch_bounds__(kThreads) void fakequant_bwd_kernel(
 
 // Batched backward: tensor k uses ticket word k of the workspace header and its own run of
 // kMaxReduceBlocks partials.
-template <int DT>
+// Backward of NS operators on one x: x is loaded once; every member has its own dy, dx and ds.
+template <int DT, int NS>
+__device__ __forceinline__ void bwd_body_shared(const FqBatchItem& it, uint32_t* __restrict__ ws_head,
+                                                double* __restrict__ partials, int bits, int block, int nblocks)
+{
+    using S = Store16<DT>;
+    const u32x4* __restrict__ x = it.x;
+    const int64_t nvec = it.nvec, n = it.n;
+    QConst k[NS];
+    double acc[NS];
+#pragma unroll
+    for (int j = 0; j < NS; ++j) {
+        k[j] = make_qconst(*it.s[j], bits);
+        acc[j] = 0.0;
+    }
+    constexpr int kU = kUnroll;
+    constexpr int64_t kChunk = (int64_t)kThreads * kU;
+    const int64_t full_end = nvec / kChunk * kChunk;
+    for (int64_t base = (int64_t)block * kChunk; base < full_end; base += (int64_t)nblocks * kChunk) {
+        u32x4 xin[kU];
+#pragma unroll
+        for (int u = 0; u < kU; ++u) xin[u] = __builtin_nontemporal_load(&x[base + u * kThreads + threadIdx.x]);
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            u32x4 gin[kU];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) gin[u] = __builtin_nontemporal_load(&it.dy[j][base + u * kThreads + threadIdx.x]);
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                u32x4 out;
+                acc[j] += (double)bwd_vec<DT>(xin[u], gin[u], k[j], out);
+                if (it.out[j]) __builtin_nontemporal_store(out, &it.out[j][base + u * kThreads + threadIdx.x]);
+            }
+        }
+    }
+    if (block == 0) {
+        for (int64_t i = full_end + threadIdx.x; i < nvec; i += kThreads) {
+            const u32x4 xin = x[i];
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
+                u32x4 out;
+                acc[j] += (double)bwd_vec<DT>(xin, it.dy[j][i], k[j], out);
+                if (it.out[j]) it.out[j][i] = out;
+            }
+        }
+        if (threadIdx.x < (unsigned)(n - nvec * 8)) {
+            const int64_t i = nvec * 8 + threadIdx.x;
+            const float xv = S::one(reinterpret_cast<const uint16_t*>(x)[i]);
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
+                const uint16_t g = reinterpret_cast<const uint16_t*>(it.dy[j])[i];
+                bool keep;
+                const float tt = ds_term(xv, S::one(g), k[j], keep);
+                acc[j] += (double)tt;
+                if (it.out[j]) reinterpret_cast<uint16_t*>(it.out[j])[i] = keep ? g : (uint16_t)0;
+            }
+        }
+    }
+    // Grid-wide part for all members at once: the NS partials go out together and the NS tickets
+    // are taken back to back (one store acknowledgement and one atomic round trip for the group,
+    // not one per member); then whoever arrived last for a member finishes that member.
+    __shared__ double wave_part[kMaxShare][kThreads / kWave];
+    __shared__ bool is_last[kMaxShare];
+    const int lane = threadIdx.x % kWave, wid = threadIdx.x / kWave;
+#pragma unroll
+    for (int j = 0; j < NS; ++j) {
+        const double w = wave_sum(acc[j]);
+        if (lane == 0) wave_part[j][wid] = w;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            double bsum = 0.0;
+#pragma unroll
+            for (int i = 0; i < kThreads / kWave; ++i) bsum += wave_part[j][i];
+            __hip_atomic_store(&partials[it.slot[j] * kMaxReduceBlocks + block], bsum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the write-through stores are acknowledged before any ticket
+        uint32_t ticket[NS];
+#pragma unroll
+        for (int j = 0; j < NS; ++j)
+            ticket[j] = __hip_atomic_fetch_add(ws_head + it.slot[j], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            is_last[j] = (ticket[j] == kTicketBase + (uint32_t)nblocks - 1);
+            if (ticket[j] - kTicketBase >= (uint32_t)nblocks) *it.ds[j] = __uint_as_float(0x7FC00000u);   // uninitialised workspace
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NS; ++j) {
+        if (is_last[j]) final_reduce(it.ds[j], ws_head + it.slot[j], partials + it.slot[j] * kMaxReduceBlocks, nblocks);
+        __syncthreads();      // final_reduce's LDS words are reused by the next member
+    }
+}
+
+template <int DT, bool SHARED>
 __global__ __launch_bounds__(kThreads) void fakequant_bwd_batch_kernel(
     const FqBatch b, uint32_t* __restrict__ ws_head, double* __restrict__ partials, int bits)
 {
     const int k = batch_item_of(b, (int)blockIdx.x);
     const FqBatchItem& it = b.it[k];
     const int block = (int)blockIdx.x - b.first_block[k], nblocks = b.first_block[k + 1] - b.first_block[k];
-    const int slot = b.index0 + k;
-    if (it.out) bwd_body<DT, true>(it.x, it.dy, it.s, it.out, it.ds, ws_head + slot, partials + slot * kMaxReduceBlocks, it.nvec, it.n, bits, block, nblocks);
-    else        bwd_body<DT, false>(it.x, it.dy, it.s, it.out, it.ds, ws_head + slot, partials + slot * kMaxReduceBlocks, it.nvec, it.n, bits, block, nblocks);
+    if (SHARED && it.ns == 2) { bwd_body_shared<DT, 2>(it, ws_head, partials, bits, block, nblocks); return; }
+    if (SHARED && it.ns == 3) { bwd_body_shared<DT, 3>(it, ws_head, partials, bits, block, nblocks); return; }
+    uint32_t* ticket = ws_head + it.slot[0];
+    double* parts = partials + it.slot[0] * kMaxReduceBlocks;
+    if (it.out[0]) bwd_body<DT, true>(it.x, it.dy[0], it.s[0], it.out[0], it.ds[0], ticket, parts, it.nvec, it.n, bits, block, nblocks);
+    else           bwd_body<DT, false>(it.x, it.dy[0], it.s[0], it.out[0], it.ds[0], ticket, parts, it.nvec, it.n, bits, block, nblocks);
 }
 
 __global__ void scale_sgd_vec_kernel(float* s, const float* ds, int n, float lr)
@@ -436,27 +608,48 @@ static int check_items(const sasq_fq_item* items, int count, bool backward)
 // (it selects the tensor's ticket word and partials).
 static void build_launch(const sasq_fq_item* items, int lo, int hi, int total_blocks, int max_per_item, FqBatch& b)
 {
+    // entries: operators on the same x (same pointer, same size) share one, up to kMaxShare members
+    b.count = 0;
     int64_t total_vec = 0;
+    bool taken[kMaxBatch] = {false};
     for (int i = lo; i < hi; ++i) {
-        const sasq_fq_item& it = items[i];
-        const int64_t n = it.rows * it.cols;
-        b.it[i - lo] = FqBatchItem{static_cast<const u32x4*>(it.x), static_cast<const u32x4*>(it.dy), it.s,
-                                   static_cast<u32x4*>(it.out), it.ds, n / 8, n};
-        total_vec += n / 8 + 1;
+        if (taken[i - lo]) continue;
+        const int64_t n = items[i].rows * items[i].cols;
+        FqBatchItem& e = b.it[b.count++];
+        e.x = static_cast<const u32x4*>(items[i].x);
+        e.nvec = n / 8;
+        e.n = n;
+        e.ns = 0;
+        for (int j = i; j < hi && e.ns < kMaxShare; ++j) {
+            if (taken[j - lo] || items[j].x != items[i].x || items[j].rows * items[j].cols != n) continue;
+            taken[j - lo] = true;
+            e.s[e.ns] = items[j].s;
+            e.dy[e.ns] = static_cast<const u32x4*>(items[j].dy);
+            e.out[e.ns] = static_cast<u32x4*>(items[j].out);
+            e.ds[e.ns] = items[j].ds;
+            e.slot[e.ns] = j;
+            ++e.ns;
+        }
+        total_vec += (n / 8 + 1) * e.ns;
     }
-    b.count = hi - lo;
-    b.index0 = lo;
     b.first_block[0] = 0;
     const int64_t per_block = (int64_t)kThreads * kUnroll;
     for (int i = 0; i < b.count; ++i) {
         const int64_t need = (b.it[i].nvec + per_block - 1) / per_block;            // blocks that would each have a full chunk
-        int64_t share = ((b.it[i].nvec + 1) * total_blocks + total_vec - 1) / total_vec;
+        int64_t share = ((b.it[i].nvec + 1) * b.it[i].ns * total_blocks + total_vec - 1) / total_vec;
         if (share > need) share = need;
         if (share > max_per_item) share = max_per_item;
         if (share < 1) share = 1;
         b.first_block[i + 1] = b.first_block[i] + (int)share;
     }
     for (int i = b.count; i < kMaxBatch; ++i) b.first_block[i + 1] = b.first_block[b.count];
+}
+
+static bool any_shared(const FqBatch& b)
+{
+    for (int i = 0; i < b.count; ++i)
+        if (b.it[i].ns > 1) return true;
+    return false;
 }
 
 // next launch: items [lo, return value)
@@ -486,8 +679,14 @@ extern "C" int sasq_fakequant_fwd_batch(const sasq_fq_item* items, int count, in
         FqBatch b{};
         build_launch(items, lo, hi, kBatchFwdBlocks, kBatchFwdBlocks, b);
         const int grid = b.first_block[b.count];
-        if (dt == SASQ_F16) fakequant_fwd_batch_kernel<SASQ_F16><<<grid, kThreads, 0, as_stream(stream)>>>(b, bits);
-        else                fakequant_fwd_batch_kernel<SASQ_BF16><<<grid, kThreads, 0, as_stream(stream)>>>(b, bits);
+        hipStream_t st = as_stream(stream);
+        if (any_shared(b)) {
+            if (dt == SASQ_F16) fakequant_fwd_batch_kernel<SASQ_F16, true><<<grid, kThreads, 0, st>>>(b, bits);
+            else                fakequant_fwd_batch_kernel<SASQ_BF16, true><<<grid, kThreads, 0, st>>>(b, bits);
+        } else {
+            if (dt == SASQ_F16) fakequant_fwd_batch_kernel<SASQ_F16, false><<<grid, kThreads, 0, st>>>(b, bits);
+            else                fakequant_fwd_batch_kernel<SASQ_BF16, false><<<grid, kThreads, 0, st>>>(b, bits);
+        }
         lo = hi;
     }
     return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
@@ -516,8 +715,14 @@ extern "C" int sasq_fakequant_bwd_batch(const sasq_fq_item* items, int count, in
         // a tensor alone in its launch gets what the single-tensor call gives it: one block per CU
         build_launch(items, lo, hi, hi - lo == 1 ? kMaxReduceBlocks : kBatchBwdBlocks, kMaxReduceBlocks, b);
         const int grid = b.first_block[b.count];
-        if (dt == SASQ_F16) fakequant_bwd_batch_kernel<SASQ_F16><<<grid, kThreads, 0, as_stream(stream)>>>(b, head, parts, bits);
-        else                fakequant_bwd_batch_kernel<SASQ_BF16><<<grid, kThreads, 0, as_stream(stream)>>>(b, head, parts, bits);
+        hipStream_t st = as_stream(stream);
+        if (any_shared(b)) {
+            if (dt == SASQ_F16) fakequant_bwd_batch_kernel<SASQ_F16, true><<<grid, kThreads, 0, st>>>(b, head, parts, bits);
+            else                fakequant_bwd_batch_kernel<SASQ_BF16, true><<<grid, kThreads, 0, st>>>(b, head, parts, bits);
+        } else {
+            if (dt == SASQ_F16) fakequant_bwd_batch_kernel<SASQ_F16, false><<<grid, kThreads, 0, st>>>(b, head, parts, bits);
+            else                fakequant_bwd_batch_kernel<SASQ_BF16, false><<<grid, kThreads, 0, st>>>(b, head, parts, bits);
+        }
         lo = hi;
     }
     return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;

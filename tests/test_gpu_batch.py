@@ -223,3 +223,40 @@ def test_pc_batch_errors_and_layer_sizes():
         assert torch.equal(y1.view(torch.int16), yb[i].view(torch.int16)), i
         assert torch.equal(dx1.view(torch.int16), dxb[i].view(torch.int16)), i
         assert torch.equal(ds1, dsb[i]), i
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("shape", [(3, 5), (64, 256), (257, 1031), (700, 4099)])
+def test_batch_operators_sharing_one_input(dtype, shape):
+    """Five operators, three of them (not adjacent in the batch) on the same x with different factors,
+    two on another x: the library reads a shared x once.  Everything must equal the single-tensor
+    calls bit for bit (ds within the reduction-order tolerance) and the oracle."""
+    xa = wl.random_bits(87, f"sxa{shape}{dtype}", shape, dtype, gain=2.0)
+    xb = wl.random_bits(87, f"sxb{shape}{dtype}", shape, dtype, gain=3.0)
+    xs = [xa, xb, xa, xb, xa]
+    dys = [wl.random_bits(87, f"sd{i}{shape}{dtype}", shape, dtype, gain=1.0 + i) for i in range(5)]
+    s0 = float(oracle.absmax_scale(xa, 8, dtype))
+    ss = [np.float32(s0 / d) for d in (1.0, 2.0, 3.5, 5.0, 9.0)]
+    xad, xbd = to_dev(xa, dtype), to_dev(xb, dtype)
+    xd = [xad, xbd, xad, xbd, xad]                                   # the same device tensors: same pointers
+    dyd = [to_dev(d, dtype) for d in dys]
+    sd = torch.tensor([float(s) for s in ss], dtype=torch.float32, device="cuda")
+    yd = [torch.empty_like(xad) for _ in range(5)]
+    dxd = [torch.empty_like(xad) if i != 2 else None for i in range(5)]  # one member of the group without dx
+    dsd = torch.full((5,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = B.new_workspace(B.sasq_fakequant_bwd_batch_workspace(5))
+    B.sasq_fakequant_fwd_batch([(xd[i], sd[i:i + 1], yd[i]) for i in range(5)], 8)
+    items = [(xd[i], dyd[i], sd[i:i + 1], dxd[i], dsd[i:i + 1]) for i in range(5)]
+    B.sasq_fakequant_bwd_batch(items, ws, 8)
+    ds1 = dsd.cpu().numpy().copy()
+    B.sasq_fakequant_bwd_batch(items, ws, 8)                          # same workspace again: tickets were reset
+    torch.cuda.synchronize()
+    assert np.array_equal(dsd.cpu().numpy(), ds1)
+    for i in range(5):
+        y_ref, _ = oracle.fakequant_fwd(xs[i], ss[i], 8, dtype)
+        ref = oracle.fakequant_bwd(xs[i], dys[i], ss[i], 8, dtype)
+        assert np.array_equal(wl.storage_bits_to_f32(to_bits(yd[i]), dtype), wl.storage_bits_to_f32(y_ref, dtype)), i
+        if dxd[i] is not None:
+            assert np.array_equal(wl.storage_bits_to_f32(to_bits(dxd[i]), dtype), wl.storage_bits_to_f32(ref["dx"], dtype)), i
+        tol = 1e-4 * abs(ref["ds64"]) + 1e-7 * ref["sum_abs"] + 1e-30
+        assert abs(float(ds1[i]) - ref["ds64"]) <= tol, (i, ds1[i], ref["ds64"])
