@@ -91,14 +91,71 @@ __device__ __forceinline__ int lin_item_of(const LinBatch& b, int block)
     return k;
 }
 
-template <int DT, bool PERM8>
-__global__ __launch_bounds__(256) void quantize_act_batch_kernel(const LinBatch b, int bits)
+// The activation pre-passes of a layer.  Projections that read the same X (q/k/v, gate/up: one
+// activation tensor, one factor each) form one entry: X is loaded once and quantized with every
+// member's factor into that member's staging buffer.
+constexpr int kMaxQuantShare = 3;
+struct QuantItem {
+    const void* x;
+    int M, K;
+    int ns;                                  // members
+    const float* s[kMaxQuantShare];
+    int8_t* xq[kMaxQuantShare];
+};
+struct QuantBatch {
+    QuantItem it[kMaxLinearBatch];
+    int first_block[kMaxLinearBatch + 1];
+    int count;
+};
+
+template <int DT, bool PERM8, int NS>
+__device__ __forceinline__ void quantize_act_shared_body(const QuantItem& it, int bits, int block, int nblocks)
 {
-    const int k = lin_item_of(b, (int)blockIdx.x);
-    const LinItem& it = b.it[k];
+    using S = Store16<DT>;
+    const u32x4* __restrict__ x = static_cast<const u32x4*>(it.x);
+    const int K = it.K;
+    const int64_t nvec = (int64_t)it.M * K / 8;
+    QConst k[NS];
+#pragma unroll
+    for (int j = 0; j < NS; ++j) k[j] = make_qconst(*it.s[j], bits);
+    const int kvec = K >> 3;                      // 8-element vectors per row
+    for (int64_t i = (int64_t)block * 256 + threadIdx.x; i < nvec; i += (int64_t)nblocks * 256) {
+        const u32x4 v = x[i];
+        const int64_t m = i / kvec;
+        const int k0 = (int)(i - m * kvec) << 3;
+        const int r = (int)(m & 15), ch = (k0 & 63) >> 4;
+        const int64_t blk = (m >> 4) * (K >> 6) + (k0 >> 6);
+        const int64_t off = blk * 1024 + ((4 * r + (ch ^ swz64(r))) << 4) + (k0 & 15);
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            float c[8];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                c[2 * w] = quantize(S::lo(v[w]), k[j]).c;
+                c[2 * w + 1] = quantize(S::hi(v[w]), k[j]).c;
+            }
+            u32x2 o;
+            if (PERM8) { o[0] = pack_codes4(c[0], c[2], c[4], c[6]); o[1] = pack_codes4(c[1], c[3], c[5], c[7]); }
+            else       { o[0] = pack_codes4(c[0], c[1], c[2], c[3]); o[1] = pack_codes4(c[4], c[5], c[6], c[7]); }
+            *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(it.xq[j]) + off) = o;
+        }
+    }
+}
+
+template <int DT, bool PERM8>
+__global__ __launch_bounds__(256) void quantize_act_batch_kernel(const QuantBatch b, int bits)
+{
+    int k = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxLinearBatch; ++i)
+        if (i < b.count && (int)blockIdx.x >= b.first_block[i]) k = i;
+    const QuantItem& it = b.it[k];
+    const int block = (int)blockIdx.x - b.first_block[k], nblocks = b.first_block[k + 1] - b.first_block[k];
+    if (it.ns == 2) { quantize_act_shared_body<DT, PERM8, 2>(it, bits, block, nblocks); return; }
+    if (it.ns == 3) { quantize_act_shared_body<DT, PERM8, 3>(it, bits, block, nblocks); return; }
     const int64_t n = (int64_t)it.M * it.K;
-    quantize_act_body<DT, PERM8, true>(static_cast<const u32x4*>(it.x), it.s, reinterpret_cast<u32x2*>(it.xq), n / 8, n, it.K, bits,
-                                       (int)blockIdx.x - b.first_block[k], b.first_block[k + 1] - b.first_block[k]);
+    quantize_act_body<DT, PERM8, true>(static_cast<const u32x4*>(it.x), it.s[0], reinterpret_cast<u32x2*>(it.xq[0]), n / 8, n, it.K, bits,
+                                       block, nblocks);
 }
 
 // Same pre-pass with one factor per group of `group` consecutive channels (Sec. 3, Eq. 3; Eq. 1
@@ -1185,13 +1242,10 @@ extern "C" int sasq_static_linear_batch(const sasq_linear_item* items, int count
     for (int i = 1; i < count; ++i)
         for (int j = i; j > 0 && items[order[j]].K > items[order[j - 1]].K; --j) { const int tmp = order[j]; order[j] = order[j - 1]; order[j - 1] = tmp; }
 
-    LinBatch q{}, g{};
+    LinBatch g{};
     char* ws = static_cast<char*>(workspace);
-    int64_t total_vec = 0;
-    for (int i = 0; i < count; ++i) total_vec += items[order[i]].M * items[order[i]].K / 8 + 1;
-    const int kQuantBlocks = 4096;
-    q.count = g.count = count;
-    q.first_block[0] = g.first_block[0] = 0;
+    g.count = count;
+    g.first_block[0] = 0;
     for (int i = 0; i < count; ++i) {
         const sasq_linear_item& src = items[order[i]];
         LinItem li;
@@ -1206,19 +1260,45 @@ extern "C" int sasq_static_linear_batch(const sasq_linear_item* items, int count
         li.M = (int)src.M; li.N = (int)src.N; li.K = (int)src.K;
         li.tiles_m = (int)((src.M + 255) / 256);
         li.tiles_n = (int)((src.N + 255) / 256);
-        q.it[i] = g.it[i] = li;
-        const int64_t nvec = src.M * src.K / 8;
-        int64_t share = ((nvec + 1) * kQuantBlocks + total_vec - 1) / total_vec;
+        g.it[i] = li;
+        g.first_block[i + 1] = g.first_block[i] + ((li.tiles_m * li.tiles_n + 7) / 8) * 8;
+    }
+    for (int i = count; i < kMaxLinearBatch; ++i) g.first_block[i + 1] = g.first_block[count];
+
+    // the pre-passes: projections on the same X (same pointer, M and K) share one entry
+    QuantBatch q{};
+    bool taken[kMaxLinearBatch] = {false};
+    int64_t total_vec = 0;
+    for (int i = 0; i < count; ++i) {
+        if (taken[i]) continue;
+        QuantItem& e = q.it[q.count++];
+        e.x = g.it[i].x;
+        e.M = g.it[i].M;
+        e.K = g.it[i].K;
+        e.ns = 0;
+        for (int j = i; j < count && e.ns < kMaxQuantShare; ++j) {
+            if (taken[j] || g.it[j].x != e.x || g.it[j].M != e.M || g.it[j].K != e.K) continue;
+            taken[j] = true;
+            e.s[e.ns] = g.it[j].s;
+            e.xq[e.ns] = g.it[j].xq;
+            ++e.ns;
+        }
+        total_vec += ((int64_t)e.M * e.K / 8 + 1) * e.ns;
+    }
+    const int kQuantBlocks = 4096;
+    q.first_block[0] = 0;
+    for (int i = 0; i < q.count; ++i) {
+        const int64_t nvec = (int64_t)q.it[i].M * q.it[i].K / 8;
+        int64_t share = ((nvec + 1) * q.it[i].ns * kQuantBlocks + total_vec - 1) / total_vec;
         const int64_t need = (nvec + 255) / 256;
         if (share > need) share = need;
         if (share < 1) share = 1;
         q.first_block[i + 1] = q.first_block[i] + (int)share;
-        g.first_block[i + 1] = g.first_block[i] + ((li.tiles_m * li.tiles_n + 7) / 8) * 8;
     }
-    for (int i = count; i < kMaxLinearBatch; ++i) { q.first_block[i + 1] = q.first_block[count]; g.first_block[i + 1] = g.first_block[count]; }
+    for (int i = q.count; i < kMaxLinearBatch; ++i) q.first_block[i + 1] = q.first_block[q.count];
 
     hipStream_t st = as_stream(stream);
-    const int qgrid = q.first_block[count], ggrid = g.first_block[count];
+    const int qgrid = q.first_block[q.count], ggrid = g.first_block[count];
     const bool perm8 = wf == SASQ_W_INT4_PACKED;      // row-major packed int4 unpacks in (0,2,4,6,1,3,5,7) order
 #define SASQ_LAUNCH_BATCH(DTV)                                                                                          \
     do {                                                                                                                \

@@ -225,9 +225,47 @@ def test_pc_batch_errors_and_layer_sizes():
         assert torch.equal(ds1, dsb[i]), i
 
 
+@pytest.fixture
+def force_sharing():
+    """The library groups operators on one x only from 12 M elements up; this lifts the threshold."""
+    import os
+    os.environ["SASQ_FAKEQUANT_SHARE"] = "3"
+    yield
+    os.environ.pop("SASQ_FAKEQUANT_SHARE", None)
+
+
+def test_batch_sharing_at_its_natural_size():
+    """Two operators on one 4096 x 4096 input (grouped by the library's own rule) and one on another:
+    against the single-tensor calls, bit for bit (ds within the reduction-order tolerance)."""
+    dtype = "f16"
+    g = torch.Generator(device="cuda").manual_seed(9)
+    xa = (torch.randn((4096, 4096), device="cuda", generator=g) * 2).to(TDT[dtype])
+    xb = (torch.randn((4096, 4096), device="cuda", generator=g) * 2).to(TDT[dtype])
+    xd = [xa, xb, xa]
+    dyd = [torch.randn((4096, 4096), device="cuda", generator=g).to(TDT[dtype]) for _ in range(3)]
+    sd = torch.tensor([0.05, 0.03, 0.011], dtype=torch.float32, device="cuda")
+    yb = [torch.empty_like(xa) for _ in range(3)]
+    dxb = [torch.empty_like(xa) for _ in range(3)]
+    dsb = torch.zeros(3, dtype=torch.float32, device="cuda")
+    ws = B.new_workspace(B.sasq_fakequant_bwd_batch_workspace(3))
+    B.sasq_fakequant_fwd_batch([(xd[i], sd[i:i + 1], yb[i]) for i in range(3)], 8)
+    B.sasq_fakequant_bwd_batch([(xd[i], dyd[i], sd[i:i + 1], dxb[i], dsb[i:i + 1]) for i in range(3)], ws, 8)
+    torch.cuda.synchronize()
+    ws1 = B.new_workspace(B.sasq_fakequant_bwd_workspace(4096, 4096))
+    for i in range(3):
+        y1, dx1 = torch.empty_like(xa), torch.empty_like(xa)
+        ds1 = torch.zeros(1, dtype=torch.float32, device="cuda")
+        B.sasq_fakequant_fwd(xd[i], sd[i:i + 1], y1, None, 8)
+        B.sasq_fakequant_bwd(xd[i], dyd[i], sd[i:i + 1], dx1, ds1, ws1, 8)
+        torch.cuda.synchronize()
+        assert torch.equal(y1.view(torch.int16), yb[i].view(torch.int16)), i
+        assert torch.equal(dx1.view(torch.int16), dxb[i].view(torch.int16)), i
+        assert rel_err(float(dsb[i].item()), float(ds1.item())) <= 1e-5, i
+
+
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("shape", [(3, 5), (64, 256), (257, 1031), (700, 4099)])
-def test_batch_operators_sharing_one_input(dtype, shape):
+def test_batch_operators_sharing_one_input(dtype, shape, force_sharing):
     """Five operators, three of them (not adjacent in the batch) on the same x with different factors,
     two on another x: the library reads a shared x once.  Everything must equal the single-tensor
     calls bit for bit (ds within the reduction-order tolerance) and the oracle."""
