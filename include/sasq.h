@@ -142,9 +142,10 @@ int sasq_fakequant_bwd_pc(const void* x, const void* dy, const float* s, void* d
  *           backward only.  Items must not overlap each other's outputs.
  *   workspace (backward)  >= sasq_fakequant_bwd_batch_workspace(count) bytes, initialised once
  *           with sasq_workspace_init; not shared with an overlapping call.
- * Items that name the same x (same pointer, same rows * cols; the operators in front of q/k/v or of
- * gate/up read one activation tensor, each with its own factor) may be run together, up to three at
- * a time, x being read from memory once for the group (large tensors only).  Outputs are unchanged.
+ * Forward items that name the same x (same pointer, same rows * cols; the operators in front of
+ * q/k/v or of gate/up read one activation tensor, each with its own factor) may be run together, up
+ * to three at a time, x being read from memory once for the group (large tensors only).  Outputs
+ * are unchanged.
  */
 typedef struct {
     const void* x;      /* [rows, cols] device, 16-bit `dt`                      */

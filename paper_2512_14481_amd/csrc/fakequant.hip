@@ -93,8 +93,8 @@ __global__ __launch_bounds__(kThreads) void fakequant_fwd_kernel(
 // Several tensors in one launch (the fake-quant operators of one decoder layer): the grid is cut
 // into one run of blocks per tensor, sized by the host in proportion to the tensor.
 constexpr int kMaxBatch = SASQ_MAX_BATCH;
-// Operators that read the same x (the fake-quant operators in front of q/k/v, or gate/up: one input,
-// one factor each) form one entry: its blocks load x once and apply every member's factor.
+// Forward operators that read the same x (the fake-quant operators in front of q/k/v, or gate/up:
+// one input, one factor each) form one entry: its blocks load x once and apply every member's factor.
 constexpr int kMaxShare = 3;
 struct FqBatchItem {
     const u32x4* x;
@@ -334,112 +334,16 @@ __global__ __launch_bounds__(kThreads) void fakequant_bwd_kernel(
 
 // Batched backward: tensor k uses ticket word k of the workspace header and its own run of
 // kMaxReduceBlocks partials.
-// Backward of NS operators on one x: x is loaded once; every member has its own dy, dx and ds.
-template <int DT, int NS>
-__device__ __forceinline__ void bwd_body_shared(const FqBatchItem& it, uint32_t* __restrict__ ws_head,
-                                                double* __restrict__ partials, int bits, int block, int nblocks)
-{
-    using S = Store16<DT>;
-    const u32x4* __restrict__ x = it.x;
-    const int64_t nvec = it.nvec, n = it.n;
-    QConst k[NS];
-    double acc[NS];
-#pragma unroll
-    for (int j = 0; j < NS; ++j) {
-        k[j] = make_qconst(*it.s[j], bits);
-        acc[j] = 0.0;
-    }
-    constexpr int kU = kUnroll;
-    constexpr int64_t kChunk = (int64_t)kThreads * kU;
-    const int64_t full_end = nvec / kChunk * kChunk;
-    for (int64_t base = (int64_t)block * kChunk; base < full_end; base += (int64_t)nblocks * kChunk) {
-        u32x4 xin[kU];
-#pragma unroll
-        for (int u = 0; u < kU; ++u) xin[u] = __builtin_nontemporal_load(&x[base + u * kThreads + threadIdx.x]);
-#pragma unroll
-        for (int j = 0; j < NS; ++j) {
-            u32x4 gin[kU];
-#pragma unroll
-            for (int u = 0; u < kU; ++u) gin[u] = __builtin_nontemporal_load(&it.dy[j][base + u * kThreads + threadIdx.x]);
-#pragma unroll
-            for (int u = 0; u < kU; ++u) {
-                u32x4 out;
-                acc[j] += (double)bwd_vec<DT>(xin[u], gin[u], k[j], out);
-                if (it.out[j]) __builtin_nontemporal_store(out, &it.out[j][base + u * kThreads + threadIdx.x]);
-            }
-        }
-    }
-    if (block == 0) {
-        for (int64_t i = full_end + threadIdx.x; i < nvec; i += kThreads) {
-            const u32x4 xin = x[i];
-#pragma unroll
-            for (int j = 0; j < NS; ++j) {
-                u32x4 out;
-                acc[j] += (double)bwd_vec<DT>(xin, it.dy[j][i], k[j], out);
-                if (it.out[j]) it.out[j][i] = out;
-            }
-        }
-        if (threadIdx.x < (unsigned)(n - nvec * 8)) {
-            const int64_t i = nvec * 8 + threadIdx.x;
-            const float xv = S::one(reinterpret_cast<const uint16_t*>(x)[i]);
-#pragma unroll
-            for (int j = 0; j < NS; ++j) {
-                const uint16_t g = reinterpret_cast<const uint16_t*>(it.dy[j])[i];
-                bool keep;
-                const float tt = ds_term(xv, S::one(g), k[j], keep);
-                acc[j] += (double)tt;
-                if (it.out[j]) reinterpret_cast<uint16_t*>(it.out[j])[i] = keep ? g : (uint16_t)0;
-            }
-        }
-    }
-    // Grid-wide part for all members at once: the NS partials go out together and the NS tickets
-    // are taken back to back (one store acknowledgement and one atomic round trip for the group,
-    // not one per member); then whoever arrived last for a member finishes that member.
-    __shared__ double wave_part[kMaxShare][kThreads / kWave];
-    __shared__ bool is_last[kMaxShare];
-    const int lane = threadIdx.x % kWave, wid = threadIdx.x / kWave;
-#pragma unroll
-    for (int j = 0; j < NS; ++j) {
-        const double w = wave_sum(acc[j]);
-        if (lane == 0) wave_part[j][wid] = w;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-#pragma unroll
-        for (int j = 0; j < NS; ++j) {
-            double bsum = 0.0;
-#pragma unroll
-            for (int i = 0; i < kThreads / kWave; ++i) bsum += wave_part[j][i];
-            __hip_atomic_store(&partials[it.slot[j] * kMaxReduceBlocks + block], bsum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the write-through stores are acknowledged before any ticket
-        uint32_t ticket[NS];
-#pragma unroll
-        for (int j = 0; j < NS; ++j)
-            ticket[j] = __hip_atomic_fetch_add(ws_head + it.slot[j], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-        for (int j = 0; j < NS; ++j) {
-            is_last[j] = (ticket[j] == kTicketBase + (uint32_t)nblocks - 1);
-            if (ticket[j] - kTicketBase >= (uint32_t)nblocks) *it.ds[j] = __uint_as_float(0x7FC00000u);   // uninitialised workspace
-        }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < NS; ++j) {
-        if (is_last[j]) final_reduce(it.ds[j], ws_head + it.slot[j], partials + it.slot[j] * kMaxReduceBlocks, nblocks);
-        __syncthreads();      // final_reduce's LDS words are reused by the next member
-    }
-}
-
-template <int DT, bool SHARED>
+// Batched backward: every entry is one operator (sharing the read of x did not pay here: the
+// fused body needs 200 registers and ran 2 % slower than the operators apart); it uses the ticket
+// word and the run of kMaxReduceBlocks partials of its index in the caller's batch.
+template <int DT>
 __global__ __launch_bounds__(kThreads) void fakequant_bwd_batch_kernel(
     const FqBatch b, uint32_t* __restrict__ ws_head, double* __restrict__ partials, int bits)
 {
     const int k = batch_item_of(b, (int)blockIdx.x);
     const FqBatchItem& it = b.it[k];
     const int block = (int)blockIdx.x - b.first_block[k], nblocks = b.first_block[k + 1] - b.first_block[k];
-    if (SHARED && it.ns == 2) { bwd_body_shared<DT, 2>(it, ws_head, partials, bits, block, nblocks); return; }
-    if (SHARED && it.ns == 3) { bwd_body_shared<DT, 3>(it, ws_head, partials, bits, block, nblocks); return; }
     uint32_t* ticket = ws_head + it.slot[0];
     double* parts = partials + it.slot[0] * kMaxReduceBlocks;
     if (it.out[0]) bwd_body<DT, true>(it.x, it.dy[0], it.s[0], it.out[0], it.ds[0], ticket, parts, it.nvec, it.n, bits, block, nblocks);
@@ -611,17 +515,17 @@ static int check_items(const sasq_fq_item* items, int count, bool backward)
 // Items [lo, hi) as one launch: `total_blocks` cut into one run per tensor, proportional to its
 // size, at least one block and at most `max_per_item` each.  A tensor keeps its index in the batch
 // (it selects the tensor's ticket word and partials).
-static void build_launch(const sasq_fq_item* items, int lo, int hi, int total_blocks, int max_per_item, FqBatch& b)
+static void build_launch(const sasq_fq_item* items, int lo, int hi, int total_blocks, int max_per_item, bool share, FqBatch& b)
 {
     // entries: operators on the same x (same pointer, same size) share one, up to kMaxShare members
     // (SASQ_FAKEQUANT_SHARE=1|2|3 overrides the limit and lifts the size threshold: a tuning and test aid).  A group's run of blocks is
     // capped like a single tensor's, so members are only added while the group still gets all the
     // blocks its members would have had apart.
-    int max_share = kMaxShare;
+    int max_share = share ? kMaxShare : 1;
     int64_t min_elements = kShareMinElements;
     if (const char* e = getenv("SASQ_FAKEQUANT_SHARE")) {
         const int v = atoi(e);
-        if (v >= 1 && v <= kMaxShare) { max_share = v; min_elements = 0; }
+        if (share && v >= 1 && v <= kMaxShare) { max_share = v; min_elements = 0; }
     }
     int64_t all_vec = 0;
     for (int i = lo; i < hi; ++i) all_vec += items[i].rows * items[i].cols / 8 + 1;
@@ -695,7 +599,7 @@ extern "C" int sasq_fakequant_fwd_batch(const sasq_fq_item* items, int count, in
     for (int lo = 0; lo < count;) {
         const int hi = launch_end(items, lo, count);
         FqBatch b{};
-        build_launch(items, lo, hi, kBatchFwdBlocks, kBatchFwdBlocks, b);
+        build_launch(items, lo, hi, kBatchFwdBlocks, kBatchFwdBlocks, true, b);
         const int grid = b.first_block[b.count];
         hipStream_t st = as_stream(stream);
         if (any_shared(b)) {
@@ -731,16 +635,11 @@ extern "C" int sasq_fakequant_bwd_batch(const sasq_fq_item* items, int count, in
         const int hi = launch_end(items, lo, count);
         FqBatch b{};
         // a tensor alone in its launch gets what the single-tensor call gives it: one block per CU
-        build_launch(items, lo, hi, hi - lo == 1 ? kMaxReduceBlocks : kBatchBwdBlocks, kMaxReduceBlocks, b);
+        build_launch(items, lo, hi, hi - lo == 1 ? kMaxReduceBlocks : kBatchBwdBlocks, kMaxReduceBlocks, false, b);
         const int grid = b.first_block[b.count];
         hipStream_t st = as_stream(stream);
-        if (any_shared(b)) {
-            if (dt == SASQ_F16) fakequant_bwd_batch_kernel<SASQ_F16, true><<<grid, kThreads, 0, st>>>(b, head, parts, bits);
-            else                fakequant_bwd_batch_kernel<SASQ_BF16, true><<<grid, kThreads, 0, st>>>(b, head, parts, bits);
-        } else {
-            if (dt == SASQ_F16) fakequant_bwd_batch_kernel<SASQ_F16, false><<<grid, kThreads, 0, st>>>(b, head, parts, bits);
-            else                fakequant_bwd_batch_kernel<SASQ_BF16, false><<<grid, kThreads, 0, st>>>(b, head, parts, bits);
-        }
+        if (dt == SASQ_F16) fakequant_bwd_batch_kernel<SASQ_F16><<<grid, kThreads, 0, st>>>(b, head, parts, bits);
+        else                fakequant_bwd_batch_kernel<SASQ_BF16><<<grid, kThreads, 0, st>>>(b, head, parts, bits);
         lo = hi;
     }
     return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
