@@ -34,7 +34,7 @@ INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8, published
 F16_MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense fp16 / bf16, published
 # what a register-only v_mfma_i32_32x32x32_i8 loop sustains on this part with GEMM-like operand codes (the part is
 # power-limited under MFMA load; profiles/mfma_peak_and_clock.txt) -- context for `frac`, not the roofline's peak
-INT8_MFMA_SUSTAINED_TOPS = 3750.0
+INT8_MFMA_SUSTAINED_TOPS = 3700.0    # 3613-3750 across boxes (python bench.py --mfma-peak)
 # HBM-side bytes per sasq_static_linear call (both kernels), averaged over gate/up/down of config 3:
 # rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a plain 1 GiB copy), see
 # profiles/bench_c3_mlp7b_counters.txt.  Algorithmic bytes are 221.2 MB.
@@ -185,6 +185,29 @@ def cpu_baseline(cfg, rows: int):
                       f"(fake-quant fwd+bwd, SGD, static linear); {t_total:.1f} s"}
 
 
+def mfma_peak():
+    """What the part's matrix units sustain on their own (register-only loop, GEMM register pattern),
+    per operand pattern: TOP/s of each of 80 back-to-back launches (about 0.5 s of load per pattern)."""
+    sink = torch.empty(65536, dtype=torch.int32, device="cuda")
+    iters, launches = 20000, 80
+    out = {"metric": "register-only MFMA loop, sustained", "unit": "TOP/s (TFLOP/s for f16)", "iters_per_launch": iters,
+           "launches": launches, "patterns": {}}
+    for kind, name, ops in ((0, "i8 zeros", 65536.0), (1, "i8 random bits", 65536.0), (2, "i8 GEMM-like codes", 65536.0),
+                            (3, "f16 small random values", 32768.0)):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(launches + 1)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for l in range(launches):
+            B.sasq_mfma_probe(kind, iters, sink)
+            ev[l + 1].record()
+        torch.cuda.synchronize()
+        tops = [1024.0 * iters * 16 * ops / (ev[l].elapsed_time(ev[l + 1]) * 1e-3) / 1e12 for l in range(launches)]
+        settled = sorted(tops[launches // 2:])
+        out["patterns"][name] = {"first_launches": [round(v) for v in tops[:4]], "settled_median": round(settled[len(settled) // 2]),
+                                 "settled_min": round(settled[0]), "settled_max": round(settled[-1])}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -195,6 +218,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--unbatched", action="store_true",
                     help="one launch per tensor for the fake-quant operators instead of one per layer")
+    ap.add_argument("--mfma-peak", action="store_true",
+                    help="instead of the workload: time the library's register-only MFMA loop under sustained load "
+                         "(80 back-to-back launches per operand pattern) and print what the matrix units sustain")
     ap.add_argument("--calib", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     a = ap.parse_args()
@@ -203,6 +229,10 @@ def main():
                  "one tiny all-gather for ds, but nothing multi-GPU is implemented)")
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if a.mfma_peak:
+        torch.cuda.set_device(0)
+        mfma_peak()
+        return
 
     cfg = wl.CONFIGS[a.config]
     ws_small = B.new_workspace(max(B.sasq_absmax_scale_workspace(1, 1), B.sasq_fakequant_bwd_workspace(1, 1)))
