@@ -479,3 +479,22 @@ def test_scale_adamw():
             assert np.allclose(vd.cpu().numpy(), v, rtol=2e-6, atol=1e-30)
             # keep both sides on the same state so that differences do not accumulate
             pd.copy_(torch.from_numpy(p)); md.copy_(torch.from_numpy(m)); vd.copy_(torch.from_numpy(v))
+
+
+def test_mfma_probe_runs_and_validates():
+    """The diagnostic MFMA loop the benchmark times: runs, writes its sink, rejects bad arguments."""
+    sink = torch.full((65536,), 7, dtype=torch.int32, device="cuda")
+    B.sasq_mfma_probe(0, 3, sink)                          # zero operands: every accumulator stays zero
+    torch.cuda.synchronize()
+    assert int(sink.abs().max()) == 0
+    for kind in (1, 2, 3):
+        B.sasq_mfma_probe(kind, 2, sink)
+    torch.cuda.synchronize()
+    # kind 2, 2 iterations: each accumulator element is 2 * sum_k a*b with |a| <= 1, |b| <= 32 over 32 k: bounded
+    B.sasq_mfma_probe(2, 2, sink)
+    torch.cuda.synchronize()
+    assert int(sink.abs().max()) <= 2 * 32 * 32 * 256
+    with pytest.raises(B.SasqError):
+        B.sasq_mfma_probe(9, 2, sink)
+    with pytest.raises(B.SasqError):
+        B.sasq_mfma_probe(0, 0, sink)
