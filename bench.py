@@ -39,7 +39,7 @@ INT8_MFMA_SUSTAINED_TOPS = 3700.0    # 3613-3750 across boxes (python bench.py -
 # rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a plain 1 GiB copy), see
 # profiles/bench_c3_mlp7b_counters.txt.  Algorithmic bytes are 221.2 MB.
 C3_LINEAR_TRAFFIC_BYTES = 450654 * 1024          # one call per projection, average
-C3_LINEAR_BATCH_TRAFFIC_BYTES = 1362638 * 1024   # the batched call (all three projections)
+C3_LINEAR_BATCH_TRAFFIC_BYTES = 1364068 * 1024   # the batched call (all three projections)
 HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published
 LR = 2e-4
 TDT = {"f16": torch.float16, "bf16": torch.bfloat16}
