@@ -130,6 +130,35 @@ def test_linear_batch_matches_oracle(batch, dtype, fmt, blocked):
         assert_same_values(to_bits(it[5]), refs[j], dtype, f"Y of item {j}")
 
 
+@pytest.mark.parametrize("blocked", [False, True])
+@pytest.mark.parametrize("dtype,fmt", [("f16", "int8"), ("bf16", "int4")])
+def test_linear_batch_with_projections_sharing_inputs(dtype, fmt, blocked):
+    """q/k/v-like and gate/up-like projections on shared activation tensors (the pre-pass reads a
+    shared X once and stages one code buffer per projection), interleaved with one on its own X;
+    ragged M; every weight format (row-major int4 stores its codes in the permuted K order)."""
+    wf = WF[(fmt, blocked)]
+    M = 70
+    xa = wl.random_bits(93, f"sha{dtype}", (M, 256), dtype, gain=2.0)
+    xb = wl.random_bits(93, f"shb{dtype}", (M, 128), dtype, gain=2.0)
+    xc = wl.random_bits(93, f"shc{dtype}", (M, 256), dtype, gain=2.0)
+    dev = {"a": to_dev(xa, dtype), "b": to_dev(xb, dtype), "c": to_dev(xc, dtype)}
+    bits = {"a": xa, "b": xb, "c": xc}
+    plan = [("a", 96), ("b", 40), ("a", 33), ("c", 64), ("b", 300), ("a", 128)]      # (input, N): a x3, b x2, c alone
+    items, refs = [], []
+    for j, (name, N) in enumerate(plan):
+        K = bits[name].shape[1]
+        wq, s_w = oracle.quantize_weight(wl.random_f32(93, f"shw{j}", (N, K), 0.02), fmt)
+        s = np.float32(oracle.absmax_scale(bits[name], 8, dtype) / (2 + j))          # a different factor per projection
+        refs.append(oracle.static_linear(bits[name], s, wq, s_w, None, 8, fmt, dtype, want_acc=False, want_xq=False)["y"])
+        y = torch.full((M, N), float("nan"), dtype=TDT[dtype], device="cuda")
+        items.append((dev[name], dev_scalar(s), device_weights(wq, fmt, blocked), torch.from_numpy(s_w).cuda(), None, y))
+    ws = B.new_workspace(B.sasq_static_linear_batch_workspace(items, wf))
+    B.sasq_static_linear_batch(items, wf, ws)
+    torch.cuda.synchronize()
+    for j, it in enumerate(items):
+        assert_same_values(to_bits(it[5]), refs[j], dtype, f"Y of item {j} ({plan[j]})")
+
+
 def test_linear_batch_rejects():
     x = torch.zeros((4, 96), dtype=torch.float16, device="cuda")
     y = torch.zeros((4, 4), dtype=torch.float16, device="cuda")
