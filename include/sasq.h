@@ -112,6 +112,23 @@ int sasq_fakequant_bwd(const void* x, const void* dy, const float* s, void* dx, 
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * sasq_fakequant_bwd for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs,
+ * outputs, arithmetic and reduction order as sasq_fakequant_bwd (results are bit-identical); the
+ * ticket word and the 256 fp64 block partials (3 KB) live in a device array that is part of the
+ * library image instead of a caller workspace.  The call allocates nothing and frees nothing.
+ *   - Each GPU holds one copy of that array for the life of the process; every call on a GPU uses
+ *     it, so two calls that can overlap in time on one GPU (different streams) race: serialise them.
+ *   - rows * cols above SASQ_FAKEQUANT_BWD_STATIC_MAX_ELEMENTS is rejected with SASQ_ERR_SHAPE.
+ *   - The first call on a device looks the array's address up (no allocation); make that call
+ *     outside graph capture.  A failed lookup returns SASQ_ERR_WORKSPACE.
+ *   - Two kernels are enqueued: a one-thread clear of the ticket word, then the backward kernel.
+ */
+#define SASQ_FAKEQUANT_BWD_STATIC_MAX_ELEMENTS (INT64_C(1) << 40)
+int sasq_fakequant_bwd_static(const void* x, const void* dy, const float* s, void* dx, float* ds,
+                              int64_t rows, int64_t cols, int bits, sasq_dtype dt, void* stream);
+
+/*
  * Per-channel variants of the fake-quant operator: one learned factor per activation channel
  * (column), the granularity of the paper's main experiments (Sec. 4; Sec. 5.1 "Implementation";
  * Sec. 2, Fig. 2(b)).  Same element arithmetic as above with s = s[k] for column k;

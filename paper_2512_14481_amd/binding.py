@@ -61,6 +61,7 @@ def _lib() -> ctypes.CDLL:
         L.sasq_fakequant_bwd_workspace.restype = sz
         L.sasq_fakequant_bwd_workspace.argtypes = [i64, i64]
         L.sasq_fakequant_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, sz, vp]
+        L.sasq_fakequant_bwd_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, vp]
         L.sasq_scale_sgd.argtypes = [vp, vp, f32, vp]
         L.sasq_scale_sgd_vec.argtypes = [vp, vp, i64, f32, vp]
         L.sasq_fakequant_fwd_batch.argtypes = [ctypes.POINTER(_FqItem), i32, i32, i32, vp]
@@ -171,6 +172,16 @@ def sasq_fakequant_bwd(x: torch.Tensor, dy: torch.Tensor, s: torch.Tensor, dx: O
     _check(_lib().sasq_fakequant_bwd(_ptr(x), _ptr(dy), _ptr(s), _ptr(dx), _ptr(ds), rows, cols, bits, _dt(x),
                                      _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
            "sasq_fakequant_bwd")
+
+
+def sasq_fakequant_bwd_static(x: torch.Tensor, dy: torch.Tensor, s: torch.Tensor, dx: Optional[torch.Tensor],
+                              ds: torch.Tensor, bits: int = 8) -> None:
+    _want(s, torch.float32, "s"); _want(ds, torch.float32, "ds")
+    if dy.dtype != x.dtype or dy.shape != x.shape or (dx is not None and (dx.dtype != x.dtype or dx.shape != x.shape)):
+        raise ValueError("dy and dx must match x")
+    rows, cols = x.shape[0], x.numel() // max(x.shape[0], 1)
+    _check(_lib().sasq_fakequant_bwd_static(_ptr(x), _ptr(dy), _ptr(s), _ptr(dx), _ptr(ds), rows, cols, bits, _dt(x),
+                                            _stream()), "sasq_fakequant_bwd_static")
 
 
 def sasq_fakequant_fwd_pc(x: torch.Tensor, s: torch.Tensor, y: torch.Tensor,

@@ -9,6 +9,7 @@
 #include "sasq_device.h"
 #include <cstdlib>
 #include <cmath>
+#include <mutex>
 
 namespace sasq {
 
@@ -452,6 +453,73 @@ extern "C" int sasq_fakequant_bwd(const void* x, const void* dy, const float* s,
     auto DX = static_cast<u32x4*>(dx);
     auto head = static_cast<uint32_t*>(workspace);
     auto parts = reinterpret_cast<double*>(static_cast<char*>(workspace) + kWsHeaderBytes);
+    if (dt == SASQ_F16) {
+        if (dx) fakequant_bwd_kernel<SASQ_F16, true><<<grid, kThreads, 0, st>>>(X, G, s, DX, ds, head, parts, nvec, n, bits);
+        else    fakequant_bwd_kernel<SASQ_F16, false><<<grid, kThreads, 0, st>>>(X, G, s, DX, ds, head, parts, nvec, n, bits);
+    } else {
+        if (dx) fakequant_bwd_kernel<SASQ_BF16, true><<<grid, kThreads, 0, st>>>(X, G, s, DX, ds, head, parts, nvec, n, bits);
+        else    fakequant_bwd_kernel<SASQ_BF16, false><<<grid, kThreads, 0, st>>>(X, G, s, DX, ds, head, parts, nvec, n, bits);
+    }
+    return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+}
+
+// ---- backward without a workspace argument and without any allocation ----------------------------
+// For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+// loops, harnesses that forbid it): the ticket word and the block partials live in a file-scope
+// device array instead of a caller-provided workspace.  Each GPU holds its own copy of the array
+// at its own address; the address is looked up once per device and cached.  In host code the
+// array's name is only a handle for that lookup, never a device address.
+namespace sasq {
+
+constexpr size_t kStaticScratchBytes = kWsHeaderBytes + sizeof(double) * kMaxReduceBlocks;   // 3 KB
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];          // per device: where `scratch` lives on that GPU
+
+// Address of this device's copy of `scratch` (nullptr on failure).  No allocation.
+static void* scratch_of_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+
+// The ticket word must be zero when the backward kernel starts.  (A fill kernel, not a memset:
+// memset nodes recorded into a captured graph are avoided on purpose.)
+__global__ void clear_ticket_kernel(uint32_t* head) { if (threadIdx.x == 0) head[0] = kTicketBase; }
+
+}  // namespace sasq
+
+extern "C" int sasq_fakequant_bwd_static(const void* x, const void* dy, const float* s, void* dx, float* ds,
+                                         int64_t rows, int64_t cols, int bits, sasq_dtype dt, void* stream)
+{
+    if (!x || !dy || !s || !ds) return SASQ_ERR_NULL;
+    int rc = check_shape(rows, cols, bits, (int)dt);
+    if (rc) return rc;
+    if (rows * cols > SASQ_FAKEQUANT_BWD_STATIC_MAX_ELEMENTS) return SASQ_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(dy) || (dx && !aligned16(dx))) return SASQ_ERR_ALIGN;
+    void* base = scratch_of_current_device();
+    if (!base) return SASQ_ERR_WORKSPACE;
+    const int64_t n = rows * cols, nvec = n / 8;
+    const int grid = grid_for(nvec, kMaxReduceBlocks);
+    hipStream_t st = as_stream(stream);
+    auto X = static_cast<const u32x4*>(x);
+    auto G = static_cast<const u32x4*>(dy);
+    auto DX = static_cast<u32x4*>(dx);
+    auto head = static_cast<uint32_t*>(base);
+    auto parts = reinterpret_cast<double*>(static_cast<char*>(base) + kWsHeaderBytes);
+    clear_ticket_kernel<<<1, 64, 0, st>>>(head);
     if (dt == SASQ_F16) {
         if (dx) fakequant_bwd_kernel<SASQ_F16, true><<<grid, kThreads, 0, st>>>(X, G, s, DX, ds, head, parts, nvec, n, bits);
         else    fakequant_bwd_kernel<SASQ_F16, false><<<grid, kThreads, 0, st>>>(X, G, s, DX, ds, head, parts, nvec, n, bits);
