@@ -33,16 +33,29 @@ def stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(verbose: bool = True) -> str:
+def build(verbose: bool = True, incremental: bool = False) -> str:
     """Compile every source to an object file (in parallel: the GEMM file alone takes two minutes),
-    then link.  Objects live in a temporary directory; only libsasq.so stays in the tree."""
+    then link.  Objects live in a temporary directory; only libsasq.so stays in the tree.
+    incremental=True (a developer's shortcut, `python -m paper_2512_14481_amd.build -i`) keeps the
+    objects in _build/ at the repository root and recompiles only sources newer than their object
+    (every source after a header change)."""
     import concurrent.futures
+    import contextlib
     import tempfile
 
     compile_flags = [f for f in FLAGS if f != "-shared"]
-    with tempfile.TemporaryDirectory(prefix="sasq_build_") as tmp:
+    headers = glob.glob(os.path.join(CSRC, "*.h")) + [os.path.join(ROOT, "include", "sasq.h")]
+    if incremental:
+        keep = os.path.join(ROOT, "_build")
+        os.makedirs(keep, exist_ok=True)
+        tmp_ctx = contextlib.nullcontext(keep)
+    else:
+        tmp_ctx = tempfile.TemporaryDirectory(prefix="sasq_build_")
+    with tmp_ctx as tmp:
         def compile_one(src: str) -> str:
             obj = os.path.join(tmp, os.path.basename(src) + ".o")
+            if incremental and os.path.exists(obj) and all(os.path.getmtime(d) <= os.path.getmtime(obj) for d in [src] + headers):
+                return obj
             cmd = [HIPCC] + compile_flags + ["-c", src, "-o", obj]
             if verbose:
                 print(" ".join(cmd), flush=True)
@@ -61,5 +74,5 @@ def build(verbose: bool = True) -> str:
 
 
 if __name__ == "__main__":
-    build()
+    build(incremental="-i" in sys.argv[1:])
     sys.exit(0)
