@@ -71,6 +71,23 @@ const char* sasq_status_string(int status);
 int sasq_version(void);
 
 /*
+ * Test and tuning aid, not part of the method: force one of the library's kernel variants instead
+ * of the choice the library makes from the shapes.  Every variant of a call computes the same
+ * results bit for bit; the parity tests use this to cover each of them, the benchmark to compare
+ * them.  The setting is process-wide and not thread-safe; value 0 restores the library's choice.
+ * Unknown knob or value: SASQ_ERR_UNSUPPORTED.  The library reads no environment variables.
+ */
+typedef enum {
+    SASQ_TUNE_LINEAR_PATH = 0,   /* 1: separate activation-quantize pass, 2: quantize on load          */
+    SASQ_TUNE_LINEAR_TILE = 1,   /* 1: 256x256, 2: 128x256, 3: 128x128 workgroup tiles                  */
+    SASQ_TUNE_LINEAR_MFMA = 2,   /* 1: 32x32x32 int8 MFMA kernel, 2: 16x16x64 (where it exists)         */
+    SASQ_TUNE_FQ_SHARE = 3,      /* 1..3: forward operators per group sharing one read of x, any size   */
+    SASQ_TUNE_BWD_TILE = 4,      /* backward GEMM: 1: 256x256, 2: 128x128 tiles                         */
+    SASQ_TUNE_COUNT = 5
+} sasq_tune_knob;
+int sasq_set_tuning(int knob, int value);
+
+/*
  * Prepare a workspace for use by the calls below (zero-fills its control words, the first
  * 1024 bytes or the whole workspace if smaller, on `stream`).  Call once per workspace
  * allocation, before the first call that uses it.  Minimum size 256 bytes.

@@ -56,6 +56,7 @@ def _lib() -> ctypes.CDLL:
         L.sasq_status_string.restype = ctypes.c_char_p
         L.sasq_status_string.argtypes = [i32]
         L.sasq_version.restype = i32
+        L.sasq_set_tuning.argtypes = [i32, i32]
         L.sasq_workspace_init.argtypes = [vp, sz, vp]
         L.sasq_fakequant_fwd.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp]
         L.sasq_fakequant_bwd_workspace.restype = sz
@@ -135,6 +136,13 @@ def _dt(t: torch.Tensor) -> int:
 
 def sasq_version() -> int:
     return int(_lib().sasq_version())
+
+
+SASQ_TUNE_LINEAR_PATH, SASQ_TUNE_LINEAR_TILE, SASQ_TUNE_LINEAR_MFMA, SASQ_TUNE_FQ_SHARE, SASQ_TUNE_BWD_TILE = range(5)
+
+
+def sasq_set_tuning(knob: int, value: int) -> None:
+    _check(_lib().sasq_set_tuning(knob, value), "sasq_set_tuning")
 
 
 def sasq_workspace_init(workspace: torch.Tensor) -> None:

@@ -586,13 +586,12 @@ static int check_items(const sasq_fq_item* items, int count, bool backward)
 static void build_launch(const sasq_fq_item* items, int lo, int hi, int total_blocks, int max_per_item, bool share, FqBatch& b)
 {
     // entries: operators on the same x (same pointer, same size) share one, up to kMaxShare members
-    // (SASQ_FAKEQUANT_SHARE=1|2|3 overrides the limit and lifts the size threshold: a tuning and test aid).  A group's run of blocks is
+    // (sasq_set_tuning(SASQ_TUNE_FQ_SHARE, 1|2|3) overrides the limit and lifts the size threshold).  A group's run of blocks is
     // capped like a single tensor's, so members are only added while the group still gets all the
     // blocks its members would have had apart.
     int max_share = share ? kMaxShare : 1;
     int64_t min_elements = kShareMinElements;
-    if (const char* e = getenv("SASQ_FAKEQUANT_SHARE")) {
-        const int v = atoi(e);
+    if (const int v = tuning(SASQ_TUNE_FQ_SHARE)) {
         if (share && v >= 1 && v <= kMaxShare) { max_share = v; min_elements = 0; }
     }
     int64_t all_vec = 0;

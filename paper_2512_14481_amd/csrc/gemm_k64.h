@@ -1,0 +1,24 @@
+// Host-side interface of the 16x16x64 int8 GEMM kernels (static_linear_k64.hip), used by the entry
+// points in static_linear.hip.
+#pragma once
+
+#include "gemm_tile.h"
+
+namespace sasq {
+
+struct GemmK64Args {
+    const int8_t* xq;        // staged activation codes (1 KB blocks of 16 rows x 64 K-bytes)
+    const uint8_t* wq;       // int8 weights, row-major or pre-arranged
+    const float* s;          // activation factor (one, or one per row with `rows`)
+    const float* s_w;
+    const float* bias;
+    uint16_t* y;
+    int32_t* acc_out;
+    int64_t M, N, K;
+};
+
+// tile: 0 = 256x256, 1 = 128x256, 2 = 128x128 (two workgroups per CU).  K must be a multiple of 64.
+void launch_gemm_k64(const GemmK64Args& a, sasq_dtype dt, bool blocked, int tile, bool rows, hipStream_t st);
+void launch_gemm_k64_batch(const LinBatch& b, int grid, sasq_dtype dt, bool blocked, hipStream_t st);
+
+}  // namespace sasq

@@ -56,4 +56,31 @@ __device__ __forceinline__ bool tile_of_block(int bid, int tiles_m, int tiles_n,
     return true;
 }
 
+// The projections of one layer in one launch (their activation pre-passes and their GEMMs).
+constexpr int kMaxLinearBatch = SASQ_MAX_BATCH;
+struct LinItem {
+    const void* x;          // 16-bit activations
+    int8_t* xq;             // staged codes (workspace)
+    const float* s;
+    const uint8_t* wq;
+    const float* s_w;
+    const float* bias;
+    uint16_t* y;
+    int M, N, K, tiles_m, tiles_n;
+};
+struct LinBatch {
+    LinItem it[kMaxLinearBatch];
+    int first_block[kMaxLinearBatch + 1];
+    int count;
+};
+
+__device__ __forceinline__ int lin_item_of(const LinBatch& b, int block)
+{
+    int k = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxLinearBatch; ++i)
+        if (i < b.count && block >= b.first_block[i]) k = i;
+    return k;
+}
+
 }  // namespace sasq

@@ -302,12 +302,11 @@ static void launch_bwd(const void* dy, const void* wt, void* dx, float* acc_out,
 }
 
 // 256x256 tiles unless they would leave most of the 256 CUs idle for a round; then 128x128
-// (two workgroups per CU).  Overridable with SASQ_LINEAR_BWD_TILE=256|128 (tuning aid).
+// (two workgroups per CU).  sasq_set_tuning(SASQ_TUNE_BWD_TILE, 1 | 2) forces one of them.
 static bool bwd_small_tiles(int64_t M, int64_t K)
 {
-    const char* e = getenv("SASQ_LINEAR_BWD_TILE");
-    if (e && !strcmp(e, "256")) return false;
-    if (e && !strcmp(e, "128")) return true;
+    if (tuning(SASQ_TUNE_BWD_TILE) == 1) return false;
+    if (tuning(SASQ_TUNE_BWD_TILE) == 2) return true;
     const int64_t t256 = ((M + 255) / 256) * ((K + 255) / 256), t128 = ((M + 127) / 128) * ((K + 127) / 128);
     const double c256 = (double)((t256 + 255) / 256), c128 = (double)((t128 + 511) / 512) * 0.5 * 1.42;
     return c128 < c256;

@@ -185,7 +185,17 @@ extern "C" const char* sasq_status_string(int status)
     }
 }
 
-extern "C" int sasq_version(void) { return 100; }
+extern "C" int sasq_version(void) { return 200; }
+
+namespace sasq { int g_tuning[SASQ_TUNE_COUNT] = {0}; }
+
+extern "C" int sasq_set_tuning(int knob, int value)
+{
+    static const int kMax[SASQ_TUNE_COUNT] = {2, 3, 2, 3, 2};
+    if (knob < 0 || knob >= SASQ_TUNE_COUNT || value < 0 || value > kMax[knob]) return SASQ_ERR_UNSUPPORTED;
+    sasq::g_tuning[knob] = value;
+    return SASQ_OK;
+}
 
 extern "C" int sasq_workspace_init(void* workspace, size_t workspace_bytes, void* stream)
 {

@@ -134,6 +134,10 @@ constexpr size_t kWsHeaderBytes = 1024;
 constexpr size_t kWsMinBytes = 256;
 constexpr uint32_t kTicketBase = 0;
 
+// Kernel-variant overrides set through sasq_set_tuning (a test and tuning aid; 0 = choose by shape).
+extern int g_tuning[SASQ_TUNE_COUNT];
+inline int tuning(int knob) { return g_tuning[knob]; }
+
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

@@ -2,6 +2,7 @@
 // fixed scale, int8 MFMA GEMM against frozen per-output-channel weights, dequantizing epilogue.
 #include "sasq_device.h"
 #include "gemm_tile.h"
+#include "gemm_k64.h"
 #include <cstdlib>
 #include <cstring>
 #include <type_traits>
@@ -62,33 +63,6 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(
     int64_t nvec, int64_t n, int K, int bits)
 {
     quantize_act_body<DT, PERM8, TILED>(x, s_ptr, xq, nvec, n, K, bits, (int)blockIdx.x, (int)gridDim.x);
-}
-
-// The projections of one layer in one launch (their activation pre-passes, and below their GEMMs).
-constexpr int kMaxLinearBatch = SASQ_MAX_BATCH;
-struct LinItem {
-    const void* x;          // 16-bit activations
-    int8_t* xq;             // staged codes (workspace)
-    const float* s;
-    const uint8_t* wq;
-    const float* s_w;
-    const float* bias;
-    uint16_t* y;
-    int M, N, K, tiles_m, tiles_n;
-};
-struct LinBatch {
-    LinItem it[kMaxLinearBatch];
-    int first_block[kMaxLinearBatch + 1];
-    int count;
-};
-
-__device__ __forceinline__ int lin_item_of(const LinBatch& b, int block)
-{
-    int k = 0;
-#pragma unroll
-    for (int i = 1; i < kMaxLinearBatch; ++i)
-        if (i < b.count && block >= b.first_block[i]) k = i;
-    return k;
 }
 
 // The activation pre-passes of a layer.  Projections that read the same X (q/k/v, gate/up: one
@@ -905,15 +879,8 @@ void linear_mfma_batch_kernel(const LinBatch b, int a_bits)
 static size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Which activation path the MFMA kernel takes: 0 = by shape, 1 = separate quantize pass,
-// 2 = quantize-on-load.  Overridable with SASQ_STATIC_LINEAR_PATH=twopass|fused (tuning aid).
-static int path_override()
-{
-    const char* e = getenv("SASQ_STATIC_LINEAR_PATH");
-    if (!e) return 0;
-    if (!strcmp(e, "twopass")) return 1;
-    if (!strcmp(e, "fused")) return 2;
-    return 0;
-}
+// 2 = quantize-on-load (sasq_set_tuning(SASQ_TUNE_LINEAR_PATH, ...)).
+static int path_override() { return tuning(SASQ_TUNE_LINEAR_PATH); }
 
 // Quantize-on-load re-quantizes each activation row once per column tile (about 3 VALU
 // operations per element on the SIMD that also issues the MFMAs) and doubles the A-side L2
@@ -942,15 +909,10 @@ static void launch_tiles(const void* xin, const void* wq, const float* s, const 
 // Tile choice.  256x256 tiles are the most efficient per operation but a launch of T tiles takes
 // ceil(T / 256) rounds on 256 CUs; problems with few tiles use 128x256 or 128x128 tiles (the
 // latter two workgroups per CU) so that the chip is filled.  Relative costs per output element
-// (measured) are folded into `cost`.  Overridable with SASQ_STATIC_LINEAR_TILE=256|128x256|128.
+// (measured) are folded into `cost`.  sasq_set_tuning(SASQ_TUNE_LINEAR_TILE, 1 | 2 | 3) forces one.
 static int choose_tile(int64_t M, int64_t N)
 {
-    const char* e = getenv("SASQ_STATIC_LINEAR_TILE");
-    if (e) {
-        if (!strcmp(e, "256")) return 0;
-        if (!strcmp(e, "128x256")) return 1;
-        if (!strcmp(e, "128")) return 2;
-    }
+    if (const int t = tuning(SASQ_TUNE_LINEAR_TILE)) return t - 1;
     auto rounds = [&](int bm, int bn, int slots) {
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
         return (double)((tiles + slots - 1) / slots);
@@ -962,10 +924,27 @@ static int choose_tile(int64_t M, int64_t N)
     return c1 <= c2 ? 1 : 2;
 }
 
+// int8 weights over staged activations run on the 16x16x64 MFMA kernel (static_linear_k64.hip) unless
+// sasq_set_tuning(SASQ_TUNE_LINEAR_MFMA, 1) asks for the 32x32x32 one.
+static bool use_k64(int xmode, int wmode)
+{
+    return xmode == X_PREQ && (wmode == W_I8 || wmode == W_I8B) && tuning(SASQ_TUNE_LINEAR_MFMA) != 1;
+}
+
+template <int DT>
+static void launch_k64(const void* xq, const void* wq, const float* s, const float* s_w, const float* bias, void* y,
+                       int32_t* acc_out, int64_t M, int64_t N, int64_t K, bool blocked, bool rows, hipStream_t st)
+{
+    GemmK64Args a{static_cast<const int8_t*>(xq), static_cast<const uint8_t*>(wq), s, s_w, bias,
+                  static_cast<uint16_t*>(y), acc_out, M, N, K};
+    launch_gemm_k64(a, (sasq_dtype)DT, blocked, choose_tile(M, N), rows, st);
+}
+
 template <int DT, int XMODE, int WMODE>
 static void launch_mfma(const void* xin, const void* wq, const float* s, const float* s_w, const float* bias,
                         void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K, int a_bits, hipStream_t st)
 {
+    if (use_k64(XMODE, WMODE)) { launch_k64<DT>(xin, wq, s, s_w, bias, y, acc_out, M, N, K, WMODE == W_I8B, false, st); return; }
     switch (choose_tile(M, N)) {
         case 0: launch_tiles<DT, XMODE, WMODE, 256, 256>(xin, wq, s, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
         case 1: launch_tiles<DT, XMODE, WMODE, 128, 256>(xin, wq, s, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
@@ -1043,11 +1022,7 @@ static void launch_mfma_grouped(const void* xin, const void* wq, const float* s_
     // 128x128 tiles, two workgroups per CU: the fp32 sums and the accumulators then all fit in
     // VGPRs (no accumulator-register moves in the fold) and one wave's fold overlaps the MFMAs of
     // the other wave on its SIMD; measured 1.3-1.6 x faster than 128x256 tiles at every group size.
-    int tile = 2;
-    if (const char* e = getenv("SASQ_STATIC_LINEAR_TILE")) {
-        if (!strcmp(e, "128x256")) tile = 1;
-        if (!strcmp(e, "128")) tile = 2;
-    }
+    const int tile = tuning(SASQ_TUNE_LINEAR_TILE) == 2 ? 1 : 2;
     auto acc_out = reinterpret_cast<int32_t*>(f_out);
     if (tile == 1) launch_tiles<DT, X_PREQ, WMODE, 128, 256, true>(xin, wq, s_g, s_w, bias, y, acc_out, M, N, K, a_bits, st, group_tiles);
     else           launch_tiles<DT, X_PREQ, WMODE, 128, 128, true>(xin, wq, s_g, s_w, bias, y, acc_out, M, N, K, a_bits, st, group_tiles);
@@ -1095,6 +1070,7 @@ template <int DT, int WMODE>
 static void launch_mfma_rows(const void* xin, const void* wq, const float* s_row, const float* s_w, const float* bias,
                              void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K, int a_bits, hipStream_t st)
 {
+    if (use_k64(X_PREQ, WMODE)) { launch_k64<DT>(xin, wq, s_row, s_w, bias, y, acc_out, M, N, K, WMODE == W_I8B, true, st); return; }
     switch (choose_tile(M, N)) {
         case 0: launch_tiles<DT, X_PREQ, WMODE, 256, 256, false, true>(xin, wq, s_row, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
         case 1: launch_tiles<DT, X_PREQ, WMODE, 128, 256, false, true>(xin, wq, s_row, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
@@ -1343,7 +1319,9 @@ extern "C" int sasq_static_linear_batch(const sasq_linear_item* items, int count
     do {                                                                                                                \
         if (perm8) quantize_act_batch_kernel<DTV, true><<<qgrid, 256, 0, st>>>(q, a_bits);                              \
         else       quantize_act_batch_kernel<DTV, false><<<qgrid, 256, 0, st>>>(q, a_bits);                             \
-        switch (wf) {                                                                                                   \
+        if (use_k64(X_PREQ, wf == SASQ_W_INT8 ? W_I8 : wf == SASQ_W_INT8_BLOCKED ? W_I8B : W_I4)) {                     \
+            launch_gemm_k64_batch(g, ggrid, dt, wf == SASQ_W_INT8_BLOCKED, st);                                         \
+        } else switch (wf) {                                                                                            \
             case SASQ_W_INT8:         linear_mfma_batch_kernel<DTV, W_I8><<<ggrid, kGemmThreads, 0, st>>>(g, a_bits); break;   \
             case SASQ_W_INT4_PACKED:  linear_mfma_batch_kernel<DTV, W_I4><<<ggrid, kGemmThreads, 0, st>>>(g, a_bits); break;   \
             case SASQ_W_INT8_BLOCKED: linear_mfma_batch_kernel<DTV, W_I8B><<<ggrid, kGemmThreads, 0, st>>>(g, a_bits); break;  \

@@ -1,0 +1,363 @@
+// int8 GEMM of the static-inference linear (Sec. 3, Eq. 2) on v_mfma_i32_16x16x64_i8, over
+// pre-quantized activations, with the dequantizing epilogue.
+//
+// Same machine shape as the 32x32x32 kernel in static_linear.hip -- workgroup tile BM x BN, four
+// waves in a 2x2 arrangement, a ring of four LDS stages of 64 K-bytes filled by direct L2 -> LDS
+// loads three to four stages ahead, XOR-swizzled 16-byte chunks, XCD-aware tile order, the
+// LDS-staged 128-bit store epilogue -- but the wave's (BM/2) x (BN/2) block is (BM/32) x (BN/32)
+// tiles of 16x16 and one MFMA contracts a whole 64-byte stage.  On this part the matrix units are
+// power-limited, and the 16x16x64 form sustains about 15 % more than 32x32x32 on the same operand
+// codes (a register-only loop reads 4.4-4.5 POP/s against 3.9): it moves half as many accumulator
+// values per multiply-add.  Fragment bytes read from LDS per multiply-add are the same.
+//
+// MFMA operand layout: lane l supplies row l%16 of its operand and the 16 K-bytes 16*(l/16) ..
+// +15 of the stage; A = weight tile (rows n), B = activation tile (rows m); the result D[i][j]
+// (i <-> n, j <-> m) puts n = 4*(l/16) + v, m = l%16 in register v of lane l, so a lane holds
+// four consecutive n of one m.
+#include "sasq_device.h"
+#include "gemm_tile.h"
+#include "gemm_k64.h"
+#include <type_traits>
+
+namespace sasq {
+
+enum { KW_I8 = 0, KW_I8B = 2 };
+
+// One direct 128-bit-per-lane load from global memory into LDS: lane i deposits its 16 bytes at
+// LDS address lds_addr + 16 i.  The memory address is a scalar base plus a 32-bit per-lane offset,
+// so that the instruction needs no vector address arithmetic.  The compiler does not see the LDS
+// write: the callers order it against their LDS reads with s_waitcnt vmcnt and barriers.
+__device__ __forceinline__ void lds_load16(uint32_t lds_addr, const void* base, uint32_t lane_off)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
+}   // row-major int8 / pre-arranged int8 (values shared with static_linear.hip)
+
+template <int DT, int WMODE, int BM, int BN, bool ROWS>
+__device__ __forceinline__
+void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq,
+                   const float* __restrict__ s_ptr, const float* __restrict__ s_w,
+                   const float* __restrict__ bias, uint16_t* __restrict__ y,
+                   int32_t* __restrict__ acc_out, int M, int N, int K,
+                   int tiles_m, int tiles_n, int bid)
+{
+    using S = Store16<DT>;
+    using T = Tile<BM, BN>;
+    constexpr int MF = BM / 32, NF = BN / 32;          // 16x16 tiles per wave along m, n
+    constexpr int XS = T::XS, WS = T::WS;              // 1 KB slabs per wave per stage
+    constexpr int kLoads = XS + WS;                    // direct loads per wave per K tile
+    __shared__ __attribute__((aligned(1024))) char lds[T::kLds];
+    auto stage_ptr = [&](int st, int operand) -> char* { return &lds[st * T::kStageBytes + operand * T::kXBytes]; };
+
+    int tm, tn;
+    if (!tile_of_block(bid, tiles_m, tiles_n, tm, tn)) return;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // uniform: LDS addresses of the loads stay scalar
+    const int wm = wave & 1, wn = wave >> 1;
+    const int KT = K / kBK;
+
+    // ---- direct L2 -> LDS loads: load j of wave w fills rows (4j + w)*16 .. +16 of a stage ----
+    // Address of a load = scalar base of the operand panel at the K tile (advanced once per K tile)
+    // + a per-lane 32-bit offset fixed for the whole tile: the load itself then costs the wave two
+    // scalar instructions and the load (anything more does not fit behind a 16-cycle MFMA).
+    const int lrow = lane >> 2;
+    const int lchunk = (lane & 3) ^ (((lane >> 3) & 3) ^ ((lane >> 5) & 1));
+    const int last_rb = (M - 1) >> 4;
+    const int8_t* xpanel = xq + (int64_t)(m0 >> 4) * KT * 1024;
+    const int8_t* wpanel = reinterpret_cast<const int8_t*>(wq) + (WMODE == KW_I8B ? (int64_t)(n0 >> 4) * KT * 1024 : (int64_t)n0 * K);
+    uint32_t xoff[XS], woff[WS];
+#pragma unroll
+    for (int j = 0; j < XS; ++j)
+        xoff[j] = (uint32_t)(min(4 * j + wave, last_rb - (m0 >> 4)) * KT * 1024 + lane * 16);
+#pragma unroll
+    for (int j = 0; j < WS; ++j) {
+        if (WMODE == KW_I8B) woff[j] = (uint32_t)(min(4 * j + wave, ((N - 1) >> 4) - (n0 >> 4)) * KT * 1024 + lane * 16);
+        else                 woff[j] = (uint32_t)(min((4 * j + wave) * 16 + lrow, N - 1 - n0) * K + lchunk * 16);
+    }
+    constexpr int kWTileStep = WMODE == KW_I8B ? 1024 : kBK;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_ptr_t)&lds[0] + (uint32_t)wave * 1024u;
+    auto dma = [&](int Tk, int j) {                  // loads 0..XS-1: activations, XS..: weights
+        const uint32_t st_off = (uint32_t)(Tk & 3) * T::kStageBytes;
+        if (j < XS) lds_load16(lds_base + st_off + j * 4096, xpanel + (int64_t)Tk * 1024, xoff[j]);
+        else        lds_load16(lds_base + st_off + T::kXBytes + (j - XS) * 4096, wpanel + (int64_t)Tk * kWTileStep, woff[j - XS]);
+    };
+
+    // ---- LDS -> MFMA fragments: lane l reads chunk l/16 of row l%16 of a 16-row tile ----
+    const int frow = lane & 15, fq = lane >> 4;
+    const int foff = frow * kBK + ((fq ^ swz64(frow)) << 4);
+    const int xbase = wm * (BM / 2) * kBK, wbase = wn * (BN / 2) * kBK;
+    i32x4 fx[2][MF], fw[2][NF];
+    auto read_frag = [&](int set, int st, int idx) {   // the MF activation fragments first, then the NF weight ones
+        if (idx < MF) fx[set][idx] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 0) + xbase + idx * 16 * kBK + foff);
+        else          fw[set][idx - MF] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 1) + wbase + (idx - MF) * 16 * kBK + foff);
+    };
+
+    i32x4 acc[NF][MF];
+
+    // ---- K pipeline ----
+    // Iteration i multiplies K tile i from fragment set i&1 while it reads the fragments of tile
+    // i+1 into the other set and issues the loads of tile i+4 into the stage tile i has just left.
+    // At its top: this wave's fragment reads of tile i are complete and its own loads of tile i+1
+    // have landed (loads return in issue order, so that is one s_waitcnt vmcnt with the loads of
+    // the later tiles still allowed in flight); after the barrier the same holds for every wave,
+    // so tile i+1 may be read and stage i&3 refilled.
+    // Side work is dealt out behind the MFMAs (one wave per SIMD: nothing else hides a clump of
+    // issue): the fragment reads first, every `kFragStep` MFMAs, then the loads.
+    // The last four or five iterations (TAIL) request a tile only if there is one left and wait for
+    // what is still due.
+    constexpr int NM = MF * NF, NFR = MF + NF;
+    constexpr int kFragStep = NM / 2 / NFR >= 1 ? NM / 2 / NFR : 1;
+    constexpr int kLoadStep = (NM - kFragStep * NFR) / kLoads;
+    static_assert(kLoadStep >= 1, "side work does not fit behind the MFMAs");
+    auto iteration = [&](int i, auto cur_tag, auto first_tag, auto tail_tag) {
+        constexpr int CUR = decltype(cur_tag)::value;
+        constexpr bool FIRST = decltype(first_tag)::value;
+        constexpr bool TAIL = decltype(tail_tag)::value;
+        if (!TAIL) {
+            __builtin_amdgcn_s_waitcnt(kWaitLgkm0 & waitcnt_vm(2 * kLoads));
+        } else {
+            const int later = min(i + 3, KT - 1) - (i + 1);    // tiles after i+1 already requested
+            if (later >= 2)      __builtin_amdgcn_s_waitcnt(kWaitLgkm0 & waitcnt_vm(2 * kLoads));
+            else if (later == 1) __builtin_amdgcn_s_waitcnt(kWaitLgkm0 & waitcnt_vm(kLoads));
+            else                 __builtin_amdgcn_s_waitcnt(kWaitLgkm0 & waitcnt_vm(0));
+        }
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        const int stn = (i + 1) & 3;
+        const bool more = !TAIL || i + 1 < KT;                 // a next tile to read fragments of
+#pragma unroll
+        for (int g = 0; g < NF; ++g) {
+#pragma unroll
+            for (int b = 0; b < MF; ++b) {
+                const i32x4 zero = {0, 0, 0, 0};
+                // K tile 0 multiplies into a zero accumulator operand instead of clearing the accumulators
+                acc[g][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[CUR][g], fx[CUR][b], FIRST ? zero : acc[g][b], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                const int t = g * MF + b;
+                if (t < kFragStep * NFR) {
+                    if (t % kFragStep == 0 && more) read_frag(1 - CUR, stn, t / kFragStep);
+                } else if (!TAIL || i + 4 < KT) {
+                    const int u = t - kFragStep * NFR;
+                    if (u % kLoadStep == 0 && u / kLoadStep < kLoads) dma(i + 4, u / kLoadStep);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+    using C0 = std::integral_constant<int, 0>;
+    using C1 = std::integral_constant<int, 1>;
+    using Yes = std::true_type;
+    using No = std::false_type;
+    // fill: the first four tiles requested, tile 0 landed for everyone, its fragments read
+    const int nfill = min(KT, 4);
+    for (int t = 0; t < nfill; ++t)
+#pragma unroll
+        for (int j = 0; j < kLoads; ++j) dma(t, j);
+    if (nfill == 4)      __builtin_amdgcn_s_waitcnt(waitcnt_vm(3 * kLoads));
+    else if (nfill == 3) __builtin_amdgcn_s_waitcnt(waitcnt_vm(2 * kLoads));
+    else if (nfill == 2) __builtin_amdgcn_s_waitcnt(waitcnt_vm(kLoads));
+    else                 __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int k = 0; k < NFR; ++k) read_frag(0, 0, k);
+    // An even number of steady iterations (they always have a tile i+4 to request), then the tail,
+    // written out so that every copy of the loop body knows its fragment set at compile time.
+    const int steady = KT >= 6 ? ((KT - 4) & ~1) : 0;
+    if (steady > 0) {
+        iteration(0, C0{}, Yes{}, No{});
+        iteration(1, C1{}, No{}, No{});
+#pragma unroll 1
+        for (int it = 2; it < steady; it += 2) {
+            iteration(it, C0{}, No{}, No{});
+            iteration(it + 1, C1{}, No{}, No{});
+        }
+    } else {
+#pragma unroll
+        for (int g = 0; g < NF; ++g)
+#pragma unroll
+            for (int b = 0; b < MF; ++b) acc[g][b] = i32x4{0, 0, 0, 0};
+    }
+    iteration(steady, C0{}, No{}, Yes{});                       // KT - steady is 1 .. 5
+    if (steady + 1 < KT) {
+        iteration(steady + 1, C1{}, No{}, Yes{});
+        if (steady + 2 < KT) {
+            iteration(steady + 2, C0{}, No{}, Yes{});
+            if (steady + 3 < KT) {
+                iteration(steady + 3, C1{}, No{}, Yes{});
+                if (steady + 4 < KT) iteration(steady + 4, C0{}, No{}, Yes{});
+            }
+        }
+    }
+    // the last fragment reads (none pending) and loads (none in flight) are complete; LDS is reused
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0 & waitcnt_vm(0));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    // ---- epilogue: Y = fl32(fl32(acc) * fl32(s * s_w[n])) (+ bias), staged through LDS in [m][n]
+    // order as 16-bit values, written with 128-bit stores, BN contiguous bytes per row ----
+    const float s = ROWS ? 1.0f : *s_ptr;
+    const bool has_bias = bias != nullptr;
+    char* epi = &lds[wave * T::kEpiBytes];
+    const int wn0 = n0 + wn * (BN / 2), wm0 = m0 + wm * (BM / 2);
+    float srow[MF];                                            // ROWS: the factor of each row this lane holds
+#pragma unroll
+    for (int b = 0; b < MF; ++b) srow[b] = ROWS ? s_ptr[min(wm0 + b * 16 + frow, M - 1)] : 1.0f;
+    const bool cols_inside = wn0 + BN / 2 <= N && (reinterpret_cast<uintptr_t>(s_w) & 15u) == 0 &&
+                             (bias == nullptr || (reinterpret_cast<uintptr_t>(bias) & 15u) == 0);
+    auto write_tile = [&](auto bias_tag) {
+        constexpr bool BIAS = decltype(bias_tag)::value;
+#pragma unroll
+        for (int g = 0; g < NF; ++g) {
+            const int nl = g * 16 + 4 * fq;                    // column within the wave's block
+            float cs[4], bs[4];
+            if (cols_inside) {
+                const f32x4 sv = *reinterpret_cast<const f32x4*>(s_w + wn0 + nl);
+                f32x4 bv = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (BIAS) bv = *reinterpret_cast<const f32x4*>(bias + wn0 + nl);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { cs[e] = ROWS ? sv[e] : s * sv[e]; bs[e] = bv[e]; }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int ne = min(wn0 + nl + e, N - 1);
+                    cs[e] = ROWS ? s_w[ne] : s * s_w[ne];
+                    bs[e] = BIAS ? bias[ne] : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < MF; ++b) {
+                const int ml = b * 16 + frow;
+                float yv[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float cc = ROWS ? srow[b] * cs[e] : cs[e];
+                    float v = (float)acc[g][b][e] * cc;
+                    if (BIAS) v = v + bs[e];
+                    yv[e] = v;
+                }
+                u32x2 pk = {S::pack(yv[0], yv[1]), S::pack(yv[2], yv[3])};
+                *reinterpret_cast<u32x2*>(epi + ml * T::kEpiStride + nl * 2) = pk;
+            }
+        }
+    };
+    if (has_bias) write_tile(std::true_type{});
+    else          write_tile(std::false_type{});
+    // each wave reads back only what it wrote itself: no workgroup barrier needed
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+    const bool vec_ok = (N & 7) == 0;
+    constexpr int kChunksPerRow = BN / 16;                      // 16-byte chunks in a wave-block row
+    constexpr int kRowsPerPass = 64 / kChunksPerRow;
+    const int crow = lane / kChunksPerRow, cchunk = lane % kChunksPerRow;
+    if (vec_ok && wm0 + BM / 2 <= M && wn0 + BN / 2 <= N) {
+        const char* src = epi + crow * T::kEpiStride + cchunk * 16;
+        char* dst = reinterpret_cast<char*>(y + (int64_t)(wm0 + crow) * N + wn0 + cchunk * 8);
+        const int64_t row_step = (int64_t)kRowsPerPass * N * 2;
+        constexpr int kPasses = (BM / 2) / kRowsPerPass;
+#pragma unroll
+        for (int p0 = 0; p0 < kPasses; p0 += 8) {
+            u32x4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = *reinterpret_cast<const u32x4*>(src + (p0 + j) * kRowsPerPass * T::kEpiStride);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x4*>(dst + (p0 + j) * row_step) = v[j];
+        }
+    } else
+#pragma unroll 4
+    for (int p = 0; p < (BM / 2) / kRowsPerPass; ++p) {
+        const int ml = p * kRowsPerPass + crow;
+        const int m = wm0 + ml, n = wn0 + cchunk * 8;
+        if (m >= M || n >= N) continue;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(epi + ml * T::kEpiStride + cchunk * 16);
+        uint16_t* dst = y + (int64_t)m * N + n;
+        if (vec_ok && n + 7 < N) {
+            *reinterpret_cast<u32x4*>(dst) = v;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (n + e < N) dst[e] = (uint16_t)(v[e >> 1] >> (16 * (e & 1)));
+        }
+    }
+    // inspection output (int32 accumulators): straight from the registers, apart from the common path
+    if (acc_out) {
+#pragma unroll
+        for (int g = 0; g < NF; ++g)
+#pragma unroll
+            for (int b = 0; b < MF; ++b) {
+                const int m = wm0 + b * 16 + frow, n = wn0 + g * 16 + 4 * fq;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (m < M && n + e < N) acc_out[(int64_t)m * N + n + e] = acc[g][b][e];
+            }
+    }
+}
+
+template <int DT, int WMODE, int BM, int BN, bool ROWS>
+__global__ __launch_bounds__(kGemmThreads)
+__attribute__((amdgpu_waves_per_eu(Tile<BM, BN>::kWavesPerSimd, Tile<BM, BN>::kWavesPerSimd)))
+void gemm_k64_kernel(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq,
+                     const float* __restrict__ s_ptr, const float* __restrict__ s_w,
+                     const float* __restrict__ bias, uint16_t* __restrict__ y,
+                     int32_t* __restrict__ acc_out, int M, int N, int K, int tiles_m, int tiles_n)
+{
+    gemm_k64_body<DT, WMODE, BM, BN, ROWS>(xq, wq, s_ptr, s_w, bias, y, acc_out, M, N, K, tiles_m, tiles_n, (int)blockIdx.x);
+}
+
+// Several projections in one launch, 256x256 tiles: each projection owns a run of workgroup ids
+// (a multiple of 8, so the XCD-aware tile numbering holds inside it), longest K first.
+template <int DT, int WMODE>
+__global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void gemm_k64_batch_kernel(const LinBatch b)
+{
+    const int k = lin_item_of(b, (int)blockIdx.x);
+    const LinItem& it = b.it[k];
+    gemm_k64_body<DT, WMODE, 256, 256, false>(it.xq, it.wq, it.s, it.s_w, it.bias, it.y, nullptr, it.M, it.N, it.K,
+                                               it.tiles_m, it.tiles_n, (int)blockIdx.x - b.first_block[k]);
+}
+
+template <int DT, int WMODE, int BM, int BN, bool ROWS>
+static void launch_one(const GemmK64Args& a, hipStream_t st)
+{
+    const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
+    const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
+    gemm_k64_kernel<DT, WMODE, BM, BN, ROWS><<<grid, kGemmThreads, 0, st>>>(
+        a.xq, a.wq, a.s, a.s_w, a.bias, a.y, a.acc_out, (int)a.M, (int)a.N, (int)a.K, tiles_m, tiles_n);
+}
+
+template <int DT, int WMODE, bool ROWS>
+static void launch_tile(const GemmK64Args& a, int tile, hipStream_t st)
+{
+    switch (tile) {
+        case 0: launch_one<DT, WMODE, 256, 256, ROWS>(a, st); break;
+        case 1: launch_one<DT, WMODE, 128, 256, ROWS>(a, st); break;
+        default: launch_one<DT, WMODE, 128, 128, ROWS>(a, st); break;
+    }
+}
+
+template <int DT>
+static void launch_dt(const GemmK64Args& a, bool blocked, int tile, bool rows, hipStream_t st)
+{
+    if (blocked) { if (rows) launch_tile<DT, KW_I8B, true>(a, tile, st); else launch_tile<DT, KW_I8B, false>(a, tile, st); }
+    else         { if (rows) launch_tile<DT, KW_I8, true>(a, tile, st);  else launch_tile<DT, KW_I8, false>(a, tile, st); }
+}
+
+void launch_gemm_k64(const GemmK64Args& a, sasq_dtype dt, bool blocked, int tile, bool rows, hipStream_t st)
+{
+    if (dt == SASQ_F16) launch_dt<SASQ_F16>(a, blocked, tile, rows, st);
+    else                launch_dt<SASQ_BF16>(a, blocked, tile, rows, st);
+}
+
+void launch_gemm_k64_batch(const LinBatch& b, int grid, sasq_dtype dt, bool blocked, hipStream_t st)
+{
+    if (dt == SASQ_F16) {
+        if (blocked) gemm_k64_batch_kernel<SASQ_F16, KW_I8B><<<grid, kGemmThreads, 0, st>>>(b);
+        else         gemm_k64_batch_kernel<SASQ_F16, KW_I8><<<grid, kGemmThreads, 0, st>>>(b);
+    } else {
+        if (blocked) gemm_k64_batch_kernel<SASQ_BF16, KW_I8B><<<grid, kGemmThreads, 0, st>>>(b);
+        else         gemm_k64_batch_kernel<SASQ_BF16, KW_I8><<<grid, kGemmThreads, 0, st>>>(b);
+    }
+}
+
+}  // namespace sasq

@@ -45,3 +45,21 @@ def assert_same_values(got_bits: np.ndarray, ref_bits: np.ndarray, dtype: str, w
 
 def rel_err(a: float, b: float) -> float:
     return abs(a - b) / max(abs(b), 1e-30)
+
+
+_PATH = {None: 0, "twopass": 1, "fused": 2}
+_TILE = {None: 0, "256": 1, "128x256": 2, "128": 3}
+_MFMA = {None: 0, "32x32x32": 1, "16x16x64": 2}
+_BWD_TILE = {None: 0, "256": 1, "128": 2}
+
+
+def set_tuning(path=None, tile=None, mfma=None, share=None, bwd_tile=None):
+    """Force kernel variants through sasq_set_tuning; called without arguments it restores the
+    library's own choices.  path: "twopass" | "fused"; tile: "256" | "128x256" | "128";
+    mfma: "32x32x32" | "16x16x64"; share: 1..3; bwd_tile: "256" | "128"."""
+    from paper_2512_14481_amd import binding as B
+    B.sasq_set_tuning(B.SASQ_TUNE_LINEAR_PATH, _PATH[path])
+    B.sasq_set_tuning(B.SASQ_TUNE_LINEAR_TILE, _TILE[tile])
+    B.sasq_set_tuning(B.SASQ_TUNE_LINEAR_MFMA, _MFMA[mfma])
+    B.sasq_set_tuning(B.SASQ_TUNE_FQ_SHARE, share or 0)
+    B.sasq_set_tuning(B.SASQ_TUNE_BWD_TILE, _BWD_TILE[bwd_tile])

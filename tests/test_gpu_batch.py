@@ -257,10 +257,10 @@ def test_pc_batch_errors_and_layer_sizes():
 @pytest.fixture
 def force_sharing():
     """The library groups operators on one x only from 12 M elements up; this lifts the threshold."""
-    import os
-    os.environ["SASQ_FAKEQUANT_SHARE"] = "3"
+    from tests.gpu_util import set_tuning
+    set_tuning(share=3)
     yield
-    os.environ.pop("SASQ_FAKEQUANT_SHARE", None)
+    set_tuning()
 
 
 def test_batch_sharing_at_its_natural_size():

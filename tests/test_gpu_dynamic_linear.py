@@ -2,7 +2,6 @@
 oracle: row factors, activation codes and int32 accumulators bit for bit, Y equal by value."""
 from __future__ import annotations
 
-import os
 
 import numpy as np
 import pytest
@@ -11,17 +10,14 @@ import torch
 import oracle
 from paper_2512_14481_amd import binding as B
 from paper_2512_14481_amd import workloads as wl
-from tests.gpu_util import TDT, assert_same_values, to_bits, to_dev
+from tests.gpu_util import TDT, assert_same_values, set_tuning, to_bits, to_dev
 from tests.test_gpu_grouped_linear import WF, device_weights
 
 pytestmark = pytest.mark.gpu
 
 
-def run_dynamic(xb, wq, s_w, bias, fmt, dtype, blocked, want_debug=True, tile=None):
-    if tile is None:
-        os.environ.pop("SASQ_STATIC_LINEAR_TILE", None)
-    else:
-        os.environ["SASQ_STATIC_LINEAR_TILE"] = tile
+def run_dynamic(xb, wq, s_w, bias, fmt, dtype, blocked, want_debug=True, tile=None, mfma=None):
+    set_tuning(tile=tile, mfma=mfma)
     M, K = xb.shape
     N = wq.shape[0]
     wf = WF[(fmt, blocked)]
@@ -34,7 +30,7 @@ def run_dynamic(xb, wq, s_w, bias, fmt, dtype, blocked, want_debug=True, tile=No
     B.sasq_dynamic_linear(x, device_weights(wq, fmt, blocked), torch.from_numpy(s_w).cuda(),
                           None if bias is None else torch.from_numpy(bias).cuda(), y, wf, ws, acc, xq, srow)
     torch.cuda.synchronize()
-    os.environ.pop("SASQ_STATIC_LINEAR_TILE", None)
+    set_tuning()
     if not want_debug:
         return to_bits(y), None, None, None
     return to_bits(y), acc.cpu().numpy(), xq.cpu().numpy(), srow.cpu().numpy()
@@ -74,6 +70,9 @@ def test_dynamic_linear(shape, dtype, fmt, blocked, tile):
         assert_same_values(y, ref["y"], dtype, "Y")
         y2, _, _, _ = run_dynamic(xb, wq, s_w, b, fmt, dtype, blocked, want_debug=False, tile=tile)
         assert np.array_equal(y2, y)
+        if fmt == "int8" and shape[2] % 64 == 0:       # the int8 GEMM's other kernel
+            y3, acc3, _, _ = run_dynamic(xb, wq, s_w, b, fmt, dtype, blocked, tile=tile, mfma="32x32x32")
+            assert np.array_equal(acc3, ref["acc"]) and np.array_equal(y3, y), "32x32x32 kernel"
 
 
 def test_dynamic_linear_config3_sampled():

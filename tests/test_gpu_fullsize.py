@@ -9,7 +9,6 @@ sampled channel, always including the first/last row and column and tile-edge ne
 from __future__ import annotations
 
 import functools
-import os
 
 import numpy as np
 import pytest
@@ -18,7 +17,7 @@ import torch
 import oracle
 from paper_2512_14481_amd import binding as B
 from paper_2512_14481_amd import workloads as wl
-from tests.gpu_util import TDT, assert_same_values, dev_scalar, to_bits, to_dev
+from tests.gpu_util import TDT, assert_same_values, dev_scalar, set_tuning, to_bits, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -109,34 +108,32 @@ def test_static_linear_full_size(cfg_name, proj_name, ws):
     sd = dev_scalar(s)
     y = torch.empty((M, N), dtype=TDT[dtype], device="cuda")
     wsl = B.new_workspace(B.sasq_static_linear_workspace(M, N, K, wf))
-    os.environ.pop("SASQ_STATIC_LINEAR_PATH", None)
+    set_tuning()
     B.sasq_static_linear(x, sd, wq, s_w, None, y, wf, wsl)            # the timed configuration
     torch.cuda.synchronize()
-    for path in ("twopass", "fused"):                                 # both activation paths agree bit for bit
-        os.environ["SASQ_STATIC_LINEAR_PATH"] = path
+    for path, mfma in (("twopass", None), ("twopass", "32x32x32"), ("fused", None)):   # every activation path and GEMM kernel agrees bit for bit
+        set_tuning(path=path, mfma=mfma)
         y_alt = torch.empty_like(y)
         B.sasq_static_linear(x, sd, wq, s_w, None, y_alt, wf, wsl)
         torch.cuda.synchronize()
-        assert torch.equal(y.view(torch.int16), y_alt.view(torch.int16)), path
-    os.environ.pop("SASQ_STATIC_LINEAR_PATH", None)
+        assert torch.equal(y.view(torch.int16), y_alt.view(torch.int16)), (path, mfma)
     for tile in ("256", "128x256", "128"):                            # and every tile size
-        os.environ["SASQ_STATIC_LINEAR_TILE"] = tile
+        set_tuning(tile=tile)
         B.sasq_static_linear(x, sd, wq, s_w, None, y_alt, wf, wsl)
         torch.cuda.synchronize()
         assert torch.equal(y.view(torch.int16), y_alt.view(torch.int16)), tile
-    os.environ.pop("SASQ_STATIC_LINEAR_TILE", None)
+    set_tuning()
     # the pre-arranged weight format (what the benchmark times): bit-identical at every tile size
     wfb = B.SASQ_W_INT8_BLOCKED if fmt == "int8" else B.SASQ_W_INT4_BLOCKED
     wpk = torch.empty(B.sasq_packed_weight_bytes(N, K, wfb), dtype=torch.uint8, device="cuda")
     B.sasq_pack_weight(wq, wpk, N, K, wf)
-    for tile in (None, "256", "128x256", "128"):
-        if tile:
-            os.environ["SASQ_STATIC_LINEAR_TILE"] = tile
+    for tile, mfma in ((None, None), ("256", None), ("128x256", None), ("128", None), (None, "32x32x32")):
+        set_tuning(tile=tile, mfma=mfma)
         y_alt.fill_(0)
         B.sasq_static_linear(x, sd, wpk, s_w, None, y_alt, wfb, wsl)
         torch.cuda.synchronize()
-        assert torch.equal(y.view(torch.int16), y_alt.view(torch.int16)), f"blocked weights, tile {tile}"
-    os.environ.pop("SASQ_STATIC_LINEAR_TILE", None)
+        assert torch.equal(y.view(torch.int16), y_alt.view(torch.int16)), f"blocked weights, tile {tile}, mfma {mfma}"
+    set_tuning()
     del y_alt, wpk
     acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
     xq = torch.empty((M, K), dtype=torch.int8, device="cuda")

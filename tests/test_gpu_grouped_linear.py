@@ -3,7 +3,6 @@ codes and the fp32 group sums f bit for bit, Y equal by value; every weight form
 the scalar fallback for shapes the MFMA kernel does not take; config-3 shapes on sampled rows."""
 from __future__ import annotations
 
-import os
 
 import numpy as np
 import pytest
@@ -12,7 +11,7 @@ import torch
 import oracle
 from paper_2512_14481_amd import binding as B
 from paper_2512_14481_amd import workloads as wl
-from tests.gpu_util import TDT, assert_same_values, to_bits, to_dev
+from tests.gpu_util import TDT, assert_same_values, set_tuning, to_bits, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -32,10 +31,7 @@ def device_weights(wq, fmt, blocked):
 
 
 def run_grouped(xb, s_g, wq, s_w, bias, group, fmt, dtype, blocked, want_debug=True, tile=None):
-    if tile is None:
-        os.environ.pop("SASQ_STATIC_LINEAR_TILE", None)
-    else:
-        os.environ["SASQ_STATIC_LINEAR_TILE"] = tile
+    set_tuning(tile=tile)
     M, K = xb.shape
     N = wq.shape[0]
     wf = WF[(fmt, blocked)]
@@ -48,7 +44,7 @@ def run_grouped(xb, s_g, wq, s_w, bias, group, fmt, dtype, blocked, want_debug=T
                                  torch.from_numpy(s_w).cuda(), None if bias is None else torch.from_numpy(bias).cuda(),
                                  y, group, wf, ws, f, xq)
     torch.cuda.synchronize()
-    os.environ.pop("SASQ_STATIC_LINEAR_TILE", None)
+    set_tuning()
     return to_bits(y), (f.cpu().numpy() if want_debug else None), (xq.cpu().numpy() if want_debug else None)
 
 

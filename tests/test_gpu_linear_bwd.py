@@ -3,7 +3,6 @@ sasq_linear_bwd_input) against the CPU oracle: the prepared 16-bit weight bit fo
 the fp32 accumulation bound of the exactly rounded result."""
 from __future__ import annotations
 
-import os
 
 import numpy as np
 import pytest
@@ -12,7 +11,7 @@ import torch
 import oracle
 from paper_2512_14481_amd import binding as B
 from paper_2512_14481_amd import workloads as wl
-from tests.gpu_util import TDT, to_bits, to_dev, val
+from tests.gpu_util import TDT, set_tuning, to_bits, to_dev, val
 
 pytestmark = pytest.mark.gpu
 
@@ -41,16 +40,13 @@ def prepare(wq, s_w, fmt, dtype):
 
 
 def run_bwd(dyb, wt, K, dtype, tile=None, want_acc=False):
-    if tile is None:
-        os.environ.pop("SASQ_LINEAR_BWD_TILE", None)
-    else:
-        os.environ["SASQ_LINEAR_BWD_TILE"] = tile
+    set_tuning(bwd_tile=tile)
     M = dyb.shape[0]
     dx = torch.empty((M, K), dtype=TDT[dtype], device="cuda")
     acc = torch.empty((M, K), dtype=torch.float32, device="cuda") if want_acc else None
     B.sasq_linear_bwd_input(to_dev(dyb, dtype), wt, dx, K, acc)
     torch.cuda.synchronize()
-    os.environ.pop("SASQ_LINEAR_BWD_TILE", None)
+    set_tuning()
     if want_acc:
         return to_bits(dx), acc.cpu().numpy()
     return to_bits(dx)

@@ -6,7 +6,6 @@ within 1e-3 relative (asserted equal by value, which is stricter); ds within 1e-
 """
 from __future__ import annotations
 
-import os
 
 import numpy as np
 import pytest
@@ -15,7 +14,7 @@ import torch
 import oracle
 from paper_2512_14481_amd import binding as B
 from paper_2512_14481_amd import workloads as wl
-from tests.gpu_util import (TDT, assert_same_values, dev_scalar, rel_err, to_bits, to_dev, val)
+from tests.gpu_util import (TDT, assert_same_values, dev_scalar, rel_err, set_tuning, to_bits, to_dev, val)
 
 pytestmark = pytest.mark.gpu
 
@@ -228,15 +227,12 @@ def pack_on_device(wq, fmt):
     return packed, dst
 
 
-def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True, path=None, tile=None, blocked=False, a_bits=8):
+def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True, path=None, tile=None, blocked=False, a_bits=8, mfma=None):
     """path: None (library's choice by shape), "twopass" or "fused" (activation quantize in a
     separate pass / on load inside the GEMM).  tile: None (by shape), "256", "128x256", "128".
+    mfma: None (library's choice), "32x32x32" or "16x16x64" (the int8 GEMM kernel).
     blocked: hand the weights over in the pre-arranged format made by sasq_pack_weight."""
-    for var, val in (("SASQ_STATIC_LINEAR_PATH", path), ("SASQ_STATIC_LINEAR_TILE", tile)):
-        if val is None:
-            os.environ.pop(var, None)
-        else:
-            os.environ[var] = val
+    set_tuning(path=path, tile=tile, mfma=mfma)
     M, K = xb.shape
     N = wq.shape[0]
     wf = B.SASQ_W_INT8 if fmt == "int8" else B.SASQ_W_INT4_PACKED
@@ -252,8 +248,7 @@ def run_linear(xb, s, wq, s_w, bias, fmt, dtype, want_debug=True, path=None, til
     B.sasq_static_linear(x, dev_scalar(s), wdev, torch.from_numpy(s_w).cuda(),
                          None if bias is None else torch.from_numpy(bias).cuda(), y, wf, wsl, acc, xq, a_bits)
     torch.cuda.synchronize()
-    os.environ.pop("SASQ_STATIC_LINEAR_PATH", None)
-    os.environ.pop("SASQ_STATIC_LINEAR_TILE", None)
+    set_tuning()
     return to_bits(y), (acc.cpu().numpy() if want_debug else None), (xq.cpu().numpy() if want_debug else None)
 
 
@@ -266,11 +261,16 @@ LINEAR_SHAPES = [
 
 
 @pytest.mark.parametrize("tile", ["256", "128x256", "128"])
-@pytest.mark.parametrize("path", ["twopass", "fused"])
+@pytest.mark.parametrize("path", ["twopass", "twopass-32x32x32", "fused"])
 @pytest.mark.parametrize("dtype,fmt", [("f16", "int8"), ("bf16", "int8"), ("bf16", "int4"), ("f16", "int4")])
 @pytest.mark.parametrize("shape", LINEAR_SHAPES)
 def test_static_linear(shape, dtype, fmt, path, tile):
     M, N, K = shape
+    mfma = None
+    if path == "twopass-32x32x32":          # the int8 GEMM's other kernel (int4 weights have one kernel only)
+        if fmt == "int4":
+            pytest.skip("one GEMM kernel for int4 weights")
+        path, mfma = "twopass", "32x32x32"
     xb = wl.random_bits(12, f"lx{shape}{dtype}", (M, K), dtype, gain=2.0)
     w = wl.random_f32(12, f"lw{shape}", (N, K), 0.02)
     wq, s_w = oracle.quantize_weight(w, fmt)
@@ -278,11 +278,11 @@ def test_static_linear(shape, dtype, fmt, path, tile):
     s = np.float32(oracle.absmax_scale(xb, 8, dtype) / 3)
     for b in (None, bias):
         ref = oracle.static_linear(xb, s, wq, s_w, b, 8, fmt, dtype)
-        y, acc, xq = run_linear(xb, s, wq, s_w, b, fmt, dtype, path=path, tile=tile)
+        y, acc, xq = run_linear(xb, s, wq, s_w, b, fmt, dtype, path=path, tile=tile, mfma=mfma)
         assert np.array_equal(xq, ref["xq"]), "activation codes"
         assert np.array_equal(acc, ref["acc"]), "int32 accumulators"
         assert_same_values(y, ref["y"], dtype, "Y")
-        y2, _, _ = run_linear(xb, s, wq, s_w, b, fmt, dtype, want_debug=False, path=path, tile=tile)
+        y2, _, _ = run_linear(xb, s, wq, s_w, b, fmt, dtype, want_debug=False, path=path, tile=tile, mfma=mfma)
         assert np.array_equal(y2, y)
 
 
