@@ -46,7 +46,8 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     constexpr int MF = BM / 32, NF = BN / 32;          // 16x16 tiles per wave along m, n
     constexpr int XS = T::XS, WS = T::WS;              // 1 KB slabs per wave per stage
     constexpr int kLoads = XS + WS;                    // direct loads per wave per K tile
-    __shared__ __attribute__((aligned(1024))) char lds[T::kLds];
+    constexpr int kFacBytes = 1024;                    // per wave: the epilogue's per-column factors (BN/2 floats, loaded twice over)
+    __shared__ __attribute__((aligned(1024))) char lds[T::kLds + 4 * kFacBytes];
     auto stage_ptr = [&](int st, int operand) -> char* { return &lds[st * T::kStageBytes + operand * T::kXBytes]; };
 
     int tm, tn;
@@ -179,6 +180,17 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
 #pragma unroll
             for (int b = 0; b < MF; ++b) acc[g][b] = i32x4{0, 0, 0, 0};
     }
+    // The per-column factors of the epilogue are requested here, a few K tiles before they are
+    // needed (fetched inside the epilogue they cost eight memory latencies in a row): one direct
+    // load per wave parks the BN/2 factors of its block in LDS, behind the stages.  (An extra load
+    // in the in-order queue only makes the counted waits of the tail wait for more, never less.)
+    const int wn0 = n0 + wn * (BN / 2), wm0 = m0 + wm * (BM / 2);
+    const bool cols_inside = wn0 + BN / 2 <= N && (reinterpret_cast<uintptr_t>(s_w) & 15u) == 0 &&
+                             (bias == nullptr || (reinterpret_cast<uintptr_t>(bias) & 15u) == 0);
+    char* fac = &lds[T::kLds + wave * kFacBytes];
+    if (cols_inside)
+        lds_load16(lds_base - (uint32_t)wave * 1024u + T::kLds + (uint32_t)wave * kFacBytes, s_w + wn0,
+                   (uint32_t)(lane & (BN / 8 - 1)) * 16u);   // lanes past BN/8 fetch the same factors again: no lane reads past the block
     iteration(steady, C0{}, No{}, Yes{});                       // KT - steady is 1 .. 5
     if (steady + 1 < KT) {
         iteration(steady + 1, C1{}, No{}, Yes{});
@@ -200,20 +212,20 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     const float s = ROWS ? 1.0f : *s_ptr;
     const bool has_bias = bias != nullptr;
     char* epi = &lds[wave * T::kEpiBytes];
-    const int wn0 = n0 + wn * (BN / 2), wm0 = m0 + wm * (BM / 2);
     float srow[MF];                                            // ROWS: the factor of each row this lane holds
 #pragma unroll
     for (int b = 0; b < MF; ++b) srow[b] = ROWS ? s_ptr[min(wm0 + b * 16 + frow, M - 1)] : 1.0f;
-    const bool cols_inside = wn0 + BN / 2 <= N && (reinterpret_cast<uintptr_t>(s_w) & 15u) == 0 &&
-                             (bias == nullptr || (reinterpret_cast<uintptr_t>(bias) & 15u) == 0);
     auto write_tile = [&](auto bias_tag) {
         constexpr bool BIAS = decltype(bias_tag)::value;
+        f32x4 svs[NF];                                         // all parked factors requested together: one LDS latency
+#pragma unroll
+        for (int g = 0; g < NF; ++g) svs[g] = *reinterpret_cast<const f32x4*>(fac + (g * 16 + 4 * fq) * 4);
 #pragma unroll
         for (int g = 0; g < NF; ++g) {
             const int nl = g * 16 + 4 * fq;                    // column within the wave's block
             float cs[4], bs[4];
             if (cols_inside) {
-                const f32x4 sv = *reinterpret_cast<const f32x4*>(s_w + wn0 + nl);
+                const f32x4 sv = svs[g];
                 f32x4 bv = {0.0f, 0.0f, 0.0f, 0.0f};
                 if (BIAS) bv = *reinterpret_cast<const f32x4*>(bias + wn0 + nl);
 #pragma unroll
