@@ -72,6 +72,7 @@ struct LinBatch {
     LinItem it[kMaxLinearBatch];
     int first_block[kMaxLinearBatch + 1];
     int count;
+    int split_first, split_count;   // 16x16x64 kernel: workgroup ids from split_first on are half tiles (see gemm_k64_batch_kernel)
 };
 
 __device__ __forceinline__ int lin_item_of(const LinBatch& b, int block)

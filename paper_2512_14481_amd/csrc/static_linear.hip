@@ -1320,7 +1320,7 @@ extern "C" int sasq_static_linear_batch(const sasq_linear_item* items, int count
         if (perm8) quantize_act_batch_kernel<DTV, true><<<qgrid, 256, 0, st>>>(q, a_bits);                              \
         else       quantize_act_batch_kernel<DTV, false><<<qgrid, 256, 0, st>>>(q, a_bits);                             \
         if (use_k64(X_PREQ, wf == SASQ_W_INT8 ? W_I8 : wf == SASQ_W_INT8_BLOCKED ? W_I8B : W_I4)) {                     \
-            launch_gemm_k64_batch(g, ggrid, dt, wf == SASQ_W_INT8_BLOCKED, st);                                         \
+            launch_gemm_k64_batch(g, ggrid, dt, wf == SASQ_W_INT8_BLOCKED, tuning(SASQ_TUNE_LINEAR_TILE) == 0, st);                                         \
         } else switch (wf) {                                                                                            \
             case SASQ_W_INT8:         linear_mfma_batch_kernel<DTV, W_I8><<<ggrid, kGemmThreads, 0, st>>>(g, a_bits); break;   \
             case SASQ_W_INT4_PACKED:  linear_mfma_batch_kernel<DTV, W_I4><<<ggrid, kGemmThreads, 0, st>>>(g, a_bits); break;   \

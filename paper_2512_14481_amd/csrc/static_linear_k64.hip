@@ -23,6 +23,9 @@ namespace sasq {
 
 enum { KW_I8 = 0, KW_I8B = 2 };
 
+constexpr int kFacBytes = 1024;      // per wave: the epilogue's per-column factors (BN/2 floats, loaded twice over)
+template <int BM, int BN> constexpr int lds_bytes_k64() { return Tile<BM, BN>::kLds + 4 * kFacBytes; }
+
 // One direct 128-bit-per-lane load from global memory into LDS: lane i deposits its 16 bytes at
 // LDS address lds_addr + 16 i.  The memory address is a scalar base plus a 32-bit per-lane offset,
 // so that the instruction needs no vector address arithmetic.  The compiler does not see the LDS
@@ -39,19 +42,15 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
                    const float* __restrict__ s_ptr, const float* __restrict__ s_w,
                    const float* __restrict__ bias, uint16_t* __restrict__ y,
                    int32_t* __restrict__ acc_out, int M, int N, int K,
-                   int tiles_m, int tiles_n, int bid)
+                   int tm, int tn, char* lds)
 {
     using S = Store16<DT>;
     using T = Tile<BM, BN>;
     constexpr int MF = BM / 32, NF = BN / 32;          // 16x16 tiles per wave along m, n
     constexpr int XS = T::XS, WS = T::WS;              // 1 KB slabs per wave per stage
     constexpr int kLoads = XS + WS;                    // direct loads per wave per K tile
-    constexpr int kFacBytes = 1024;                    // per wave: the epilogue's per-column factors (BN/2 floats, loaded twice over)
-    __shared__ __attribute__((aligned(1024))) char lds[T::kLds + 4 * kFacBytes];
     auto stage_ptr = [&](int st, int operand) -> char* { return &lds[st * T::kStageBytes + operand * T::kXBytes]; };
 
-    int tm, tn;
-    if (!tile_of_block(bid, tiles_m, tiles_n, tm, tn)) return;
     const int m0 = tm * BM, n0 = tn * BN;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // uniform: LDS addresses of the loads stay scalar
@@ -314,19 +313,40 @@ void gemm_k64_kernel(const int8_t* __restrict__ xq, const uint8_t* __restrict__ 
                      const float* __restrict__ bias, uint16_t* __restrict__ y,
                      int32_t* __restrict__ acc_out, int M, int N, int K, int tiles_m, int tiles_n)
 {
-    gemm_k64_body<DT, WMODE, BM, BN, ROWS>(xq, wq, s_ptr, s_w, bias, y, acc_out, M, N, K, tiles_m, tiles_n, (int)blockIdx.x);
+    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes_k64<BM, BN>()];
+    int tm, tn;
+    if (!tile_of_block((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
+    gemm_k64_body<DT, WMODE, BM, BN, ROWS>(xq, wq, s_ptr, s_w, bias, y, acc_out, M, N, K, tm, tn, lds);
 }
 
 // Several projections in one launch, 256x256 tiles: each projection owns a run of workgroup ids
 // (a multiple of 8, so the XCD-aware tile numbering holds inside it), longest K first.
+// The launch's last, partly filled round: when its tiles would occupy fewer than half of the CUs,
+// the host hands them out as two 128x256 halves each (workgroup ids from b.split_first on: first
+// the upper halves, then the lower ones, in the tiles' own order), so that twice as many CUs
+// share the tail and it ends in about 0.6 of a round instead of a whole one.
 template <int DT, int WMODE>
 __global__ __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_k64_batch_kernel(const LinBatch b)
 {
-    const int k = lin_item_of(b, (int)blockIdx.x);
+    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes_k64<256, 256>()];
+    static_assert(lds_bytes_k64<128, 256>() <= lds_bytes_k64<256, 256>(), "one LDS buffer for both tile shapes");
+    int bid = (int)blockIdx.x, half = -1;
+    if (bid >= b.split_first) {                                  // a half tile of the tail
+        const int j = bid - b.split_first;
+        half = j >= b.split_count;
+        bid = b.split_first + (half ? j - b.split_count : j);
+    }
+    const int k = lin_item_of(b, bid);
     const LinItem& it = b.it[k];
-    gemm_k64_body<DT, WMODE, 256, 256, false>(it.xq, it.wq, it.s, it.s_w, it.bias, it.y, nullptr, it.M, it.N, it.K,
-                                               it.tiles_m, it.tiles_n, (int)blockIdx.x - b.first_block[k]);
+    int tm, tn;
+    if (!tile_of_block(bid - b.first_block[k], it.tiles_m, it.tiles_n, tm, tn)) return;
+    if (half < 0) {
+        gemm_k64_body<DT, WMODE, 256, 256, false>(it.xq, it.wq, it.s, it.s_w, it.bias, it.y, nullptr, it.M, it.N, it.K, tm, tn, lds);
+    } else {
+        if ((2 * tm + half) * 128 >= it.M) return;               // the lower half of a tile that ends within its upper half
+        gemm_k64_body<DT, WMODE, 128, 256, false>(it.xq, it.wq, it.s, it.s_w, it.bias, it.y, nullptr, it.M, it.N, it.K, 2 * tm + half, tn, lds);
+    }
 }
 
 template <int DT, int WMODE, int BM, int BN, bool ROWS>
@@ -361,8 +381,17 @@ void launch_gemm_k64(const GemmK64Args& a, sasq_dtype dt, bool blocked, int tile
     else                launch_dt<SASQ_BF16>(a, blocked, tile, rows, st);
 }
 
-void launch_gemm_k64_batch(const LinBatch& b, int grid, sasq_dtype dt, bool blocked, hipStream_t st)
+void launch_gemm_k64_batch(LinBatch& b, int grid, sasq_dtype dt, bool blocked, bool split_tail, hipStream_t st)
 {
+    // Tail of the launch: `grid` workgroup ids in all, 256 resident at a time.
+    b.split_first = grid;
+    b.split_count = 0;
+    const int rem = grid % 256;
+    if (split_tail && rem > 0 && rem <= 128 && grid > 256) {
+        b.split_first = grid - rem;
+        b.split_count = rem;
+        grid += rem;
+    }
     if (dt == SASQ_F16) {
         if (blocked) gemm_k64_batch_kernel<SASQ_F16, KW_I8B><<<grid, kGemmThreads, 0, st>>>(b);
         else         gemm_k64_batch_kernel<SASQ_F16, KW_I8><<<grid, kGemmThreads, 0, st>>>(b);
