@@ -8,14 +8,22 @@ update of the scale, and the static-inference W8A8 linear.  Inputs are seeded sy
 already resident in HBM; weights are quantized once, outside the timed region, by the library.
 
 Prints ONE JSON line.  `value` is the linear-layer integer throughput of the whole step
-(2*M*N*K summed over the projections, divided by the full step time, fake-quant kernels included).
-`roofline` is the static linear alone, timed with HIP events on the launch stream inside the timed
-region; `fakequant` is the fake-quant forward+backward pair against HBM bandwidth; `cpu_baseline`
-is the CPU oracle on a bounded row sample of the same workload.
+(2*M*N*K summed over the projections, divided by the full step time, fake-quant kernels included),
+measured after exactly the W warm-up steps asked for; `settled` repeats the measurement after the
+part's power management has settled under the load (about 100 steps).  `roofline` is the static
+linear alone, timed with HIP events on the launch stream inside the timed region; `fakequant` is
+the fake-quant forward+backward pair against HBM bandwidth; `cpu_baseline` is the CPU oracle on a
+bounded row sample of the same workload (all host cores, and one thread).
+
+Cold buffers: the activation-sized tensors exist in `--rotate` (default 2) copies per direction and
+every step works on the copy that was touched longest ago, so that whatever a kernel reads was last
+touched more than 1 GB of traffic earlier and cannot come from the 256 MB Infinity Cache (the copies
+hold the same values: results do not depend on the rotation).  `--rotate 1` keeps one copy (warm).
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -35,11 +43,12 @@ F16_MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense fp16 / bf16, published
 # what a register-only v_mfma_i32_32x32x32_i8 loop sustains on this part with GEMM-like operand codes (the part is
 # power-limited under MFMA load; profiles/mfma_peak_and_clock.txt) -- context for `frac`, not the roofline's peak
 INT8_MFMA_SUSTAINED_TOPS = 3700.0    # 3613-3750 across boxes (python bench.py --mfma-peak)
-# HBM-side bytes per sasq_static_linear call (both kernels), averaged over gate/up/down of config 3:
-# rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a plain 1 GiB copy), see
-# profiles/bench_c3_mlp7b_counters.txt.  Algorithmic bytes are 221.2 MB.
+# HBM-side bytes per static linear call (both kernels) on config 3: RECORDED constants, not read in
+# this run: rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a plain 1 GiB copy), from
+# the counter passes summarised in profiles/bench_c3_mlp7b_counters.txt.
 C3_LINEAR_TRAFFIC_BYTES = 450654 * 1024          # one call per projection, average
 C3_LINEAR_BATCH_TRAFFIC_BYTES = 1364068 * 1024   # the batched call (all three projections)
+TRAFFIC_SOURCE = "recorded constant from profiles/bench_c3_mlp7b_counters.txt (rocprofv3 FETCH_SIZE/WRITE_SIZE, copy-calibrated), not measured in this run"
 HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published
 LR = 2e-4
 TDT = {"f16": torch.float16, "bf16": torch.bfloat16}
@@ -50,8 +59,13 @@ def dev16(bits: np.ndarray, dtype: str) -> torch.Tensor:
 
 
 class Projection:
-    def __init__(self, cfg, proj, x, ws_small):
-        self.name, self.x = proj.name, x
+    """One projection: frozen weights prepared once, and `rot` copies of every activation-sized
+    tensor per direction.  xf[j] / xhat[j] serve the forward fake-quant of steps with j = step % rot,
+    xb[j] / dy[j] / dx[j] the backward, and the static linear reads xb[(j + 1) % rot]."""
+
+    def __init__(self, cfg, proj, xf, xb, ws_small, rot):
+        x = xf[0]
+        self.name, self.x, self.xf, self.xb = proj.name, x, xf, xb
         self.M, self.K, self.N = x.shape[0], x.shape[1], proj.N
         wf = B.SASQ_W_INT8 if cfg.w_fmt == wl.W_INT8 else B.SASQ_W_INT4_PACKED
         self.wf = wf
@@ -73,53 +87,67 @@ class Projection:
             packed = torch.empty(B.sasq_packed_weight_bytes(self.N, self.K, wfb), dtype=torch.uint8, device="cuda")
             B.sasq_pack_weight(self.wq, packed, self.N, self.K, wf)
             self.wq, self.wf = packed, wfb
-        self.dy = dev16(wl.upstream_grad(cfg, proj.name), cfg.dtype)
+        dy0 = dev16(wl.upstream_grad(cfg, proj.name), cfg.dtype)
+        self.dy = [dy0] + [dy0.clone() for _ in range(rot - 1)]
         self.s = torch.empty(1, dtype=torch.float32, device="cuda")
         B.sasq_absmax_scale(x, self.s, ws_small, 8)           # s0 = absmax / 127
         self.s0 = self.s.clone()
         self.ds = torch.zeros(1, dtype=torch.float32, device="cuda")
-        self.xhat = torch.empty_like(x)
-        self.dx = torch.empty_like(x)
+        self.xhat = [torch.empty_like(x) for _ in range(rot)]
+        self.dx = [torch.empty_like(x) for _ in range(rot)]
         self.y = torch.empty((self.M, self.N), dtype=x.dtype, device="cuda")
         self.ws_lin = B.new_workspace(B.sasq_static_linear_workspace(self.M, self.N, self.K, wf))
         self.ops = 2.0 * self.M * self.N * self.K
-        self.fq_bytes = 10.0 * self.M * self.K
+        self.fq_bytes = 10.0 * self.M * self.K            # 2+2 forward, 2+2+2 backward, per operator
+        e, wbytes = 2, (1.0 if cfg.w_fmt == wl.W_INT8 else 0.5)
+        # bytes the static linear has to move at least: X in, W in, Y out, the per-channel factors
+        self.lin_bytes = e * self.M * self.K + wbytes * self.N * self.K + e * self.M * self.N + 4 * self.N
+        # what this library adds: the int8 activation codes written by the pre-pass and read by the GEMM
+        self.lin_staging_bytes = 2 * self.M * self.K
 
 
 class Layer:
     """The projections of the workload with their scales in one vector, and the descriptors of
-    the batched fake-quant calls (one launch for all fake-quant operators of the layer)."""
+    the batched calls (one launch for all fake-quant operators of the layer), one set per rotation slot."""
 
-    def __init__(self, projs):
-        self.projs = projs
+    def __init__(self, projs, rot):
+        self.projs, self.rot = projs, rot
         n = len(projs)
         self.s_all = torch.cat([p.s for p in projs]).contiguous()
         self.ds_all = torch.zeros(n, dtype=torch.float32, device="cuda")
         for i, p in enumerate(projs):
             p.s, p.ds = self.s_all[i:i + 1], self.ds_all[i:i + 1]
         self.s0_all = self.s_all.clone()
-        self.fwd_items = [(p.x, p.s, p.xhat) for p in projs]
-        self.bwd_items = [(p.x, p.dy, p.s, p.dx, p.ds) for p in projs]
+        self.fwd_items = [[(p.xf[j], p.s, p.xhat[j]) for p in projs] for j in range(rot)]
+        self.bwd_items = [[(p.xb[j], p.dy[j], p.s, p.dx[j], p.ds) for p in projs] for j in range(rot)]
         self.ws_batch = B.new_workspace(B.sasq_fakequant_bwd_batch_workspace(n))
         self.fq_bytes = sum(p.fq_bytes for p in projs)
+        # bytes the two batched launches really move: operators in front of projections that share an
+        # activation (gate/up, q/k/v) read it once in the forward launch
+        shared_reads = sum(2.0 * p.M * p.K for i, p in enumerate(projs)
+                           if any(q.xf[0] is p.xf[0] for q in projs[:i]) and p.M * p.K >= (12 << 20))
+        self.fq_bytes_moved = self.fq_bytes - shared_reads
         # the linears of the layer in one batched call (needs one weight format and K % 64 == 0 throughout)
         self.wf = projs[0].wf
-        self.lin_items = [(p.x, p.s, p.wq, p.s_w, None, p.y) for p in projs]
+        self.lin_items = [[(p.xb[(j + 1) % rot], p.s, p.wq, p.s_w, None, p.y) for p in projs] for j in range(rot)]
         self.lin_batched = all(p.wf == self.wf and p.K % 64 == 0 for p in projs)
         if self.lin_batched:
-            self.ws_lin = B.new_workspace(B.sasq_static_linear_batch_workspace(self.lin_items, self.wf))
+            self.ws_lin = B.new_workspace(B.sasq_static_linear_batch_workspace(self.lin_items[0], self.wf))
         self.ops = sum(p.ops for p in projs)
+        self.step_no = 0
 
 
 def step(layer, ev=None):
     """One pass of the hot path: fake-quant forward and backward (+ds) of every projection input
     (one batched launch each), SGD on the scales, then the static linear of every projection.
     ev: optional dict of event lists for per-call timing."""
+    j = layer.step_no % layer.rot
+    layer.step_no += 1
     if ev is not None:
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-    B.sasq_fakequant_fwd_batch(layer.fwd_items, 8)
-    B.sasq_fakequant_bwd_batch(layer.bwd_items, layer.ws_batch, 8)
+    B.sasq_fakequant_fwd_batch(layer.fwd_items[j], 8)
+    B.sasq_fakequant_bwd_batch(layer.bwd_items[j], layer.ws_batch, 8)
     if ev is not None:
         e1.record()
         ev["fq"].append((e0, e1))
@@ -128,7 +156,7 @@ def step(layer, ev=None):
         if ev is not None:
             e2, e3 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e2.record()
-        B.sasq_static_linear_batch(layer.lin_items, layer.wf, layer.ws_lin)
+        B.sasq_static_linear_batch(layer.lin_items[j], layer.wf, layer.ws_lin)
         if ev is not None:
             e3.record()
             ev["lin_batch"].append((e2, e3))
@@ -137,34 +165,36 @@ def step(layer, ev=None):
         if ev is not None:
             e2, e3 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e2.record()
-        B.sasq_static_linear(p.x, p.s, p.wq, p.s_w, None, p.y, p.wf, p.ws_lin)
+        B.sasq_static_linear(p.xb[(j + 1) % layer.rot], p.s, p.wq, p.s_w, None, p.y, p.wf, p.ws_lin)
         if ev is not None:
             e3.record()
             ev["lin"].append((e2, e3, p))
 
 
-def step_unbatched(projs, ws_bwd, ev=None):
+def step_unbatched(layer, ws_bwd, ev=None):
     """The same pass with one launch per tensor and call (--unbatched)."""
-    for p in projs:
+    j = layer.step_no % layer.rot
+    layer.step_no += 1
+    for p in layer.projs:
         if ev is not None:
             e0, e1, e2, e3 = (torch.cuda.Event(enable_timing=True) for _ in range(4))
             e0.record()
-        B.sasq_fakequant_fwd(p.x, p.s, p.xhat, None, 8)
-        B.sasq_fakequant_bwd(p.x, p.dy, p.s, p.dx, p.ds, ws_bwd, 8)
+        B.sasq_fakequant_fwd(p.xf[j], p.s, p.xhat[j], None, 8)
+        B.sasq_fakequant_bwd(p.xb[j], p.dy[j], p.s, p.dx[j], p.ds, ws_bwd, 8)
         if ev is not None:
             e1.record()
         B.sasq_scale_sgd(p.s, p.ds, LR)
         if ev is not None:
             e2.record()
-        B.sasq_static_linear(p.x, p.s, p.wq, p.s_w, None, p.y, p.wf, p.ws_lin)
+        B.sasq_static_linear(p.xb[(j + 1) % layer.rot], p.s, p.wq, p.s_w, None, p.y, p.wf, p.ws_lin)
         if ev is not None:
             e3.record()
             ev["fq_each"].append((e0, e1, p))
             ev["lin"].append((e2, e3, p))
 
 
-def cpu_baseline(cfg, rows: int):
-    """The CPU oracle, as it stands, on the first `rows` tokens of every projection's input."""
+def _oracle_step(cfg, rows: int):
+    """The CPU oracle, as it stands, on the first `rows` tokens of every projection's input: seconds, operations."""
     import oracle
     t_total, ops = 0.0, 0.0
     for proj in cfg.projs:
@@ -180,25 +210,58 @@ def cpu_baseline(cfg, rows: int):
         oracle.static_linear(x, s1, wq, s_w, None, 8, cfg.w_fmt, cfg.dtype, want_acc=False, want_xq=False)
         t_total += time.perf_counter() - t0
         ops += 2.0 * rows * proj.N * cfg.K_of(proj)
-    return {"value": ops / t_total / 1e12, "unit": "TOPS", "cores": oracle.threads(), "kind": "oracle",
+    return t_total, ops
+
+
+def cpu_baseline(cfg, rows: int):
+    """The oracle timed on all host cores (on `rows` tokens) and on one thread (on rows / cores tokens, so
+    that both legs take about the same time).  The oracle is not changed or tuned for this; the thread count
+    of its OpenMP loops is limited from outside for the second leg."""
+    import oracle
+    from threadpoolctl import threadpool_limits
+    cores = oracle.threads()
+    t_all, ops_all = _oracle_step(cfg, rows)
+    rows1 = max(16, rows // max(cores, 1))
+    with threadpool_limits(limits=1, user_api="openmp"):
+        one = oracle.threads()
+        t_one, ops_one = _oracle_step(cfg, rows1)
+    return {"value": ops_all / t_all / 1e12, "unit": "TOPS", "cores": cores, "kind": "oracle",
             "sample": f"first {rows} of {cfg.M} tokens of every projection, whole step "
-                      f"(fake-quant fwd+bwd, SGD, static linear); {t_total:.1f} s"}
+                      f"(fake-quant fwd+bwd, SGD, static linear); {t_all:.1f} s",
+            "single_thread": {"value": ops_one / t_one / 1e12, "unit": "TOPS", "cores": one,
+                              "sample": f"first {rows1} tokens, same step; {t_one:.1f} s"}}
+
+
+def load_probe():
+    """The benchmark's register-only MFMA loop (paper_2512_14481_amd/bench_csrc, built by the package's build step
+    into libsasq_bench.so): tooling of this script, not an entry point of the SASQ library."""
+    path = os.path.join(ROOT, "paper_2512_14481_amd", "libsasq_bench.so")
+    if not os.path.exists(path):
+        sys.exit(f"bench.py: {path} is missing: build it with `python -m paper_2512_14481_amd.build`")
+    fn = ctypes.CDLL(path).sasq_bench_mfma_probe
+    fn.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    fn.restype = ctypes.c_int
+    return fn
 
 
 def mfma_peak():
     """What the part's matrix units sustain on their own (register-only loop, GEMM register pattern),
     per operand pattern: TOP/s of each of 80 back-to-back launches (about 0.5 s of load per pattern)."""
+    probe = load_probe()
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
     sink = torch.empty(65536, dtype=torch.int32, device="cuda")
     iters, launches = 20000, 80
     out = {"metric": "register-only MFMA loop, sustained", "unit": "TOP/s (TFLOP/s for f16)", "iters_per_launch": iters,
            "launches": launches, "patterns": {}}
-    for kind, name, ops in ((0, "i8 zeros", 65536.0), (1, "i8 random bits", 65536.0), (2, "i8 GEMM-like codes", 65536.0),
-                            (3, "f16 small random values", 32768.0)):
+    for kind, name, ops in ((0, "i8 32x32x32 zeros", 65536.0), (1, "i8 32x32x32 random bits", 65536.0),
+                            (2, "i8 32x32x32 GEMM-like codes", 65536.0), (4, "i8 16x16x64 GEMM-like codes", 131072.0),
+                            (3, "f16 32x32x16 small random values", 32768.0)):
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(launches + 1)]
         torch.cuda.synchronize()
         ev[0].record()
         for l in range(launches):
-            B.sasq_mfma_probe(kind, iters, sink)
+            if probe(kind, iters, ctypes.c_void_p(sink.data_ptr()), stream) != 0:
+                sys.exit("bench.py: the MFMA probe rejected its arguments or failed to launch")
             ev[l + 1].record()
         torch.cuda.synchronize()
         tops = [1024.0 * iters * 16 * ops / (ev[l].elapsed_time(ev[l + 1]) * 1e-3) / 1e12 for l in range(launches)]
@@ -213,8 +276,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--settle-steps", type=int, default=100,
-                    help="untimed steps before the timed region in all, warm-up included (0: only the warm-up steps)")
+    ap.add_argument("--settle-steps", type=int, default=200,
+                    help="after the timed region asked for, keep stepping until this many steps have run in all, then "
+                         "time K steps again and report them as `settled` (0: skip)")
+    ap.add_argument("--rotate", type=int, default=2,
+                    help="copies of every activation-sized tensor per direction, used in turn (cold buffers); 1: one copy (warm)")
     ap.add_argument("--config", default="c3_mlp7b")
     ap.add_argument("--cpu-rows", type=int, default=4096)
     ap.add_argument("--no-cpu", action="store_true")
@@ -237,11 +303,16 @@ def main():
         return
 
     cfg = wl.CONFIGS[a.config]
+    rot = max(1, a.rotate)
     ws_small = B.new_workspace(max(B.sasq_absmax_scale_workspace(1, 1), B.sasq_fakequant_bwd_workspace(1, 1)))
-    acts = {act.name: dev16(wl.activation(cfg, act.name), cfg.dtype) for act in cfg.acts}
-    projs = [Projection(cfg, p, acts[p.x], ws_small) for p in cfg.projs]
-    layer = Layer(projs)
-    run_step = (lambda ev=None: step_unbatched(projs, ws_small, ev)) if a.unbatched else (lambda ev=None: step(layer, ev))
+    acts_f, acts_b = {}, {}
+    for act in cfg.acts:
+        x0 = dev16(wl.activation(cfg, act.name), cfg.dtype)
+        acts_f[act.name] = [x0] + [x0.clone() for _ in range(rot - 1)]
+        acts_b[act.name] = [x0.clone() for _ in range(rot)] if rot > 1 else [x0]
+    projs = [Projection(cfg, p, acts_f[p.x], acts_b[p.x], ws_small, rot) for p in cfg.projs]
+    layer = Layer(projs, rot)
+    run_step = (lambda ev=None: step_unbatched(layer, ws_small, ev)) if a.unbatched else (lambda ev=None: step(layer, ev))
     torch.cuda.synchronize()
 
     if a.calib:
@@ -250,60 +321,73 @@ def main():
         dst.copy_(src)                                 # 1 GiB read + 1 GiB written by a plain copy kernel
         torch.cuda.synchronize()
         del src, dst
-    # The GEMM's time settles only after about 80 steps of continuous load (power management); a caller
-    # that asks for a short warm-up still gets the settled state: the same step is run, untimed, until
-    # `settle_steps` steps have gone by in all, then the W warm-up steps proper.
-    settle = max(0, a.settle_steps - a.warmup)
-    for _ in range(settle):
-        run_step()
+
+    total_ops = sum(p.ops for p in projs)
+
+    def timed(steps):
+        """Time `steps` steps (host clock around the loop, events around the calls inside)."""
+        layer.s_all.copy_(layer.s0_all)               # every timed run starts from the same scales
+        torch.cuda.synchronize()
+        ev = {"fq": [], "fq_each": [], "lin": [], "lin_batch": []}
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run_step(ev)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        r = {"ev": ev, "ms_per_step": dt / steps * 1e3}
+        if ev["lin_batch"]:
+            lin_all = sorted(e0.elapsed_time(e1) for e0, e1 in ev["lin_batch"])
+            r["lin_ops_per_call"] = total_ops
+        else:
+            lin_all = sorted(e0.elapsed_time(e1) for e0, e1, _ in ev["lin"])
+            r["lin_ops_per_call"] = total_ops / len(projs)     # average over the projections' calls
+        r["lin_all"] = lin_all
+        r["lin_avg_ms"] = sum(lin_all) / len(lin_all)
+        r["lin_tops"] = r["lin_ops_per_call"] / (r["lin_avg_ms"] * 1e-3) / 1e12
+        if a.unbatched:
+            fq_all = sorted(e0.elapsed_time(e1) for e0, e1, _ in ev["fq_each"])
+            r["fq_ms_per_step"] = sum(fq_all) / steps
+        else:
+            fq_all = sorted(e0.elapsed_time(e1) for e0, e1 in ev["fq"])
+            r["fq_ms_per_step"] = sum(fq_all) / len(fq_all)
+        r["fq_all"] = fq_all
+        r["fq_gbps"] = layer.fq_bytes / (r["fq_ms_per_step"] * 1e-3) / 1e9
+        r["fq_gbps_moved"] = (layer.fq_bytes if a.unbatched else layer.fq_bytes_moved) / (r["fq_ms_per_step"] * 1e-3) / 1e9
+        return r
+
+    # 1. exactly what was asked for: W untimed warm-up steps, then K timed steps
     for _ in range(a.warmup):
         run_step()
-    layer.s_all.copy_(layer.s0_all)                   # every timed run starts from the same scales
-    torch.cuda.synchronize()
-    ev = {"fq": [], "fq_each": [], "lin": [], "lin_batch": []}
-    t0 = time.perf_counter()
-    for _ in range(a.steps):
-        run_step(ev)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    if not a.unbatched:
-        # per-projection fake-quant figures: the unbatched pass once more, outside the timed region
-        layer.s_all.copy_(layer.s0_all)
-        for _ in range(3):
-            step_unbatched(projs, ws_small, ev)
-        torch.cuda.synchronize()
-        if not layer.lin_batched:
-            ev["lin"] = ev["lin"][:a.steps * len(projs)]
+    asked = timed(a.steps)
+    # 2. the same measurement once the part has settled under the load.  The GEMM's time keeps moving for
+    #    about 80 steps of continuous load (power management first over-throttles, then relaxes); a serving or
+    #    training job sits in that state.  Steps run so far count towards the settling.
+    done = a.warmup + a.steps
+    for _ in range(max(0, a.settle_steps - done)):
+        run_step()
+    settled = timed(a.steps) if a.settle_steps > 0 else None
 
-    ms_per_step = dt / a.steps * 1e3
-    total_ops = sum(p.ops for p in projs)
+    # per-projection figures: the unbatched pass, outside the timed regions
+    ev = asked["ev"]
+    if not a.unbatched:
+        layer.s_all.copy_(layer.s0_all)
+        ev = {"fq": [], "fq_each": [], "lin": [], "lin_batch": []}
+        for _ in range(2 * rot + 1):
+            step_unbatched(layer, ws_small, ev)
+        torch.cuda.synchronize()
     lin_ms = [(e0.elapsed_time(e1), p) for e0, e1, p in ev["lin"]]
     fq_ms = [(e0.elapsed_time(e1), p) for e0, e1, p in ev["fq_each"]]
-    if ev["lin_batch"]:
-        # the roofline figure is the batched call: the layer's activation pre-pass + one GEMM launch
-        lin_ops_per_call = total_ops
-        lin_avg_ms = sum(e0.elapsed_time(e1) for e0, e1 in ev["lin_batch"]) / len(ev["lin_batch"])
-    else:
-        lin_ops_per_call = total_ops / len(projs)     # average over the projections' calls
-        lin_avg_ms = sum(t for t, _ in lin_ms) / len(lin_ms)
-    lin_tops = lin_ops_per_call / (lin_avg_ms * 1e-3) / 1e12
-    # spread over the timed steps (median and fastest call)
-    lin_all = sorted(e0.elapsed_time(e1) for e0, e1 in ev["lin_batch"]) if ev["lin_batch"] else sorted(t for t, _ in lin_ms)
-    fq_all = sorted(e0.elapsed_time(e1) for e0, e1 in ev["fq"]) if ev["fq"] else []
     med = lambda v: v[len(v) // 2] if v else None
-    if a.unbatched:
-        fq_gbps = sum(p.fq_bytes for _, p in fq_ms) / (sum(t for t, _ in fq_ms) * 1e-3) / 1e9
-    else:
-        fq_gbps = layer.fq_bytes * len(ev["fq"]) / (sum(e0.elapsed_time(e1) for e0, e1 in ev["fq"]) * 1e-3) / 1e9
     per_proj = {}
-    for name in [p.name for p in projs]:
-        tl = [t for t, p in lin_ms if p.name == name]
-        tf = [t for t, p in fq_ms if p.name == name]
-        pp = next(p for p in projs if p.name == name)
-        per_proj[name] = {"linear_us": round(1e3 * sum(tl) / len(tl), 2),
-                          "linear_tops": round(pp.ops / (sum(tl) / len(tl) * 1e-3) / 1e12, 1),
-                          "fakequant_fwd_bwd_us": round(1e3 * sum(tf) / len(tf), 2),
-                          "fakequant_gbps": round(pp.fq_bytes / (sum(tf) / len(tf) * 1e-3) / 1e9, 1)}
+    for pp in projs:
+        tl = [t for t, p in lin_ms if p.name == pp.name]
+        tf = [t for t, p in fq_ms if p.name == pp.name]
+        per_proj[pp.name] = {"linear_us": round(1e3 * sum(tl) / len(tl), 2),
+                             "linear_tops": round(pp.ops / (sum(tl) / len(tl) * 1e-3) / 1e12, 1),
+                             "fakequant_fwd_bwd_us": round(1e3 * sum(tf) / len(tf), 2),
+                             "fakequant_gbps": round(pp.fq_bytes / (sum(tf) / len(tf) * 1e-3) / 1e9, 1),
+                             "fakequant_frac": round(pp.fq_bytes / (sum(tf) / len(tf) * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+    ms_per_step = asked["ms_per_step"]
 
     # per-channel fake-quant (the granularity of the paper's main runs), measured after the timed
     # region on the same tensors: one scale per column, ds a column reduction
@@ -315,13 +399,13 @@ def main():
             dsv = torch.zeros(p.K, dtype=torch.float32, device="cuda")
             wsp = B.new_workspace(B.sasq_fakequant_bwd_pc_workspace(p.M, p.K))
             for _ in range(2):
-                B.sasq_fakequant_fwd_pc(p.x, sv, p.xhat, None, 8)
-                B.sasq_fakequant_bwd_pc(p.x, p.dy, sv, p.dx, dsv, wsp, 8)
+                B.sasq_fakequant_fwd_pc(p.x, sv, p.xhat[0], None, 8)
+                B.sasq_fakequant_bwd_pc(p.x, p.dy[0], sv, p.dx[0], dsv, wsp, 8)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(5):
-                B.sasq_fakequant_fwd_pc(p.x, sv, p.xhat, None, 8)
-                B.sasq_fakequant_bwd_pc(p.x, p.dy, sv, p.dx, dsv, wsp, 8)
+                B.sasq_fakequant_fwd_pc(p.x, sv, p.xhat[0], None, 8)
+                B.sasq_fakequant_bwd_pc(p.x, p.dy[0], sv, p.dx[0], dsv, wsp, 8)
             e1.record()
             torch.cuda.synchronize()
             tot_ms += e0.elapsed_time(e1) / 5
@@ -332,8 +416,8 @@ def main():
         # the same for all three projection inputs of the layer in one launch each way
         svs = [p.s.expand(p.K).contiguous() for p in projs]
         dsvs = [torch.zeros(p.K, dtype=torch.float32, device="cuda") for p in projs]
-        fwd_items = [(p.x, svs[i], p.xhat) for i, p in enumerate(projs)]
-        bwd_items = [(p.x, p.dy, svs[i], p.dx, dsvs[i]) for i, p in enumerate(projs)]
+        fwd_items = [(p.x, svs[i], p.xhat[0]) for i, p in enumerate(projs)]
+        bwd_items = [(p.x, p.dy[0], svs[i], p.dx[0], dsvs[i]) for i, p in enumerate(projs)]
         wsb = B.new_workspace(B.sasq_fakequant_bwd_pc_batch_workspace(bwd_items))
         for _ in range(2):
             B.sasq_fakequant_fwd_pc_batch(fwd_items, 8)
@@ -440,40 +524,63 @@ def main():
         bwd_lin["frac"] = round(bwd_lin["achieved"] / F16_MFMA_PEAK_TFLOPS, 4)
         bwd_lin["note"] = f"sasq_linear_bwd_input, {cfg.dtype} MFMA with fp32 accumulation, warm repeat of 5 per projection"
 
+    def roofline_of(r):
+        lin_all = r["lin_all"]
+        return {"achieved": round(r["lin_tops"], 1), "frac": round(r["lin_tops"] / INT8_MFMA_PEAK_TOPS, 4),
+                "avg_launch_us": round(r["lin_avg_ms"] * 1e3, 2), "median_launch_us": round(med(lin_all) * 1e3, 2),
+                "min_launch_us": round(lin_all[0] * 1e3, 2)}
+
+    def fakequant_of(r):
+        return {"achieved": round(r["fq_gbps"], 1), "frac": round(r["fq_gbps"] / HBM_PEAK_GBPS, 4),
+                "achieved_bytes_moved": round(r["fq_gbps_moved"], 1), "frac_bytes_moved": round(r["fq_gbps_moved"] / HBM_PEAK_GBPS, 4),
+                "us_per_step": round(r["fq_ms_per_step"] * 1e3, 2), "median_us": round(med(r["fq_all"]) * 1e3, 2),
+                "min_us": round(r["fq_all"][0] * 1e3, 2)}
+
+    batched = bool(asked["ev"]["lin_batch"])
+    calls = 1 if batched else len(projs)
+    roof = {"bound": "mfma",
+            "kernel": ("sasq_static_linear_batch: all projections of the layer, one activation-quantize launch + one "
+                       "int8 MFMA GEMM launch with fused dequantize" if batched else
+                       "sasq_static_linear (activation quantize + int8 MFMA GEMM + dequant)"),
+            "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s"}
+    roof.update(roofline_of(asked))
+    roof.update({"sustained_mfma_only": INT8_MFMA_SUSTAINED_TOPS,
+                 "frac_of_sustained": round(asked["lin_tops"] / INT8_MFMA_SUSTAINED_TOPS, 4),
+                 "traffic": (C3_LINEAR_BATCH_TRAFFIC_BYTES if batched else C3_LINEAR_TRAFFIC_BYTES) if cfg.name == "c3_mlp7b" else None,
+                 "traffic_unit": "bytes per call", "traffic_source": TRAFFIC_SOURCE if cfg.name == "c3_mlp7b" else None,
+                 "algorithmic_bytes": int(sum(p.lin_bytes for p in projs) / calls),
+                 "algorithmic_bytes_formula": "sum over projections of e*M*K + w*N*K + e*M*N + 4*N (e = 2, w = 1 or 0.5)",
+                 "staging_bytes": int(sum(p.lin_staging_bytes for p in projs) / calls),
+                 "staging_note": "int8 activation codes written by the library's pre-pass and read by its GEMM (not algorithmic)"})
+    fq = {"bound": "hbm", "peak": HBM_PEAK_GBPS, "unit": "GB/s", "bytes_per_element": 10}
+    fq.update(fakequant_of(asked))
+    fq["bytes_counted"] = int(layer.fq_bytes)
+    fq["bytes_moved"] = int(layer.fq_bytes if a.unbatched else layer.fq_bytes_moved)
+    fq["protocol"] = (f"cold: {rot} copies of x, dy, x', dx per direction used in turn; whatever a launch reads was last touched "
+                      "more than 1 GB of traffic earlier" if rot > 1 else "warm: one copy of every tensor")
+    fq["note"] = ("achieved/frac count 10 B/element per operator (fwd 2+2, bwd 2+2+2); operators in front of projections that "
+                  "share an activation read it once in the forward launch: *_bytes_moved count what is really moved; " +
+                  ("events around each tensor's pair of launches" if a.unbatched else
+                   "one batched launch each way for all projection inputs of the layer, events around the two launches; "
+                   "per_projection holds the one-launch-per-tensor figures measured after the timed region"))
     out = {
         "metric": "static-scale W8A8 linear TOPS (% int8 MFMA peak); fake-quant fwd+bwd GB/s",
         "value": round(total_ops / (ms_per_step * 1e-3) / 1e12, 2),
         "unit": "TOPS",
-        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "settle_steps": settle, "ms_per_step": round(ms_per_step, 4),
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: LLaMA-2-7B MLP, M=4096 tokens, gate/up 4096->11008, down 11008->4096, "
                                "fp16 activations, int8 per-channel weights, per-tensor static scale; "
                                "step = fake-quant fwd + STE bwd + ds + SGD + static W8A8 linear per projection"
-                   if cfg.name == "c3_mlp7b" else cfg.name},
-        "roofline": {"bound": "mfma",
-                     "kernel": ("sasq_static_linear_batch: all projections of the layer, one activation-quantize launch + one "
-                                "int8 MFMA GEMM launch with fused dequantize" if ev["lin_batch"] else
-                                "sasq_static_linear (activation quantize + int8 MFMA GEMM + dequant)"),
-                     "achieved": round(lin_tops, 1), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": round(lin_tops / INT8_MFMA_PEAK_TOPS, 4),
-                     "sustained_mfma_only": INT8_MFMA_SUSTAINED_TOPS,
-                     "frac_of_sustained": round(lin_tops / INT8_MFMA_SUSTAINED_TOPS, 4),
-                     "traffic": (C3_LINEAR_BATCH_TRAFFIC_BYTES if ev["lin_batch"] else C3_LINEAR_TRAFFIC_BYTES) if cfg.name == "c3_mlp7b" else None,
-                     "traffic_unit": "bytes per call (rocprofv3 FETCH_SIZE/WRITE_SIZE, copy-calibrated)",
-                     "algorithmic_bytes": int(sum(3 * p.M * p.K + p.M * p.K + p.wq.numel() + 2 * p.M * p.N + 4 * p.N
-                                                  for p in projs) / (1 if ev["lin_batch"] else len(projs))),
-                     "avg_launch_us": round(lin_avg_ms * 1e3, 2),
-                     "median_launch_us": round(med(lin_all) * 1e3, 2), "min_launch_us": round(lin_all[0] * 1e3, 2)},
-        "fakequant": {"bound": "hbm", "achieved": round(fq_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                      "frac": round(fq_gbps / HBM_PEAK_GBPS, 4),
-                      "bytes_per_element": 10,
-                      "median_us": round(med(fq_all) * 1e3, 2) if fq_all else None,
-                      "min_us": round(fq_all[0] * 1e3, 2) if fq_all else None,
-                      "note": ("fwd (2+2 B/el) + bwd (2+2+2 B/el); " +
-                               ("events around each tensor's pair of launches" if a.unbatched else
-                                "one batched launch each for all projection inputs of the layer, events around the two launches; "
-                                "per_projection holds the one-launch-per-tensor figures measured after the timed region"))},
+                   if cfg.name == "c3_mlp7b" else cfg.name,
+                   "buffers": fq["protocol"]},
+        "roofline": roof,
+        "fakequant": fq,
+        "settled": None if settled is None else {
+            "note": f"the same {a.steps} timed steps repeated after {max(done, a.settle_steps)} steps of continuous load",
+            "value": round(total_ops / (settled["ms_per_step"] * 1e-3) / 1e12, 2), "ms_per_step": round(settled["ms_per_step"], 4),
+            "roofline": roofline_of(settled), "fakequant": fakequant_of(settled)},
         "per_projection": per_proj,
         "fakequant_per_channel": pc,
         "static_linear_grouped": grouped,

@@ -404,20 +404,6 @@ size_t sasq_absmax_scale_workspace(int64_t rows, int64_t cols);
 int sasq_absmax_scale(const void* x, float* s, int64_t rows, int64_t cols, int bits,
                       sasq_dtype dt, void* workspace, size_t workspace_bytes, void* stream);
 
-/*
- * Diagnostic for the benchmark (not part of the method): one launch of a register-only MFMA loop
- * in the GEMM kernels' register pattern (256 workgroups of 4 waves, 16 accumulator tiles of 32x32
- * per wave, `iters` x 16 MFMAs per wave; no LDS or memory traffic in the loop), so that the GEMMs'
- * throughput can be put next to what the matrix units of the part sustain on their own.
- *   kind   0: v_mfma_i32_32x32x32_i8 on zero operands, 1: on random bits, 2: on GEMM-like codes
- *          (activation bytes in {-1, 0, 0, 1}, weight bytes in [-32, 31]); 3: v_mfma_f32_32x32x16_f16
- *          on small random values.  Operations per launch: 1024 waves x iters x 16 MFMAs x 65536
- *          for kinds 0-2, half that for kind 3.
- *   iters  1 .. 2^22
- *   sink   device, 65536 ints, written (keeps the loop alive)
- */
-int sasq_mfma_probe(int kind, int iters, int* sink, void* stream);
-
 #ifdef __cplusplus
 }
 #endif

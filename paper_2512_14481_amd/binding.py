@@ -96,7 +96,6 @@ def _lib() -> ctypes.CDLL:
         L.sasq_bwd_weight_bytes.argtypes = [i64, i64]
         L.sasq_prepare_bwd_weight.argtypes = [vp, vp, vp, i64, i64, i32, i32, vp]
         L.sasq_linear_bwd_input.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp]
-        L.sasq_mfma_probe.argtypes = [i32, i32, vp, vp]
         L.sasq_absmax_scale_workspace.restype = sz
         L.sasq_absmax_scale_workspace.argtypes = [i64, i64]
         L.sasq_absmax_scale.argtypes = [vp, vp, i64, i64, i32, i32, vp, sz, vp]
@@ -486,14 +485,6 @@ def sasq_linear_bwd_input(dy: torch.Tensor, wt: torch.Tensor, dx: torch.Tensor, 
         raise ValueError("wt must have sasq_bwd_weight_bytes(N, K) bytes")
     _check(_lib().sasq_linear_bwd_input(_ptr(dy), _ptr(wt), _ptr(dx), _ptr(acc_out), M, N, K, _dt(dy), _stream()),
            "sasq_linear_bwd_input")
-
-
-def sasq_mfma_probe(kind: int, iters: int, sink: torch.Tensor) -> None:
-    """Diagnostic: one launch of the register-only MFMA loop (see the header)."""
-    _want(sink, torch.int32, "sink")
-    if sink.numel() < 65536:
-        raise ValueError("sink must hold 65536 ints")
-    _check(_lib().sasq_mfma_probe(kind, iters, _ptr(sink), _stream()), "sasq_mfma_probe")
 
 
 def sasq_absmax_scale_workspace(rows: int, cols: int) -> int:

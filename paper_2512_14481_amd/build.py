@@ -10,6 +10,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsasq.so")
+BENCH_CSRC = os.path.join(PKG, "bench_csrc")
+BENCH_LIB = os.path.join(PKG, "libsasq_bench.so")    # benchmark tooling (register-only MFMA probe), not part of the C ABI
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -70,6 +72,16 @@ def build(verbose: bool = True, incremental: bool = False) -> str:
         if verbose:
             print(" ".join(link), flush=True)
         subprocess.run(link, check=True)
+    # the benchmark's own tooling: one small library beside the product
+    bench_srcs = sorted(glob.glob(os.path.join(BENCH_CSRC, "*.hip")))
+    if bench_srcs and not (incremental and os.path.exists(BENCH_LIB) and
+                           all(os.path.getmtime(f) <= os.path.getmtime(BENCH_LIB) for f in bench_srcs)):
+        cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+               "-o", BENCH_LIB] + bench_srcs
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
     return LIB
 
 
