@@ -1024,6 +1024,12 @@ static void launch_mfma_grouped(const void* xin, const void* wq, const float* s_
     // the other wave on its SIMD; measured 1.3-1.6 x faster than 128x256 tiles at every group size.
     const int tile = tuning(SASQ_TUNE_LINEAR_TILE) == 2 ? 1 : 2;
     auto acc_out = reinterpret_cast<int32_t*>(f_out);
+    if (use_k64(X_PREQ, WMODE)) {
+        GemmK64Args a{static_cast<const int8_t*>(xin), static_cast<const uint8_t*>(wq), s_g, s_w, bias,
+                      static_cast<uint16_t*>(y), acc_out, M, N, K};
+        launch_gemm_k64_grouped(a, (sasq_dtype)DT, WMODE == W_I8B, tile, group_tiles, st);
+        return;
+    }
     if (tile == 1) launch_tiles<DT, X_PREQ, WMODE, 128, 256, true>(xin, wq, s_g, s_w, bias, y, acc_out, M, N, K, a_bits, st, group_tiles);
     else           launch_tiles<DT, X_PREQ, WMODE, 128, 128, true>(xin, wq, s_g, s_w, bias, y, acc_out, M, N, K, a_bits, st, group_tiles);
 }

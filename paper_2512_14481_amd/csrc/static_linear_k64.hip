@@ -36,14 +36,21 @@ __device__ __forceinline__ void lds_load16(uint32_t lds_addr, const void* base, 
                  :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
 }   // row-major int8 / pre-arranged int8 (values shared with static_linear.hip)
 
-template <int DT, int WMODE, int BM, int BN, bool ROWS>
+// GROUPED (Sec. 3, Eq. 3): one activation factor per group of `group_tiles` K tiles; s_ptr then
+// points at the factors.  The int32 accumulators cover one group at a time (a group's first K tile
+// multiplies into a zero accumulator operand) and are folded into fp32 sums at its end,
+// f = fma(fl32(acc), s_g, f) in ascending group order; the epilogue applies s_w and the bias to f,
+// and acc_out receives f (as float bits).  Tiles of 128 rows only (f doubles the accumulator registers);
+// with 128x128 tiles two waves share a SIMD and one wave's fold runs under the other's MFMAs.
+template <int DT, int WMODE, int BM, int BN, bool ROWS, bool GROUPED = false>
 __device__ __forceinline__
 void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq,
                    const float* __restrict__ s_ptr, const float* __restrict__ s_w,
                    const float* __restrict__ bias, uint16_t* __restrict__ y,
                    int32_t* __restrict__ acc_out, int M, int N, int K,
-                   int tm, int tn, char* lds)
+                   int tm, int tn, char* lds, int group_tiles = 0)
 {
+    static_assert(!GROUPED || (BM == 128 && !ROWS), "grouped factors: 128-row tiles");
     using S = Store16<DT>;
     using T = Tile<BM, BN>;
     constexpr int MF = BM / 32, NF = BN / 32;          // 16x16 tiles per wave along m, n
@@ -94,6 +101,11 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     };
 
     i32x4 acc[NF][MF];
+    f32x4 fsum[GROUPED ? NF : 1][GROUPED ? MF : 1];           // fp32 sums over groups
+#pragma unroll
+    for (int g = 0; g < (GROUPED ? NF : 1); ++g)
+#pragma unroll
+        for (int b = 0; b < (GROUPED ? MF : 1); ++b) fsum[g][b] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
     // ---- K pipeline ----
     // Iteration i multiplies K tile i from fragment set i&1 while it reads the fragments of tile
@@ -149,6 +161,29 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     using C1 = std::integral_constant<int, 1>;
     using Yes = std::true_type;
     using No = std::false_type;
+    // one K tile; with grouped factors also the group bookkeeping (all of it uniform)
+    int in_group = 0, group_idx = 0;
+    auto step = [&](int i, auto cur_tag, auto first_tag, auto tail_tag) {
+        if constexpr (!GROUPED) {
+            iteration(i, cur_tag, first_tag, tail_tag);
+        } else {
+            if (in_group == 0) iteration(i, cur_tag, Yes{}, tail_tag);
+            else               iteration(i, cur_tag, No{}, tail_tag);
+            if (++in_group == group_tiles) {
+                const float sg = s_ptr[group_idx];
+#pragma unroll
+                for (int g = 0; g < NF; ++g)
+#pragma unroll
+                    for (int b = 0; b < MF; ++b)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            fsum[GROUPED ? g : 0][GROUPED ? b : 0][e] =
+                                __builtin_fmaf((float)acc[g][b][e], sg, fsum[GROUPED ? g : 0][GROUPED ? b : 0][e]);
+                in_group = 0;
+                ++group_idx;
+            }
+        }
+    };
     // fill: the first four tiles requested, tile 0 landed for everyone, its fragments read
     const int nfill = min(KT, 4);
     for (int t = 0; t < nfill; ++t)
@@ -166,14 +201,14 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     // written out so that every copy of the loop body knows its fragment set at compile time.
     const int steady = KT >= 6 ? ((KT - 4) & ~1) : 0;
     if (steady > 0) {
-        iteration(0, C0{}, Yes{}, No{});
-        iteration(1, C1{}, No{}, No{});
+        step(0, C0{}, Yes{}, No{});
+        step(1, C1{}, No{}, No{});
 #pragma unroll 1
         for (int it = 2; it < steady; it += 2) {
-            iteration(it, C0{}, No{}, No{});
-            iteration(it + 1, C1{}, No{}, No{});
+            step(it, C0{}, No{}, No{});
+            step(it + 1, C1{}, No{}, No{});
         }
-    } else {
+    } else if (!GROUPED) {
 #pragma unroll
         for (int g = 0; g < NF; ++g)
 #pragma unroll
@@ -190,14 +225,14 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     if (cols_inside)
         lds_load16(lds_base - (uint32_t)wave * 1024u + T::kLds + (uint32_t)wave * kFacBytes, s_w + wn0,
                    (uint32_t)(lane & (BN / 8 - 1)) * 16u);   // lanes past BN/8 fetch the same factors again: no lane reads past the block
-    iteration(steady, C0{}, No{}, Yes{});                       // KT - steady is 1 .. 5
+    step(steady, C0{}, No{}, Yes{});                            // KT - steady is 1 .. 5
     if (steady + 1 < KT) {
-        iteration(steady + 1, C1{}, No{}, Yes{});
+        step(steady + 1, C1{}, No{}, Yes{});
         if (steady + 2 < KT) {
-            iteration(steady + 2, C0{}, No{}, Yes{});
+            step(steady + 2, C0{}, No{}, Yes{});
             if (steady + 3 < KT) {
-                iteration(steady + 3, C1{}, No{}, Yes{});
-                if (steady + 4 < KT) iteration(steady + 4, C0{}, No{}, Yes{});
+                step(steady + 3, C1{}, No{}, Yes{});
+                if (steady + 4 < KT) step(steady + 4, C0{}, No{}, Yes{});
             }
         }
     }
@@ -208,7 +243,7 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
 
     // ---- epilogue: Y = fl32(fl32(acc) * fl32(s * s_w[n])) (+ bias), staged through LDS in [m][n]
     // order as 16-bit values, written with 128-bit stores, BN contiguous bytes per row ----
-    const float s = ROWS ? 1.0f : *s_ptr;
+    const float s = (ROWS || GROUPED) ? 1.0f : *s_ptr;
     const bool has_bias = bias != nullptr;
     char* epi = &lds[wave * T::kEpiBytes];
     float srow[MF];                                            // ROWS: the factor of each row this lane holds
@@ -228,12 +263,12 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
                 f32x4 bv = {0.0f, 0.0f, 0.0f, 0.0f};
                 if (BIAS) bv = *reinterpret_cast<const f32x4*>(bias + wn0 + nl);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) { cs[e] = ROWS ? sv[e] : s * sv[e]; bs[e] = bv[e]; }
+                for (int e = 0; e < 4; ++e) { cs[e] = (ROWS || GROUPED) ? sv[e] : s * sv[e]; bs[e] = bv[e]; }
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int ne = min(wn0 + nl + e, N - 1);
-                    cs[e] = ROWS ? s_w[ne] : s * s_w[ne];
+                    cs[e] = (ROWS || GROUPED) ? s_w[ne] : s * s_w[ne];
                     bs[e] = BIAS ? bias[ne] : 0.0f;
                 }
             }
@@ -244,7 +279,8 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float cc = ROWS ? srow[b] * cs[e] : cs[e];
-                    float v = (float)acc[g][b][e] * cc;
+                    float v = GROUPED ? fsum[GROUPED ? g : 0][GROUPED ? b : 0][e] * cc      // Y = fl32(f * s_w[n])
+                                      : (float)acc[g][b][e] * cc;
                     if (BIAS) v = v + bs[e];
                     yv[e] = v;
                 }
@@ -300,7 +336,8 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
                 const int m = wm0 + b * 16 + frow, n = wn0 + g * 16 + 4 * fq;
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    if (m < M && n + e < N) acc_out[(int64_t)m * N + n + e] = acc[g][b][e];
+                    if (m < M && n + e < N)
+                        acc_out[(int64_t)m * N + n + e] = GROUPED ? __float_as_int(fsum[GROUPED ? g : 0][GROUPED ? b : 0][e]) : acc[g][b][e];
             }
     }
 }
@@ -317,6 +354,20 @@ void gemm_k64_kernel(const int8_t* __restrict__ xq, const uint8_t* __restrict__ 
     int tm, tn;
     if (!tile_of_block((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
     gemm_k64_body<DT, WMODE, BM, BN, ROWS>(xq, wq, s_ptr, s_w, bias, y, acc_out, M, N, K, tm, tn, lds);
+}
+
+template <int DT, int WMODE, int BM, int BN>
+__global__ __launch_bounds__(kGemmThreads)
+__attribute__((amdgpu_waves_per_eu(Tile<BM, BN>::kWavesPerSimd, Tile<BM, BN>::kWavesPerSimd)))
+void gemm_k64_grouped_kernel(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq,
+                             const float* __restrict__ s_g, const float* __restrict__ s_w,
+                             const float* __restrict__ bias, uint16_t* __restrict__ y,
+                             int32_t* __restrict__ f_out, int M, int N, int K, int tiles_m, int tiles_n, int group_tiles)
+{
+    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes_k64<BM, BN>()];
+    int tm, tn;
+    if (!tile_of_block((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
+    gemm_k64_body<DT, WMODE, BM, BN, false, true>(xq, wq, s_g, s_w, bias, y, f_out, M, N, K, tm, tn, lds, group_tiles);
 }
 
 // Several projections in one launch, 256x256 tiles: each projection owns a run of workgroup ids
@@ -373,6 +424,28 @@ static void launch_dt(const GemmK64Args& a, bool blocked, int tile, bool rows, h
 {
     if (blocked) { if (rows) launch_tile<DT, KW_I8B, true>(a, tile, st); else launch_tile<DT, KW_I8B, false>(a, tile, st); }
     else         { if (rows) launch_tile<DT, KW_I8, true>(a, tile, st);  else launch_tile<DT, KW_I8, false>(a, tile, st); }
+}
+
+template <int DT, int WMODE, int BM, int BN>
+static void launch_grouped_one(const GemmK64Args& a, int group_tiles, hipStream_t st)
+{
+    const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
+    const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
+    gemm_k64_grouped_kernel<DT, WMODE, BM, BN><<<grid, kGemmThreads, 0, st>>>(
+        a.xq, a.wq, a.s, a.s_w, a.bias, a.y, a.acc_out, (int)a.M, (int)a.N, (int)a.K, tiles_m, tiles_n, group_tiles);
+}
+
+template <int DT>
+static void launch_grouped_dt(const GemmK64Args& a, bool blocked, int tile, int group_tiles, hipStream_t st)
+{
+    if (blocked) { if (tile == 1) launch_grouped_one<DT, KW_I8B, 128, 256>(a, group_tiles, st); else launch_grouped_one<DT, KW_I8B, 128, 128>(a, group_tiles, st); }
+    else         { if (tile == 1) launch_grouped_one<DT, KW_I8, 128, 256>(a, group_tiles, st);  else launch_grouped_one<DT, KW_I8, 128, 128>(a, group_tiles, st); }
+}
+
+void launch_gemm_k64_grouped(const GemmK64Args& a, sasq_dtype dt, bool blocked, int tile, int group_tiles, hipStream_t st)
+{
+    if (dt == SASQ_F16) launch_grouped_dt<SASQ_F16>(a, blocked, tile, group_tiles, st);
+    else                launch_grouped_dt<SASQ_BF16>(a, blocked, tile, group_tiles, st);
 }
 
 void launch_gemm_k64(const GemmK64Args& a, sasq_dtype dt, bool blocked, int tile, bool rows, hipStream_t st)
