@@ -602,8 +602,8 @@ int sasq_oracle_fakequant_bwd_pc(const uint16_t* x, const uint16_t* dy, const fl
 }
 
 /*
- * AdamW step on a vector of scales (the optimiser of the paper's runs: Sec. 5.1 "AdamW ... with a
- * learning rate of 2e-4"; the scales are the only parameters, Sec. 4.2).  Decoupled weight decay:
+ * AdamW step on a vector of scales (the optimiser and learning rate of the paper's runs, Sec. 5.1
+ * "Implementation"; the scales are the only parameters, Sec. 4.2).  Decoupled weight decay:
  *   p <- p - lr*wd*p;  m <- b1*m + (1-b1)*g;  v <- b2*v + (1-b2)*g^2;
  *   p <- p - lr * (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps).
  * Evaluated in fp64 on fp32 state; results rounded once to fp32.

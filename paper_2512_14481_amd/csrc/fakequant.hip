@@ -42,8 +42,9 @@ __device__ __forceinline__ void fwd_vec(const u32x4& in, const QConst& k, u32x4&
 
 // Forward over one tensor by block `block` of the `nblocks` that share it.
 template <int DT, bool CODES>
+// (y may alias x: neither is restrict-qualified.)
 __device__ __forceinline__ void fwd_body(
-    const u32x4* __restrict__ x, const float* __restrict__ s_ptr, u32x4* __restrict__ y,
+    const u32x4* x, const float* __restrict__ s_ptr, u32x4* y,
     u32x2* __restrict__ codes, int64_t nvec, int64_t n, int bits, int block, int nblocks)
 {
     using S = Store16<DT>;
@@ -85,7 +86,7 @@ __device__ __forceinline__ void fwd_body(
 
 template <int DT, bool CODES>
 __global__ __launch_bounds__(kThreads) void fakequant_fwd_kernel(
-    const u32x4* __restrict__ x, const float* __restrict__ s_ptr, u32x4* __restrict__ y,
+    const u32x4* x, const float* __restrict__ s_ptr, u32x4* y,
     u32x2* __restrict__ codes, int64_t nvec, int64_t n, int bits)
 {
     fwd_body<DT, CODES>(x, s_ptr, y, codes, nvec, n, bits, (int)blockIdx.x, (int)gridDim.x);
@@ -127,7 +128,7 @@ template <int DT, int NS>
 __device__ __forceinline__ void fwd_body_shared(const FqBatchItem& it, int bits, int block, int nblocks)
 {
     using S = Store16<DT>;
-    const u32x4* __restrict__ x = it.x;
+    const u32x4* x = it.x;
     const int64_t nvec = it.nvec, n = it.n;
     QConst k[NS];
 #pragma unroll
@@ -231,12 +232,7 @@ __device__ __forceinline__ void publish_and_reduce(double acc, float* __restrict
         double b = 0.0;
 #pragma unroll
         for (int i = 0; i < kThreads / kWave; ++i) b += wave_part[i];
-        __hip_atomic_store(&partials[block], b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // The partial went out as an agent-scope atomic store (written through to where every XCD
-        // sees it); waiting for its acknowledgement orders it before the ticket.  A release fence
-        // here would instead write back this XCD's whole L2 once per block.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        uint32_t ticket = __hip_atomic_fetch_add(ticket_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t ticket = publish_then_ticket(&partials[block], b, ticket_word);
         is_last = (ticket == kTicketBase + (uint32_t)nblocks - 1);
         if (ticket - kTicketBase >= (uint32_t)nblocks)      // workspace was never initialised: fail loudly
             *ds = __uint_as_float(0x7FC00000u);
@@ -333,8 +329,6 @@ __global__ __launch_bounds__(kThreads) void fakequant_bwd_kernel(
     bwd_body<DT, WRITE_DX>(x, dy, s_ptr, dx, ds, ws_head, partials, nvec, n, bits, (int)blockIdx.x, (int)gridDim.x);
 }
 
-// Batched backward: tensor k uses ticket word k of the workspace header and its own run of
-// kMaxReduceBlocks partials.
 // Batched backward: every entry is one operator (sharing the read of x did not pay here: the
 // fused body needs 200 registers and ran 2 % slower than the operators apart); it uses the ticket
 // word and the run of kMaxReduceBlocks partials of its index in the caller's batch.

@@ -1,6 +1,6 @@
-// Per-channel fake quantization: one learned factor per activation column (Sec. 4 "we use
-// per-channel quantization for both activation and weight"; Sec. 2, Fig. 2(b): per-channel = the
-// elements of a column share a factor).  Same element arithmetic as the per-tensor operator
+// Per-channel fake quantization: one learned factor per activation column (the granularity Sec. 4
+// adopts for activations and weights; Sec. 2, Fig. 2(b): per-channel = the elements of a column
+// share a factor).  Same element arithmetic as the per-tensor operator
 // (Sec. 3, Eq. 1; Sec. 4.2, Eq. 4); the scale gradient becomes a column reduction:
 //     ds[k] = sum_m dy[m,k] * (q[m,k] - m[m,k] * x[m,k]/s[k]).
 //
@@ -212,8 +212,9 @@ __device__ __forceinline__ void bwd_pc_body(
             asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(dst), "v"(v) : "memory");
         }
     }
-    // the stores above are agent-scope and acknowledged before the ticket is taken
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // the stores above are agent-scope (sc1: written through to the level all XCDs share) and
+    // acknowledged before the ticket is taken: see publish_then_ticket in sasq_device.h
+    wait_stores_acknowledged();
     __syncthreads();
     if (threadIdx.x == 0) {
         const uint32_t ticket = __hip_atomic_fetch_add(&tickets[col_block], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -133,12 +133,7 @@ __global__ __launch_bounds__(kPrepThreads) void absmax_kernel(
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int i = 1; i < kPrepThreads / kWave; ++i) m = sh[i] > m ? sh[i] : m;
-        __hip_atomic_store(&partials[blockIdx.x], m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // The partial went out as an agent-scope atomic store (written through to where every XCD
-        // sees it); waiting for its acknowledgement orders it before the ticket.  A release fence
-        // here would instead write back this XCD's whole L2 once per block.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        uint32_t ticket = __hip_atomic_fetch_add(&ws_head[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t ticket = publish_then_ticket(&partials[blockIdx.x], m, &ws_head[0]);
         is_last = (ticket == kTicketBase + gridDim.x - 1);
         if (ticket - kTicketBase >= gridDim.x) *s = __uint_as_float(0x7FC00000u);
     }

@@ -227,6 +227,68 @@ def test_batched_layer_calls_match_single_calls_full_size(cfg_name):
         del Y1, wsl
 
 
+@pytest.mark.parametrize("cfg_name", ["c3_mlp7b", "c4_w4a8_13b"])
+def test_batched_layer_calls_against_the_oracle_full_size(cfg_name):
+    """The configuration the benchmark times, tied to the oracle in one step: the config's own
+    workload (seeded activations, gradients and weights, pre-arranged weight format) through the
+    batched fake-quant and batched linear entry points; forward values and dx on sampled rows, ds of
+    every operator, and Y on sampled rows and sampled columns against the oracle."""
+    cfg = wl.CONFIGS[cfg_name]
+    dtype, fmt = cfg.dtype, cfg.w_fmt
+    dt = TDT[dtype]
+    wf_rm = B.SASQ_W_INT8 if fmt == "int8" else B.SASQ_W_INT4_PACKED
+    wf = B.SASQ_W_INT8_BLOCKED if fmt == "int8" else B.SASQ_W_INT4_BLOCKED
+    M, n = cfg.M, len(cfg.projs)
+    set_tuning()
+    acts_b = {a.name: activation_bits(cfg_name, a.name) for a in cfg.acts}
+    acts = {name: to_dev(b, dtype) for name, b in acts_b.items()}
+    s_host = [np.float32(oracle.absmax_scale(acts_b[p.x], 8, dtype) / (3 + 0.5 * i)) for i, p in enumerate(cfg.projs)]
+    s_all = torch.from_numpy(np.array(s_host, dtype=np.float32)).cuda()
+    ds_all = torch.zeros(n, dtype=torch.float32, device="cuda")
+    fq_fwd, fq_bwd, lin, dys, wrefs = [], [], [], [], []
+    for i, p in enumerate(cfg.projs):
+        K, N = cfg.K_of(p), p.N
+        x = acts[p.x]
+        dyb = wl.upstream_grad(cfg, p.name)
+        dys.append(dyb)
+        w = wl.weight_fp32(cfg, p.name)
+        wq_ref, sw_ref = oracle.quantize_weight(w, fmt)
+        wrefs.append((wq_ref, sw_ref))
+        pk = torch.empty(B.sasq_packed_weight_bytes(N, K, wf), dtype=torch.uint8, device="cuda")
+        B.sasq_pack_weight(torch.from_numpy(wq_ref).cuda(), pk, N, K, wf_rm)
+        fq_fwd.append((x, s_all[i:i + 1], torch.empty_like(x)))
+        fq_bwd.append((x, to_dev(dyb, dtype), s_all[i:i + 1], torch.empty_like(x), ds_all[i:i + 1]))
+        lin.append((x, s_all[i:i + 1], pk, torch.from_numpy(sw_ref).cuda(), None, torch.empty((M, N), dtype=dt, device="cuda")))
+        del w
+    ws_b = B.new_workspace(B.sasq_fakequant_bwd_batch_workspace(n))
+    ws_l = B.new_workspace(B.sasq_static_linear_batch_workspace(lin, wf))
+    B.sasq_fakequant_fwd_batch(fq_fwd, 8)
+    B.sasq_fakequant_bwd_batch(fq_bwd, ws_b, 8)
+    B.sasq_static_linear_batch(lin, wf, ws_l)
+    torch.cuda.synchronize()
+    rows = sample_indices(M, 256, 16, seed=5)
+    ri = torch.from_numpy(rows).cuda()
+    for i, p in enumerate(cfg.projs):
+        xb, s = acts_b[p.x], s_host[i]
+        # fake-quant forward and backward: sampled rows element by element, ds over the whole tensor
+        y_ref, _ = oracle.fakequant_fwd(np.ascontiguousarray(xb[rows]), s, 8, dtype)
+        assert_same_values(to_bits(fq_fwd[i][2][ri]), y_ref, dtype, f"{p.name}: x' rows")
+        b_all = oracle.fakequant_bwd(xb, dys[i], s, 8, dtype)
+        assert_same_values(to_bits(fq_bwd[i][3][ri]), np.ascontiguousarray(b_all["dx"][rows]), dtype, f"{p.name}: dx rows")
+        got, ref = float(ds_all[i].item()), float(b_all["ds64"])
+        assert abs(got - ref) <= 1e-4 * abs(ref), (p.name, got, ref)
+        del b_all
+        # static linear: sampled rows against all columns, sampled columns against all rows
+        wq_ref, sw_ref = wrefs[i]
+        Y = lin[i][5]
+        ref_r = oracle.static_linear(np.ascontiguousarray(xb[rows]), s, wq_ref, sw_ref, None, 8, fmt, dtype, want_xq=False)
+        assert_same_values(to_bits(Y[ri]), ref_r["y"], dtype, f"{p.name}: Y rows")
+        cols = sample_indices(p.N, 256, 12, seed=6 + i)
+        ref_c = oracle.static_linear(xb, s, np.ascontiguousarray(wq_ref[cols]), np.ascontiguousarray(sw_ref[cols]),
+                                     None, 8, fmt, dtype, want_xq=False)
+        assert_same_values(to_bits(Y[:, torch.from_numpy(cols).cuda()].contiguous()), ref_c["y"], dtype, f"{p.name}: Y columns")
+
+
 @pytest.mark.parametrize("per_channel", [False, True])
 def test_fakequant_beyond_2_31_elements(per_channel, ws):
     """A tensor of 2.6e9 elements (flat indices beyond 2^31): forward and dx against the oracle on
