@@ -249,6 +249,75 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     float srow[MF];                                            // ROWS: the factor of each row this lane holds
 #pragma unroll
     for (int b = 0; b < MF; ++b) srow[b] = ROWS ? s_ptr[min(wm0 + b * 16 + frow, M - 1)] : 1.0f;
+    // Common case (block inside the matrix): the block goes out in chunks of 16 rows through a small
+    // staging buffer, software-pipelined: while chunk b is dequantized, the LDS reads of chunk b-1 are
+    // in flight; then chunk b-1 is stored, chunk b written to the buffer and read back.  LDS serves a
+    // wave's requests in order, so one buffer is enough.  (Staging the whole block first and storing
+    // it afterwards left the wave waiting for LDS and for the store queue in turn: 11 k cycles per
+    // 256x256 tile against 5 k.)
+    const bool vec_ok = (N & 7) == 0;
+    constexpr int kChunksPerRow = BN / 16;                      // 16-byte chunks in a wave-block row
+    constexpr int kRowsPerPass = 64 / kChunksPerRow;
+    const int crow = lane / kChunksPerRow, cchunk = lane % kChunksPerRow;
+    auto write_tile_chunked = [&](auto bias_tag) {
+        constexpr bool BIAS = decltype(bias_tag)::value;
+        constexpr int kPasses = 16 / kRowsPerPass;             // read-back passes per 16-row chunk
+        float cs[NF][4], bs[NF][4];
+#pragma unroll
+        for (int g = 0; g < NF; ++g) {
+            const int nl = g * 16 + 4 * fq;
+            f32x4 sv, bv = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (cols_inside) {
+                sv = *reinterpret_cast<const f32x4*>(fac + nl * 4);
+                if (BIAS) bv = *reinterpret_cast<const f32x4*>(bias + wn0 + nl);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { sv[e] = s_w[wn0 + nl + e]; if (BIAS) bv[e] = bias[wn0 + nl + e]; }
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { cs[g][e] = (ROWS || GROUPED) ? sv[e] : s * sv[e]; bs[g][e] = bv[e]; }
+        }
+        char* wr = epi + frow * T::kEpiStride + 4 * fq * 2;
+        const char* rd = epi + crow * T::kEpiStride + cchunk * 16;
+        char* dst = reinterpret_cast<char*>(y + (int64_t)(wm0 + crow) * N + wn0 + cchunk * 8);
+        const int64_t row_step = (int64_t)kRowsPerPass * N * 2, chunk_step = (int64_t)16 * N * 2;
+        u32x4 back[kPasses];
+#pragma unroll
+        for (int b = 0; b <= MF; ++b) {
+            u32x2 pk[NF];
+            if (b < MF) {
+#pragma unroll
+                for (int g = 0; g < NF; ++g) {
+                    float yv[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float cc = ROWS ? srow[b < MF ? b : 0] * cs[g][e] : cs[g][e];
+                        float v = GROUPED ? fsum[GROUPED ? g : 0][GROUPED ? (b < MF ? b : 0) : 0][e] * cc   // Y = fl32(f * s_w[n])
+                                          : (float)acc[g][b < MF ? b : 0][e] * cc;
+                        if (BIAS) v = v + bs[g][e];
+                        yv[e] = v;
+                    }
+                    pk[g] = u32x2{S::pack(yv[0], yv[1]), S::pack(yv[2], yv[3])};
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (b > 0) {
+#pragma unroll
+                for (int p = 0; p < kPasses; ++p) *reinterpret_cast<u32x4*>(dst + (b - 1) * chunk_step + p * row_step) = back[p];
+            }
+            if (b < MF) {
+#pragma unroll
+                for (int g = 0; g < NF; ++g) *reinterpret_cast<u32x2*>(wr + g * 32) = pk[g];
+#pragma unroll
+                for (int p = 0; p < kPasses; ++p) back[p] = *reinterpret_cast<const u32x4*>(rd + p * kRowsPerPass * T::kEpiStride);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    if (vec_ok && wm0 + BM / 2 <= M && wn0 + BN / 2 <= N) {
+        if (has_bias) write_tile_chunked(std::true_type{});
+        else          write_tile_chunked(std::false_type{});
+    } else {
     auto write_tile = [&](auto bias_tag) {
         constexpr bool BIAS = decltype(bias_tag)::value;
         f32x4 svs[NF];                                         // all parked factors requested together: one LDS latency
@@ -294,24 +363,6 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     // each wave reads back only what it wrote itself: no workgroup barrier needed
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
-    const bool vec_ok = (N & 7) == 0;
-    constexpr int kChunksPerRow = BN / 16;                      // 16-byte chunks in a wave-block row
-    constexpr int kRowsPerPass = 64 / kChunksPerRow;
-    const int crow = lane / kChunksPerRow, cchunk = lane % kChunksPerRow;
-    if (vec_ok && wm0 + BM / 2 <= M && wn0 + BN / 2 <= N) {
-        const char* src = epi + crow * T::kEpiStride + cchunk * 16;
-        char* dst = reinterpret_cast<char*>(y + (int64_t)(wm0 + crow) * N + wn0 + cchunk * 8);
-        const int64_t row_step = (int64_t)kRowsPerPass * N * 2;
-        constexpr int kPasses = (BM / 2) / kRowsPerPass;
-#pragma unroll
-        for (int p0 = 0; p0 < kPasses; p0 += 8) {
-            u32x4 v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = *reinterpret_cast<const u32x4*>(src + (p0 + j) * kRowsPerPass * T::kEpiStride);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x4*>(dst + (p0 + j) * row_step) = v[j];
-        }
-    } else
 #pragma unroll 4
     for (int p = 0; p < (BM / 2) / kRowsPerPass; ++p) {
         const int ml = p * kRowsPerPass + crow;
@@ -327,6 +378,7 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
                 if (n + e < N) dst[e] = (uint16_t)(v[e >> 1] >> (16 * (e & 1)));
         }
     }
+    }   // block at an edge of the matrix
     // inspection output (int32 accumulators): straight from the registers, apart from the common path
     if (acc_out) {
 #pragma unroll
