@@ -51,6 +51,7 @@ C3_LINEAR_BATCH_TRAFFIC_BYTES = 1364068 * 1024   # the batched call (all three p
 TRAFFIC_SOURCE = "recorded constant from profiles/bench_c3_mlp7b_counters.txt (rocprofv3 FETCH_SIZE/WRITE_SIZE, copy-calibrated), not measured in this run"
 HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published
 LR = 2e-4
+ROWMAJOR = False
 TDT = {"f16": torch.float16, "bf16": torch.bfloat16}
 
 
@@ -80,9 +81,9 @@ class Projection:
         if self.N % 32 == 0:
             self.wt_bwd = torch.empty(B.sasq_bwd_weight_bytes(self.N, self.K), dtype=torch.uint8, device="cuda")
             B.sasq_prepare_bwd_weight(self.wq, self.s_w, self.wt_bwd, self.N, self.K, wf, x.dtype)
-        # frozen weights are re-arranged once at set-up into the GEMM's blocked format (SASQ_BENCH_ROWMAJOR=1
-        # keeps the row-major interchange format instead)
-        if self.K % 64 == 0 and not os.environ.get("SASQ_BENCH_ROWMAJOR"):
+        # frozen weights are re-arranged once at set-up into the GEMM's blocked format (--rowmajor keeps the
+        # row-major interchange format instead)
+        if self.K % 64 == 0 and not ROWMAJOR:
             wfb = B.SASQ_W_INT8_BLOCKED if wf == B.SASQ_W_INT8 else B.SASQ_W_INT4_BLOCKED
             packed = torch.empty(B.sasq_packed_weight_bytes(self.N, self.K, wfb), dtype=torch.uint8, device="cuda")
             B.sasq_pack_weight(self.wq, packed, self.N, self.K, wf)
@@ -289,6 +290,11 @@ def main():
     ap.add_argument("--mfma-peak", action="store_true",
                     help="instead of the workload: time the library's register-only MFMA loop under sustained load "
                          "(80 back-to-back launches per operand pattern) and print what the matrix units sustain")
+    ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE",
+                    help="force a kernel variant through sasq_set_tuning for the whole run (for profiles that compare variants): "
+                         "path=twopass|fused, tile=256|128x256|128, mfma=32x32x32|16x16x64; path and tile act on single calls, "
+                         "so combine them with --unbatched")
+    ap.add_argument("--rowmajor", action="store_true", help="keep the weights in the row-major interchange format")
     ap.add_argument("--calib", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     a = ap.parse_args()
@@ -301,6 +307,17 @@ def main():
         torch.cuda.set_device(0)
         mfma_peak()
         return
+
+    knobs = {"path": (B.SASQ_TUNE_LINEAR_PATH, {"twopass": 1, "fused": 2}),
+             "tile": (B.SASQ_TUNE_LINEAR_TILE, {"256": 1, "128x256": 2, "128": 3}),
+             "mfma": (B.SASQ_TUNE_LINEAR_MFMA, {"32x32x32": 1, "16x16x64": 2})}
+    for t in a.tune:
+        name, _, val = t.partition("=")
+        if name not in knobs or val not in knobs[name][1]:
+            sys.exit(f"bench.py: unknown --tune {t}")
+        B.sasq_set_tuning(knobs[name][0], knobs[name][1][val])
+    global ROWMAJOR
+    ROWMAJOR = a.rowmajor or any(t.startswith("path=") for t in a.tune)   # both activation paths exist for row-major weights only
 
     cfg = wl.CONFIGS[a.config]
     rot = max(1, a.rotate)
@@ -372,7 +389,7 @@ def main():
     if not a.unbatched:
         layer.s_all.copy_(layer.s0_all)
         ev = {"fq": [], "fq_each": [], "lin": [], "lin_batch": []}
-        for _ in range(2 * rot + 1):
+        for _ in range(4 * rot + 1):
             step_unbatched(layer, ws_small, ev)
         torch.cuda.synchronize()
     lin_ms = [(e0.elapsed_time(e1), p) for e0, e1, p in ev["lin"]]
@@ -382,11 +399,12 @@ def main():
     for pp in projs:
         tl = [t for t, p in lin_ms if p.name == pp.name]
         tf = [t for t, p in fq_ms if p.name == pp.name]
-        per_proj[pp.name] = {"linear_us": round(1e3 * sum(tl) / len(tl), 2),
-                             "linear_tops": round(pp.ops / (sum(tl) / len(tl) * 1e-3) / 1e12, 1),
-                             "fakequant_fwd_bwd_us": round(1e3 * sum(tf) / len(tf), 2),
-                             "fakequant_gbps": round(pp.fq_bytes / (sum(tf) / len(tf) * 1e-3) / 1e9, 1),
-                             "fakequant_frac": round(pp.fq_bytes / (sum(tf) / len(tf) * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        tl_med, tf_med = med(sorted(tl)), med(sorted(tf))      # medians: a first call on fresh buffers can be far out
+        per_proj[pp.name] = {"linear_us": round(1e3 * tl_med, 2),
+                             "linear_tops": round(pp.ops / (tl_med * 1e-3) / 1e12, 1),
+                             "fakequant_fwd_bwd_us": round(1e3 * tf_med, 2),
+                             "fakequant_gbps": round(pp.fq_bytes / (tf_med * 1e-3) / 1e9, 1),
+                             "fakequant_frac": round(pp.fq_bytes / (tf_med * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
     ms_per_step = asked["ms_per_step"]
 
     # per-channel fake-quant (the granularity of the paper's main runs), measured after the timed
@@ -460,6 +478,28 @@ def main():
             grouped[f"group_{group}"] = {"achieved": round(tot_ops / (tot_ms * 1e-3) / 1e12, 1), "unit": "TOP/s",
                                          "frac": round(tot_ops / (tot_ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, 4),
                                          "us_per_call": round(1e3 * tot_ms / calls, 1), "calls": calls}
+        # the strict per-channel case (group = 1) has no MFMA form: a scalar kernel, timed once on the gate projection
+        p = projs[0]
+        if p.wf in (B.SASQ_W_INT8, B.SASQ_W_INT4_PACKED):
+            wq1, wf1 = p.wq, p.wf
+        else:                                              # the scalar kernel takes the row-major interchange format
+            wf1 = B.SASQ_W_INT8 if cfg.w_fmt == wl.W_INT8 else B.SASQ_W_INT4_PACKED
+            w = torch.from_numpy(wl.weight_fp32(cfg, p.name)).cuda()
+            wq1 = torch.empty((p.N, p.K if wf1 == B.SASQ_W_INT8 else p.K // 2),
+                              dtype=torch.int8 if wf1 == B.SASQ_W_INT8 else torch.uint8, device="cuda")
+            B.sasq_quantize_weight(w, wq1, torch.empty_like(p.s_w), wf1)
+            del w
+        sg1 = p.s.expand(p.K).contiguous()
+        B.sasq_static_linear_grouped(p.x, sg1, wq1, p.s_w, None, p.y, 1, wf1, p.ws_lin)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        B.sasq_static_linear_grouped(p.x, sg1, wq1, p.s_w, None, p.y, 1, wf1, p.ws_lin)
+        e1.record()
+        torch.cuda.synchronize()
+        ms1 = e0.elapsed_time(e1)
+        grouped["group_1"] = {"achieved": round(p.ops / (ms1 * 1e-3) / 1e12, 2), "unit": "TOP/s", "us_per_call": round(1e3 * ms1, 1),
+                              "calls": 1, "note": "scalar kernel (one thread per output), gate projection, one timed call"}
+        del wq1, sg1
         grouped["note"] = ("sasq_static_linear_grouped on the projections whose K the group divides "
                            "(gate, up, down for 128; gate, up for 512); warm repeat of 5")
 
@@ -544,7 +584,9 @@ def main():
                        "sasq_static_linear (activation quantize + int8 MFMA GEMM + dequant)"),
             "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s"}
     roof.update(roofline_of(asked))
-    roof.update({"sustained_mfma_only": INT8_MFMA_SUSTAINED_TOPS,
+    roof.update({"note": "timed right after the warm-up asked for; for about 100 steps after an idle period the part's power management "
+                         "runs this kernel 10-25 % slower than in steady state: `settled` holds the steady-state figure of the same run",
+                 "sustained_mfma_only": INT8_MFMA_SUSTAINED_TOPS,
                  "frac_of_sustained": round(asked["lin_tops"] / INT8_MFMA_SUSTAINED_TOPS, 4),
                  "traffic": (C3_LINEAR_BATCH_TRAFFIC_BYTES if batched else C3_LINEAR_TRAFFIC_BYTES) if cfg.name == "c3_mlp7b" else None,
                  "traffic_unit": "bytes per call", "traffic_source": TRAFFIC_SOURCE if cfg.name == "c3_mlp7b" else None,

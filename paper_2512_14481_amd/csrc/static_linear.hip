@@ -396,6 +396,8 @@ constexpr double kCost128x256 = 1.28, kCost128x128 = 1.42;   // time per output 
 //            likewise for k = 8.., 12..), so the activation bytes stay in natural order.
 enum { X_PREQ = 0, X_FUSED = 1 };
 enum { W_I8 = 0, W_I4 = 1, W_I8B = 2, W_I4B = 3 };
+static_assert(W_I8 == SASQ_W_INT8 && W_I4 == SASQ_W_INT4_PACKED && W_I8B == SASQ_W_INT8_BLOCKED && W_I4B == SASQ_W_INT4_BLOCKED,
+              "the weight paths are numbered like the interface's weight formats");
 
 // GROUPED (Sec. 3, Eq. 3): one activation factor per group of `group_tiles` K tiles.  s_ptr then
 // points at the G factors; the int32 accumulators cover one group at a time (the first K-substep
@@ -917,34 +919,53 @@ static int choose_tile(int64_t M, int64_t N)
         const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
         return (double)((tiles + slots - 1) / slots);
     };
-    const double c0 = rounds(256, 256, 256) * 1.00;
+    // 256x256: a last round that fills at most half of the CUs is handed out as half tiles and takes about 0.6 of a round
+    const int64_t t0 = ((M + 255) / 256) * ((N + 255) / 256);
+    const double c0 = (t0 > 256 && t0 % 256 > 0 && t0 % 256 <= 128) ? (double)(t0 / 256) + 0.6 : rounds(256, 256, 256) * 1.00;
     const double c1 = rounds(128, 256, 256) * 0.50 * kCost128x256;
     const double c2 = rounds(128, 128, 512) * 0.50 * kCost128x128;   // two co-resident workgroups share a CU
     if (c0 <= c1 && c0 <= c2) return 0;
     return c1 <= c2 ? 1 : 2;
 }
 
-// int8 weights over staged activations run on the 16x16x64 MFMA kernel (static_linear_k64.hip) unless
+// int8 weights and pre-arranged int4 weights over staged activations run on the 16x16x64 MFMA kernel (static_linear_k64.hip) unless
 // sasq_set_tuning(SASQ_TUNE_LINEAR_MFMA, 1) asks for the 32x32x32 one.
 static bool use_k64(int xmode, int wmode)
 {
-    return xmode == X_PREQ && (wmode == W_I8 || wmode == W_I8B) && tuning(SASQ_TUNE_LINEAR_MFMA) != 1;
+    return xmode == X_PREQ && (wmode == W_I8 || wmode == W_I8B || wmode == W_I4B) && tuning(SASQ_TUNE_LINEAR_MFMA) != 1;
 }
 
 template <int DT>
 static void launch_k64(const void* xq, const void* wq, const float* s, const float* s_w, const float* bias, void* y,
-                       int32_t* acc_out, int64_t M, int64_t N, int64_t K, bool blocked, bool rows, hipStream_t st)
+                       int32_t* acc_out, int64_t M, int64_t N, int64_t K, int wmode, bool rows, hipStream_t st)
 {
+    const int tile = choose_tile(M, N);
+    if (tile == 0 && !rows && !acc_out && tuning(SASQ_TUNE_LINEAR_TILE) == 0) {
+        // the plain call with 256x256 tiles is a batch of one: it gets the batch kernel's handling of a
+        // sparsely filled last round (its tiles handed out as 128x256 halves)
+        LinBatch g{};
+        g.count = 1;
+        LinItem& li = g.it[0];
+        li.x = nullptr;
+        li.xq = const_cast<int8_t*>(static_cast<const int8_t*>(xq));
+        li.s = s; li.wq = static_cast<const uint8_t*>(wq); li.s_w = s_w; li.bias = bias; li.y = static_cast<uint16_t*>(y);
+        li.M = (int)M; li.N = (int)N; li.K = (int)K;
+        li.tiles_m = (int)((M + 255) / 256); li.tiles_n = (int)((N + 255) / 256);
+        const int grid = ((li.tiles_m * li.tiles_n + 7) / 8) * 8;
+        for (int i = 0; i < kMaxLinearBatch; ++i) g.first_block[i + 1] = grid;
+        launch_gemm_k64_batch(g, grid, (sasq_dtype)DT, wmode, true, st);
+        return;
+    }
     GemmK64Args a{static_cast<const int8_t*>(xq), static_cast<const uint8_t*>(wq), s, s_w, bias,
                   static_cast<uint16_t*>(y), acc_out, M, N, K};
-    launch_gemm_k64(a, (sasq_dtype)DT, blocked, choose_tile(M, N), rows, st);
+    launch_gemm_k64(a, (sasq_dtype)DT, wmode, tile, rows, st);
 }
 
 template <int DT, int XMODE, int WMODE>
 static void launch_mfma(const void* xin, const void* wq, const float* s, const float* s_w, const float* bias,
                         void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K, int a_bits, hipStream_t st)
 {
-    if (use_k64(XMODE, WMODE)) { launch_k64<DT>(xin, wq, s, s_w, bias, y, acc_out, M, N, K, WMODE == W_I8B, false, st); return; }
+    if (use_k64(XMODE, WMODE)) { launch_k64<DT>(xin, wq, s, s_w, bias, y, acc_out, M, N, K, WMODE, false, st); return; }
     switch (choose_tile(M, N)) {
         case 0: launch_tiles<DT, XMODE, WMODE, 256, 256>(xin, wq, s, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
         case 1: launch_tiles<DT, XMODE, WMODE, 128, 256>(xin, wq, s, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
@@ -1027,7 +1048,7 @@ static void launch_mfma_grouped(const void* xin, const void* wq, const float* s_
     if (use_k64(X_PREQ, WMODE)) {
         GemmK64Args a{static_cast<const int8_t*>(xin), static_cast<const uint8_t*>(wq), s_g, s_w, bias,
                       static_cast<uint16_t*>(y), acc_out, M, N, K};
-        launch_gemm_k64_grouped(a, (sasq_dtype)DT, WMODE == W_I8B, tile, group_tiles, st);
+        launch_gemm_k64_grouped(a, (sasq_dtype)DT, WMODE, tile, group_tiles, st);
         return;
     }
     if (tile == 1) launch_tiles<DT, X_PREQ, WMODE, 128, 256, true>(xin, wq, s_g, s_w, bias, y, acc_out, M, N, K, a_bits, st, group_tiles);
@@ -1076,7 +1097,7 @@ template <int DT, int WMODE>
 static void launch_mfma_rows(const void* xin, const void* wq, const float* s_row, const float* s_w, const float* bias,
                              void* y, int32_t* acc_out, int64_t M, int64_t N, int64_t K, int a_bits, hipStream_t st)
 {
-    if (use_k64(X_PREQ, WMODE)) { launch_k64<DT>(xin, wq, s_row, s_w, bias, y, acc_out, M, N, K, WMODE == W_I8B, true, st); return; }
+    if (use_k64(X_PREQ, WMODE)) { launch_k64<DT>(xin, wq, s_row, s_w, bias, y, acc_out, M, N, K, WMODE, true, st); return; }
     switch (choose_tile(M, N)) {
         case 0: launch_tiles<DT, X_PREQ, WMODE, 256, 256, false, true>(xin, wq, s_row, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
         case 1: launch_tiles<DT, X_PREQ, WMODE, 128, 256, false, true>(xin, wq, s_row, s_w, bias, y, acc_out, M, N, K, a_bits, st); break;
@@ -1325,8 +1346,8 @@ extern "C" int sasq_static_linear_batch(const sasq_linear_item* items, int count
     do {                                                                                                                \
         if (perm8) quantize_act_batch_kernel<DTV, true><<<qgrid, 256, 0, st>>>(q, a_bits);                              \
         else       quantize_act_batch_kernel<DTV, false><<<qgrid, 256, 0, st>>>(q, a_bits);                             \
-        if (use_k64(X_PREQ, wf == SASQ_W_INT8 ? W_I8 : wf == SASQ_W_INT8_BLOCKED ? W_I8B : W_I4)) {                     \
-            launch_gemm_k64_batch(g, ggrid, dt, wf == SASQ_W_INT8_BLOCKED, tuning(SASQ_TUNE_LINEAR_TILE) == 0, st);                                         \
+        if (use_k64(X_PREQ, (int)wf)) {          /* the sasq_wfmt values are those of the kernels' weight paths */     \
+            launch_gemm_k64_batch(g, ggrid, dt, (int)wf, tuning(SASQ_TUNE_LINEAR_TILE) == 0, st);                       \
         } else switch (wf) {                                                                                            \
             case SASQ_W_INT8:         linear_mfma_batch_kernel<DTV, W_I8><<<ggrid, kGemmThreads, 0, st>>>(g, a_bits); break;   \
             case SASQ_W_INT4_PACKED:  linear_mfma_batch_kernel<DTV, W_I4><<<ggrid, kGemmThreads, 0, st>>>(g, a_bits); break;   \

@@ -21,7 +21,11 @@
 
 namespace sasq {
 
-enum { KW_I8 = 0, KW_I8B = 2 };
+// Weight paths (values shared with static_linear.hip): int8 row-major, int8 pre-arranged in 1 KB blocks, int4
+// pre-arranged (it stays packed through L2 -> LDS and is unpacked between the fragment read and the MFMA: a nibble
+// moved to the high half of a byte is the int8 value 16 w, so two mask/shift operations per dword turn 8 nibbles into
+// 8 bytes; the accumulators are then exactly 16 acc and are shifted back in the epilogue).
+enum { KW_I8 = 0, KW_I8B = 2, KW_I4B = 3 };
 
 constexpr int kFacBytes = 1024;      // per wave: the epilogue's per-column factors (BN/2 floats, loaded twice over)
 template <int BM, int BN> constexpr int lds_bytes_k64() { return Tile<BM, BN>::kLds + 4 * kFacBytes; }
@@ -55,7 +59,10 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     using T = Tile<BM, BN>;
     constexpr int MF = BM / 32, NF = BN / 32;          // 16x16 tiles per wave along m, n
     constexpr int XS = T::XS, WS = T::WS;              // 1 KB slabs per wave per stage
-    constexpr int kLoads = XS + WS;                    // direct loads per wave per K tile
+    constexpr bool I4 = WMODE == KW_I4B;
+    constexpr int WSL = I4 ? WS / 2 : WS;              // weight loads per wave per K tile (packed int4: half the bytes)
+    constexpr int kLoads = XS + WSL;                   // direct loads per wave per K tile
+    constexpr int kAccShift = I4 ? 4 : 0;
     auto stage_ptr = [&](int st, int operand) -> char* { return &lds[st * T::kStageBytes + operand * T::kXBytes]; };
 
     const int m0 = tm * BM, n0 = tn * BN;
@@ -72,32 +79,53 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     const int lchunk = (lane & 3) ^ (((lane >> 3) & 3) ^ ((lane >> 5) & 1));
     const int last_rb = (M - 1) >> 4;
     const int8_t* xpanel = xq + (int64_t)(m0 >> 4) * KT * 1024;
-    const int8_t* wpanel = reinterpret_cast<const int8_t*>(wq) + (WMODE == KW_I8B ? (int64_t)(n0 >> 4) * KT * 1024 : (int64_t)n0 * K);
-    uint32_t xoff[XS], woff[WS];
+    const int8_t* wpanel = reinterpret_cast<const int8_t*>(wq) + (WMODE == KW_I8B ? (int64_t)(n0 >> 4) * KT * 1024
+                                                                  : I4 ? (int64_t)(n0 >> 5) * KT * 1024 : (int64_t)n0 * K);
+    uint32_t xoff[XS], woff[WSL];
 #pragma unroll
     for (int j = 0; j < XS; ++j)
         xoff[j] = (uint32_t)(min(4 * j + wave, last_rb - (m0 >> 4)) * KT * 1024 + lane * 16);
 #pragma unroll
-    for (int j = 0; j < WS; ++j) {
-        if (WMODE == KW_I8B) woff[j] = (uint32_t)(min(4 * j + wave, ((N - 1) >> 4) - (n0 >> 4)) * KT * 1024 + lane * 16);
+    for (int j = 0; j < WSL; ++j) {
+        if (I4) woff[j] = (uint32_t)(min(4 * j + wave, ((N - 1) >> 5) - (n0 >> 5)) * KT * 1024 + lane * 16);   // blocks of 32 rows
+        else if (WMODE == KW_I8B) woff[j] = (uint32_t)(min(4 * j + wave, ((N - 1) >> 4) - (n0 >> 4)) * KT * 1024 + lane * 16);
         else                 woff[j] = (uint32_t)(min((4 * j + wave) * 16 + lrow, N - 1 - n0) * K + lchunk * 16);
     }
-    constexpr int kWTileStep = WMODE == KW_I8B ? 1024 : kBK;
+    constexpr int kWTileStep = (WMODE == KW_I8B || I4) ? 1024 : kBK;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_ptr_t)&lds[0] + (uint32_t)wave * 1024u;
     auto dma = [&](int Tk, int j) {                  // loads 0..XS-1: activations, XS..: weights
         const uint32_t st_off = (uint32_t)(Tk & 3) * T::kStageBytes;
         if (j < XS) lds_load16(lds_base + st_off + j * 4096, xpanel + (int64_t)Tk * 1024, xoff[j]);
-        else        lds_load16(lds_base + st_off + T::kXBytes + (j - XS) * 4096, wpanel + (int64_t)Tk * kWTileStep, woff[j - XS]);
+        else        lds_load16(lds_base + st_off + T::kXBytes + (j - XS) * 4096, wpanel + (int64_t)Tk * kWTileStep, woff[j - XS < WSL ? j - XS : 0]);
     };
 
     // ---- LDS -> MFMA fragments: lane l reads chunk l/16 of row l%16 of a 16-row tile ----
     const int frow = lane & 15, fq = lane >> 4;
     const int foff = frow * kBK + ((fq ^ swz64(frow)) << 4);
     const int xbase = wm * (BM / 2) * kBK, wbase = wn * (BN / 2) * kBK;
-    i32x4 fx[2][MF], fw[2][NF];
+    // Packed int4: a 1 KB block holds 32 rows x 64 k; the 16 codes k = 16 G .. + 15 of row r are the 8 bytes at
+    // 256 G + 8 r (G = 2 kk + g in the layout's own terms), so lane l fetches 8 bytes at 256 (l/16) + 8 (16 h + l%16),
+    // h = the 16-row half of the block its tile is.
+    using WFrag = std::conditional_t<I4, u32x2, i32x4>;
+    i32x4 fx[2][MF];
+    WFrag fw[2][NF];
     auto read_frag = [&](int set, int st, int idx) {   // the MF activation fragments first, then the NF weight ones
-        if (idx < MF) fx[set][idx] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 0) + xbase + idx * 16 * kBK + foff);
-        else          fw[set][idx - MF] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 1) + wbase + (idx - MF) * 16 * kBK + foff);
+        if (idx < MF) {
+            fx[set][idx] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 0) + xbase + idx * 16 * kBK + foff);
+        } else if constexpr (I4) {
+            const int g = idx - MF;
+            fw[set][g] = *reinterpret_cast<const u32x2*>(stage_ptr(st, 1) + (wn * (BN / 64) + (g >> 1)) * 1024 + 256 * fq + 8 * (16 * (g & 1) + frow));
+        } else {
+            fw[set][idx - MF] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 1) + wbase + (idx - MF) * 16 * kBK + foff);
+        }
+    };
+    auto wfrag = [&](const WFrag& f) -> i32x4 {         // the MFMA's weight operand: as read, or unpacked here
+        if constexpr (I4) {
+            const uint32_t p0 = f[0], p1 = f[1];
+            return i32x4{(int)((p0 << 4) & 0xF0F0F0F0u), (int)(p0 & 0xF0F0F0F0u), (int)((p1 << 4) & 0xF0F0F0F0u), (int)(p1 & 0xF0F0F0F0u)};
+        } else {
+            return f;
+        }
     };
 
     i32x4 acc[NF][MF];
@@ -140,11 +168,12 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
         const bool more = !TAIL || i + 1 < KT;                 // a next tile to read fragments of
 #pragma unroll
         for (int g = 0; g < NF; ++g) {
+            const i32x4 wv = wfrag(fw[CUR][g]);
 #pragma unroll
             for (int b = 0; b < MF; ++b) {
                 const i32x4 zero = {0, 0, 0, 0};
                 // K tile 0 multiplies into a zero accumulator operand instead of clearing the accumulators
-                acc[g][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fw[CUR][g], fx[CUR][b], FIRST ? zero : acc[g][b], 0, 0, 0);
+                acc[g][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wv, fx[CUR][b], FIRST ? zero : acc[g][b], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 const int t = g * MF + b;
                 if (t < kFragStep * NFR) {
@@ -178,7 +207,7 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
                             fsum[GROUPED ? g : 0][GROUPED ? b : 0][e] =
-                                __builtin_fmaf((float)acc[g][b][e], sg, fsum[GROUPED ? g : 0][GROUPED ? b : 0][e]);
+                                __builtin_fmaf((float)(acc[g][b][e] >> kAccShift), sg, fsum[GROUPED ? g : 0][GROUPED ? b : 0][e]);
                 in_group = 0;
                 ++group_idx;
             }
@@ -293,7 +322,7 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
                     for (int e = 0; e < 4; ++e) {
                         const float cc = ROWS ? srow[b < MF ? b : 0] * cs[g][e] : cs[g][e];
                         float v = GROUPED ? fsum[GROUPED ? g : 0][GROUPED ? (b < MF ? b : 0) : 0][e] * cc   // Y = fl32(f * s_w[n])
-                                          : (float)acc[g][b < MF ? b : 0][e] * cc;
+                                          : (float)(acc[g][b < MF ? b : 0][e] >> kAccShift) * cc;
                         if (BIAS) v = v + bs[g][e];
                         yv[e] = v;
                     }
@@ -349,7 +378,7 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
                 for (int e = 0; e < 4; ++e) {
                     const float cc = ROWS ? srow[b] * cs[e] : cs[e];
                     float v = GROUPED ? fsum[GROUPED ? g : 0][GROUPED ? b : 0][e] * cc      // Y = fl32(f * s_w[n])
-                                      : (float)acc[g][b][e] * cc;
+                                      : (float)(acc[g][b][e] >> kAccShift) * cc;
                     if (BIAS) v = v + bs[e];
                     yv[e] = v;
                 }
@@ -389,7 +418,7 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     if (m < M && n + e < N)
-                        acc_out[(int64_t)m * N + n + e] = GROUPED ? __float_as_int(fsum[GROUPED ? g : 0][GROUPED ? b : 0][e]) : acc[g][b][e];
+                        acc_out[(int64_t)m * N + n + e] = GROUPED ? __float_as_int(fsum[GROUPED ? g : 0][GROUPED ? b : 0][e]) : (acc[g][b][e] >> kAccShift);
             }
     }
 }
@@ -472,10 +501,11 @@ static void launch_tile(const GemmK64Args& a, int tile, hipStream_t st)
 }
 
 template <int DT>
-static void launch_dt(const GemmK64Args& a, bool blocked, int tile, bool rows, hipStream_t st)
+static void launch_dt(const GemmK64Args& a, int wmode, int tile, bool rows, hipStream_t st)
 {
-    if (blocked) { if (rows) launch_tile<DT, KW_I8B, true>(a, tile, st); else launch_tile<DT, KW_I8B, false>(a, tile, st); }
-    else         { if (rows) launch_tile<DT, KW_I8, true>(a, tile, st);  else launch_tile<DT, KW_I8, false>(a, tile, st); }
+    if (wmode == KW_I8B)      { if (rows) launch_tile<DT, KW_I8B, true>(a, tile, st); else launch_tile<DT, KW_I8B, false>(a, tile, st); }
+    else if (wmode == KW_I4B) { if (rows) launch_tile<DT, KW_I4B, true>(a, tile, st); else launch_tile<DT, KW_I4B, false>(a, tile, st); }
+    else                      { if (rows) launch_tile<DT, KW_I8, true>(a, tile, st);  else launch_tile<DT, KW_I8, false>(a, tile, st); }
 }
 
 template <int DT, int WMODE, int BM, int BN>
@@ -487,26 +517,42 @@ static void launch_grouped_one(const GemmK64Args& a, int group_tiles, hipStream_
         a.xq, a.wq, a.s, a.s_w, a.bias, a.y, a.acc_out, (int)a.M, (int)a.N, (int)a.K, tiles_m, tiles_n, group_tiles);
 }
 
+template <int DT, int WMODE>
+static void launch_grouped_w(const GemmK64Args& a, int tile, int group_tiles, hipStream_t st)
+{
+    if (tile == 1) launch_grouped_one<DT, WMODE, 128, 256>(a, group_tiles, st);
+    else           launch_grouped_one<DT, WMODE, 128, 128>(a, group_tiles, st);
+}
+
 template <int DT>
-static void launch_grouped_dt(const GemmK64Args& a, bool blocked, int tile, int group_tiles, hipStream_t st)
+static void launch_grouped_dt(const GemmK64Args& a, int wmode, int tile, int group_tiles, hipStream_t st)
 {
-    if (blocked) { if (tile == 1) launch_grouped_one<DT, KW_I8B, 128, 256>(a, group_tiles, st); else launch_grouped_one<DT, KW_I8B, 128, 128>(a, group_tiles, st); }
-    else         { if (tile == 1) launch_grouped_one<DT, KW_I8, 128, 256>(a, group_tiles, st);  else launch_grouped_one<DT, KW_I8, 128, 128>(a, group_tiles, st); }
+    if (wmode == KW_I8B)      launch_grouped_w<DT, KW_I8B>(a, tile, group_tiles, st);
+    else if (wmode == KW_I4B) launch_grouped_w<DT, KW_I4B>(a, tile, group_tiles, st);
+    else                      launch_grouped_w<DT, KW_I8>(a, tile, group_tiles, st);
 }
 
-void launch_gemm_k64_grouped(const GemmK64Args& a, sasq_dtype dt, bool blocked, int tile, int group_tiles, hipStream_t st)
+void launch_gemm_k64_grouped(const GemmK64Args& a, sasq_dtype dt, int wmode, int tile, int group_tiles, hipStream_t st)
 {
-    if (dt == SASQ_F16) launch_grouped_dt<SASQ_F16>(a, blocked, tile, group_tiles, st);
-    else                launch_grouped_dt<SASQ_BF16>(a, blocked, tile, group_tiles, st);
+    if (dt == SASQ_F16) launch_grouped_dt<SASQ_F16>(a, wmode, tile, group_tiles, st);
+    else                launch_grouped_dt<SASQ_BF16>(a, wmode, tile, group_tiles, st);
 }
 
-void launch_gemm_k64(const GemmK64Args& a, sasq_dtype dt, bool blocked, int tile, bool rows, hipStream_t st)
+void launch_gemm_k64(const GemmK64Args& a, sasq_dtype dt, int wmode, int tile, bool rows, hipStream_t st)
 {
-    if (dt == SASQ_F16) launch_dt<SASQ_F16>(a, blocked, tile, rows, st);
-    else                launch_dt<SASQ_BF16>(a, blocked, tile, rows, st);
+    if (dt == SASQ_F16) launch_dt<SASQ_F16>(a, wmode, tile, rows, st);
+    else                launch_dt<SASQ_BF16>(a, wmode, tile, rows, st);
 }
 
-void launch_gemm_k64_batch(LinBatch& b, int grid, sasq_dtype dt, bool blocked, bool split_tail, hipStream_t st)
+template <int DT>
+static void launch_batch_dt(const LinBatch& b, int grid, int wmode, hipStream_t st)
+{
+    if (wmode == KW_I8B)      gemm_k64_batch_kernel<DT, KW_I8B><<<grid, kGemmThreads, 0, st>>>(b);
+    else if (wmode == KW_I4B) gemm_k64_batch_kernel<DT, KW_I4B><<<grid, kGemmThreads, 0, st>>>(b);
+    else                      gemm_k64_batch_kernel<DT, KW_I8><<<grid, kGemmThreads, 0, st>>>(b);
+}
+
+void launch_gemm_k64_batch(LinBatch& b, int grid, sasq_dtype dt, int wmode, bool split_tail, hipStream_t st)
 {
     // Tail of the launch: `grid` workgroup ids in all, 256 resident at a time.
     b.split_first = grid;
@@ -517,13 +563,8 @@ void launch_gemm_k64_batch(LinBatch& b, int grid, sasq_dtype dt, bool blocked, b
         b.split_count = rem;
         grid += rem;
     }
-    if (dt == SASQ_F16) {
-        if (blocked) gemm_k64_batch_kernel<SASQ_F16, KW_I8B><<<grid, kGemmThreads, 0, st>>>(b);
-        else         gemm_k64_batch_kernel<SASQ_F16, KW_I8><<<grid, kGemmThreads, 0, st>>>(b);
-    } else {
-        if (blocked) gemm_k64_batch_kernel<SASQ_BF16, KW_I8B><<<grid, kGemmThreads, 0, st>>>(b);
-        else         gemm_k64_batch_kernel<SASQ_BF16, KW_I8><<<grid, kGemmThreads, 0, st>>>(b);
-    }
+    if (dt == SASQ_F16) launch_batch_dt<SASQ_F16>(b, grid, wmode, st);
+    else                launch_batch_dt<SASQ_BF16>(b, grid, wmode, st);
 }
 
 }  // namespace sasq

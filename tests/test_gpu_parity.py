@@ -366,6 +366,9 @@ def test_static_linear_blocked_weights(shape, dtype, fmt, tile):
         assert_same_values(y, ref["y"], dtype, "Y")
         y2, _, _ = run_linear(xb, s, wq, s_w, b, fmt, dtype, want_debug=False, tile=tile, blocked=True)
         assert np.array_equal(y2, y)
+        # the other GEMM kernel on the same pre-arranged weights
+        y3, acc3, _ = run_linear(xb, s, wq, s_w, b, fmt, dtype, tile=tile, blocked=True, mfma="32x32x32")
+        assert np.array_equal(acc3, ref["acc"]) and np.array_equal(y3, y), "32x32x32 kernel"
 
 
 @pytest.mark.parametrize("a_bits", [4, 6, 2])
