@@ -80,7 +80,7 @@ int sasq_version(void);
 typedef enum {
     SASQ_TUNE_LINEAR_PATH = 0,   /* 1: separate activation-quantize pass, 2: quantize on load          */
     SASQ_TUNE_LINEAR_TILE = 1,   /* 1: 256x256, 2: 128x256, 3: 128x128 workgroup tiles                  */
-    SASQ_TUNE_LINEAR_MFMA = 2,   /* 1: 32x32x32 int8 MFMA kernel, 2: 16x16x64 (where it exists)         */
+    SASQ_TUNE_LINEAR_MFMA = 2,   /* GEMMs: 1: the kernels on 32x32 MFMA tiles, 2: on 16x16 tiles (where they exist) */
     SASQ_TUNE_FQ_SHARE = 3,      /* 1..3: forward operators per group sharing one read of x, any size   */
     SASQ_TUNE_BWD_TILE = 4,      /* backward GEMM: 1: 256x256, 2: 128x128 tiles                         */
     SASQ_TUNE_COUNT = 5

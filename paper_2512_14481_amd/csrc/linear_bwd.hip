@@ -6,14 +6,12 @@
 // runs along operand rows.
 #include "sasq_device.h"
 #include "gemm_tile.h"
+#include "gemm_k64_body.h"
 #include <cstdlib>
 #include <cstring>
 #include <type_traits>
 
 namespace sasq {
-
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kBwdCols = kBK / 2;                  // contraction elements per stage row (16-bit)
 
@@ -301,6 +299,35 @@ static void launch_bwd(const void* dy, const void* wt, void* dx, float* acc_out,
         (int)M, (int)N, (int)K, tiles_m, tiles_n);
 }
 
+// The same GEMM on v_mfma_f32_16x16x32_{f16,bf16} through the tile body shared with the int8 forward GEMM
+// (gemm_k64_body.h): 16x16 tiles, one MFMA per 64-byte stage row, scalar-addressed direct loads, chunked epilogue.
+// The default: a register-only loop of the 16x16x32 form sustains about 18 % more than 32x32x16 on this
+// power-limited part (1.97 against 1.67 PFLOP/s for f16).  dY is the body's row-major operand, the prepared
+// weight its block operand; K of the body is the contraction length in bytes.
+template <int DT, int BM, int BN>
+__global__ __launch_bounds__(kGemmThreads)
+__attribute__((amdgpu_waves_per_eu(Tile<BM, BN>::kWavesPerSimd, Tile<BM, BN>::kWavesPerSimd)))
+void linear_bwd_k32_kernel(const uint8_t* __restrict__ dy, const uint8_t* __restrict__ wt,
+                           uint16_t* __restrict__ dx, float* __restrict__ acc_out,
+                           int M, int N, int K, int tiles_m, int tiles_n)
+{
+    __shared__ __attribute__((aligned(1024))) char lds[lds_bytes_k64<BM, BN>()];
+    int tm, tn;
+    if (!tile_of_block((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
+    gemm_k64_body<DT, KW_I8B, BM, BN, false, false, 1>(reinterpret_cast<const int8_t*>(dy), wt, nullptr, nullptr, nullptr, dx,
+                                                        reinterpret_cast<int32_t*>(acc_out), M, K, N * 2, tm, tn, lds);
+}
+
+template <int DT, int BM, int BN>
+static void launch_bwd_k32(const void* dy, const void* wt, void* dx, float* acc_out, int64_t M, int64_t N, int64_t K, hipStream_t st)
+{
+    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((K + BN - 1) / BN);
+    const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
+    linear_bwd_k32_kernel<DT, BM, BN><<<grid, kGemmThreads, 0, st>>>(
+        static_cast<const uint8_t*>(dy), static_cast<const uint8_t*>(wt), static_cast<uint16_t*>(dx), acc_out,
+        (int)M, (int)N, (int)K, tiles_m, tiles_n);
+}
+
 // 256x256 tiles unless they would leave most of the 256 CUs idle for a round; then 128x128
 // (two workgroups per CU).  sasq_set_tuning(SASQ_TUNE_BWD_TILE, 1 | 2) forces one of them.
 static bool bwd_small_tiles(int64_t M, int64_t K)
@@ -375,6 +402,17 @@ extern "C" int sasq_linear_bwd_input(const void* dy, const void* wt, void* dx, f
         return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
     }
     const bool small = bwd_small_tiles(M, K);
+    // the 16x16x32 kernel addresses dY rows with 32-bit byte offsets inside a 256-row tile
+    if (tuning(SASQ_TUNE_LINEAR_MFMA) != 1 && N <= (INT64_C(1) << 22)) {
+        if (dt == SASQ_F16) {
+            if (small) launch_bwd_k32<SASQ_F16, 128, 128>(dy, wt, dx, acc_out, M, N, K, st);
+            else       launch_bwd_k32<SASQ_F16, 256, 256>(dy, wt, dx, acc_out, M, N, K, st);
+        } else {
+            if (small) launch_bwd_k32<SASQ_BF16, 128, 128>(dy, wt, dx, acc_out, M, N, K, st);
+            else       launch_bwd_k32<SASQ_BF16, 256, 256>(dy, wt, dx, acc_out, M, N, K, st);
+        }
+        return hipGetLastError() == hipSuccess ? SASQ_OK : SASQ_ERR_LAUNCH;
+    }
     if (dt == SASQ_F16) {
         if (small) launch_bwd<SASQ_F16, 128, 128>(dy, wt, dx, acc_out, M, N, K, st);
         else       launch_bwd<SASQ_F16, 256, 256>(dy, wt, dx, acc_out, M, N, K, st);

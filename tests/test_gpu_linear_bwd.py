@@ -39,8 +39,8 @@ def prepare(wq, s_w, fmt, dtype):
     return wt, K
 
 
-def run_bwd(dyb, wt, K, dtype, tile=None, want_acc=False):
-    set_tuning(bwd_tile=tile)
+def run_bwd(dyb, wt, K, dtype, tile=None, want_acc=False, mfma=None):
+    set_tuning(bwd_tile=tile, mfma=mfma)
     M = dyb.shape[0]
     dx = torch.empty((M, K), dtype=TDT[dtype], device="cuda")
     acc = torch.empty((M, K), dtype=torch.float32, device="cuda") if want_acc else None
@@ -98,15 +98,16 @@ def test_prepared_weight_matches_oracle(seed, shape, dtype, fmt):
     assert not got[K:].any() and not got[:, N:].any()
 
 
+@pytest.mark.parametrize("mfma", ["16x16x64", "32x32x32"])      # the two GEMM kernels (16x16x32 and 32x32x16 MFMA tiles)
 @pytest.mark.parametrize("tile", ["256", "128"])
 @pytest.mark.parametrize("dtype,fmt", [("f16", "int8"), ("bf16", "int4")])
 @pytest.mark.parametrize("shape", SHAPES)
-def test_linear_bwd_matches_oracle(shape, dtype, fmt, tile):
+def test_linear_bwd_matches_oracle(shape, dtype, fmt, tile, mfma):
     dyb, wq, s_w = problem(82, shape, dtype, fmt)
     wt, K = prepare(wq, s_w, fmt, dtype)
     ref = oracle.linear_bwd_input(dyb, wq, s_w, fmt, dtype)
-    got, acc = run_bwd(dyb, wt, K, dtype, tile, want_acc=True)
-    check_dx(got, ref, dtype, shape[1], f"{shape} {dtype} {fmt} tile {tile}")
+    got, acc = run_bwd(dyb, wt, K, dtype, tile, want_acc=True, mfma=mfma)
+    check_dx(got, ref, dtype, shape[1], f"{shape} {dtype} {fmt} tile {tile} {mfma}")
     # the fp32 sums before the 16-bit rounding: N fp32 additions in any order
     err = np.abs(acc.astype(np.float64) - ref["exact"])
     assert (err <= shape[1] * 2.0 ** -24 * ref["sum_abs"] + 1e-45).all(), err.max()
