@@ -453,12 +453,12 @@ def main():
                          "frac": round(bb / (bms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                          "note": "sasq_fakequant_fwd_pc_batch + sasq_fakequant_bwd_pc_batch over the three projection inputs"}
 
-    # static linear with one activation factor per group of 128 / 512 input channels (the grouped form
+    # static linear with one activation factor per group of 32 / 128 / 512 input channels (the grouped form
     # the paper gives for per-channel activation factors), measured after the timed region
     grouped = None
     if cfg.name == "c3_mlp7b":
         grouped = {}
-        for group in (128, 512):
+        for group in (32, 128, 512):
             tot_ops, tot_ms, calls = 0.0, 0.0, 0
             for p in projs:
                 if p.K % group:
@@ -501,7 +501,9 @@ def main():
                               "calls": 1, "note": "scalar kernel (one thread per output), gate projection, one timed call"}
         del wq1, sg1
         grouped["note"] = ("sasq_static_linear_grouped on the projections whose K the group divides "
-                           "(gate, up, down for 128; gate, up for 512); warm repeat of 5")
+                           "(gate, up, down for 32 and 128; gate, up for 512); warm repeat of 5.  group_32 "
+                           "multiplies every 64-channel K tile twice (half of the channels zeroed each time): its "
+                           "TOP/s counts the useful operations only")
 
     # dynamic per-token linear (per-row absmax + quantize + the same GEMM + per-row dequantize): the
     # baseline whose online reduction the static scale removes, on the same tensors

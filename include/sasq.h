@@ -303,7 +303,9 @@ int sasq_static_linear_batch(const sasq_linear_item* items, int count, int a_bit
  *   f_out    [M, N] device fp32 or NULL: f, for inspection and tests (slower path); xq_out as in
  *            sasq_static_linear
  *   group    divides K.  The MFMA path is taken when K and group are multiples of 64 (then all
- *            four weight formats are accepted); other shapes run a scalar kernel and accept the
+ *            four weight formats are accepted), and for group = 32 with K a multiple of 64 and
+ *            any format but row-major int4 (each 64-channel K tile is then multiplied twice, one
+ *            half of the channels at a time); other shapes run a scalar kernel and accept the
  *            row-major weight formats only (SASQ_ERR_SHAPE for the pre-arranged ones).
  *   every other argument, the workspace size and the limits are those of sasq_static_linear.
  */

@@ -21,7 +21,7 @@ struct GemmK64Args {
 // tile: 0 = 256x256, 1 = 128x256, 2 = 128x128 (two workgroups per CU).  K must be a multiple of 64.
 void launch_gemm_k64(const GemmK64Args& a, sasq_dtype dt, int wmode, int tile, bool rows, hipStream_t st);
 // Grouped activation factors (a.s points at K / (64 group_tiles) factors, a.acc_out receives the fp32 sums):
-// tile 1 = 128x256, 2 = 128x128.
+// tile 1 = 128x256, 2 = 128x128.  group_tiles = 0: groups of 32 channels (two per K tile; 128x128 tiles).
 void launch_gemm_k64_grouped(const GemmK64Args& a, sasq_dtype dt, int wmode, int tile, int group_tiles, hipStream_t st);
 // split_tail: hand the tiles of a sparsely filled last round out as 128x256 halves (sets b.split_first / b.split_count)
 void launch_gemm_k64_batch(LinBatch& b, int grid, sasq_dtype dt, int wmode, bool split_tail, hipStream_t st);

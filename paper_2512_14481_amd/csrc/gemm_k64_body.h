@@ -51,12 +51,16 @@ __device__ __forceinline__ void lds_load16(uint32_t lds_addr, const void* base, 
 // f = fma(fl32(acc), s_g, f) in ascending group order; the epilogue applies s_w and the bias to f,
 // and acc_out receives f (as float bits).  Tiles of 128 rows only (f doubles the accumulator registers);
 // with 128x128 tiles two waves share a SIMD and one wave's fold runs under the other's MFMAs.
+// GROUPED = 2: groups of 32 channels, two per K tile.  One MFMA contracts the whole 64-byte stage, so every K tile
+// is multiplied twice, once with the activation fragments of channels 32..63 zeroed and once with those of 0..31
+// zeroed (lanes 32..63 resp. 0..31 of a fragment), each pass into zero accumulators and folded with its own factor:
+// twice the matrix work and a fold per 32 channels, an order of magnitude faster than the scalar kernel all the same.
 // OP 1: the same machine on v_mfma_f32_16x16x32_{f16,bf16} (DT picks the type): both operands hold 16-bit floats, 32
 // per 64-byte stage row; the "activation" operand xq is then read ROW-MAJOR (rows of K bytes, the 16-byte chunks of a
 // row gathered per lane as for row-major weights), the weight operand from 1 KB blocks; K is the contraction length in
 // BYTES; the accumulators are fp32, written out rounded to 16 bits without any factor (s_ptr, s_w, bias unused), and
 // acc_out receives the fp32 sums.  This is the backward GEMM of the frozen linear (linear_bwd.hip).
-template <int DT, int WMODE, int BM, int BN, bool ROWS, bool GROUPED = false, int OP = 0>
+template <int DT, int WMODE, int BM, int BN, bool ROWS, int GROUPED = 0, int OP = 0>
 __device__ __forceinline__
 void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq,
                    const float* __restrict__ s_ptr, const float* __restrict__ s_w,
@@ -165,6 +169,17 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     constexpr int kFragStep = NM / 2 / NFR >= 1 ? NM / 2 / NFR : 1;
     constexpr int kLoadStep = (NM - kFragStep * NFR) / kLoads;
     static_assert(kLoadStep >= 1, "side work does not fit behind the MFMAs");
+    auto fold = [&](int group_idx) {                           // f = fma(fl32(acc), s_g, f) for every accumulator
+        const float sg = s_ptr[GROUPED ? group_idx : 0];
+#pragma unroll
+        for (int g = 0; g < NF; ++g)
+#pragma unroll
+            for (int b = 0; b < MF; ++b)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    fsum[GROUPED ? g : 0][GROUPED ? b : 0][e] =
+                        __builtin_fmaf((float)((int)acc[g][b][e] >> kAccShift), sg, fsum[GROUPED ? g : 0][GROUPED ? b : 0][e]);
+    };
     auto iteration = [&](int i, auto cur_tag, auto first_tag, auto tail_tag) {
         constexpr int CUR = decltype(cur_tag)::value;
         constexpr bool FIRST = decltype(first_tag)::value;
@@ -181,6 +196,11 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
         asm volatile("" ::: "memory");
         const int stn = (i + 1) & 3;
         const bool more = !TAIL || i + 1 < KT;                 // a next tile to read fragments of
+        i32x4 xhalf[GROUPED == 2 ? MF : 1];                    // GROUPED 2: the fragments with one half of the channels zeroed
+        if constexpr (GROUPED == 2) {
+#pragma unroll
+            for (int b = 0; b < MF; ++b) xhalf[b] = fq < 2 ? fx[CUR][b] : i32x4{0, 0, 0, 0};
+        }
 #pragma unroll
         for (int g = 0; g < NF; ++g) {
             const i32x4 wv = wfrag(fw[CUR][g]);
@@ -192,7 +212,8 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
                     acc[g][b] = Mfma16x16<DT>::mma(wv, fx[CUR][b], FIRST ? zero : acc[g][b]);
                 } else {
                     const i32x4 zero = {0, 0, 0, 0};
-                    acc[g][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wv, fx[CUR][b], FIRST ? zero : acc[g][b], 0, 0, 0);
+                    acc[g][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wv, GROUPED == 2 ? xhalf[GROUPED == 2 ? b : 0] : fx[CUR][b],
+                                                                      FIRST ? zero : acc[g][b], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 const int t = g * MF + b;
@@ -205,6 +226,20 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        if constexpr (GROUPED == 2) {
+            // channels 0..31 of this K tile are in acc: fold them, then the same tile with channels 32..63
+            fold(2 * i);
+#pragma unroll
+            for (int b = 0; b < MF; ++b) xhalf[b] = fq < 2 ? i32x4{0, 0, 0, 0} : fx[CUR][b];
+#pragma unroll
+            for (int g = 0; g < NF; ++g) {
+                const i32x4 wv = wfrag(fw[CUR][g]);
+#pragma unroll
+                for (int b = 0; b < MF; ++b)
+                    acc[g][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wv, xhalf[GROUPED == 2 ? b : 0], i32x4{0, 0, 0, 0}, 0, 0, 0);
+            }
+            fold(2 * i + 1);
+        }
     };
     using C0 = std::integral_constant<int, 0>;
     using C1 = std::integral_constant<int, 1>;
@@ -215,19 +250,13 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     auto step = [&](int i, auto cur_tag, auto first_tag, auto tail_tag) {
         if constexpr (!GROUPED) {
             iteration(i, cur_tag, first_tag, tail_tag);
+        } else if constexpr (GROUPED == 2) {
+            iteration(i, cur_tag, Yes{}, tail_tag);                // both folds of the tile happen inside
         } else {
             if (in_group == 0) iteration(i, cur_tag, Yes{}, tail_tag);
             else               iteration(i, cur_tag, No{}, tail_tag);
             if (++in_group == group_tiles) {
-                const float sg = s_ptr[group_idx];
-#pragma unroll
-                for (int g = 0; g < NF; ++g)
-#pragma unroll
-                    for (int b = 0; b < MF; ++b)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            fsum[GROUPED ? g : 0][GROUPED ? b : 0][e] =
-                                __builtin_fmaf((float)((int)acc[g][b][e] >> kAccShift), sg, fsum[GROUPED ? g : 0][GROUPED ? b : 0][e]);
+                fold(group_idx);
                 in_group = 0;
                 ++group_idx;
             }

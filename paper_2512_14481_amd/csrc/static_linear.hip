@@ -1045,7 +1045,8 @@ static void launch_mfma_grouped(const void* xin, const void* wq, const float* s_
     // the other wave on its SIMD; measured 1.3-1.6 x faster than 128x256 tiles at every group size.
     const int tile = tuning(SASQ_TUNE_LINEAR_TILE) == 2 ? 1 : 2;
     auto acc_out = reinterpret_cast<int32_t*>(f_out);
-    if (use_k64(X_PREQ, WMODE)) {
+    // group_tiles 0 = groups of 32 channels: the 16x16x64 kernel only
+    if constexpr (WMODE != W_I4) if (use_k64(X_PREQ, WMODE) || group_tiles == 0) {
         GemmK64Args a{static_cast<const int8_t*>(xin), static_cast<const uint8_t*>(wq), s_g, s_w, bias,
                       static_cast<uint16_t*>(y), acc_out, M, N, K};
         launch_gemm_k64_grouped(a, (sasq_dtype)DT, WMODE, tile, group_tiles, st);
@@ -1069,7 +1070,9 @@ static void run_linear_grouped(const void* x, const float* s_g, const void* wq, 
         else        quantize_act_grouped_elem_kernel<DT><<<grid_of(n), 256, 0, st>>>(static_cast<const uint16_t*>(x), s_g, dst, n, (int)K, (int)group, a_bits);
     };
     if (xq_out) quantize_rowmajor(xq_out);
-    const bool mfma_ok = (K % kBK) == 0 && (group % kBK) == 0;
+    // groups of 32 channels run on the matrix units too (16x16x64 kernel, int8 and pre-arranged int4 weights)
+    const bool half_ok = group == 32 && (K % kBK) == 0 && wf != SASQ_W_INT4_PACKED;
+    const bool mfma_ok = ((K % kBK) == 0 && (group % kBK) == 0) || half_ok;
     if (mfma_ok) {
         // row-major packed int4 unpacks in (0,2,4,6,1,3,5,7) order: the activation bytes are stored to match
         if (wf == SASQ_W_INT4_PACKED)
@@ -1191,8 +1194,8 @@ extern "C" int sasq_static_linear_grouped(const void* x, const float* s_g, const
         return SASQ_ERR_UNSUPPORTED;
     if (dt != SASQ_F16 && dt != SASQ_BF16) return SASQ_ERR_UNSUPPORTED;
     if (wf == SASQ_W_INT4_PACKED && (K & 1)) return SASQ_ERR_SHAPE;
-    // the pre-arranged formats exist for the MFMA kernel only, which takes whole K tiles per group
-    if ((wf == SASQ_W_INT8_BLOCKED || wf == SASQ_W_INT4_BLOCKED) && ((K % kBK) || (group % kBK))) return SASQ_ERR_SHAPE;
+    // the pre-arranged formats exist for the MFMA kernels only, which take whole K tiles per group or groups of 32
+    if ((wf == SASQ_W_INT8_BLOCKED || wf == SASQ_W_INT4_BLOCKED) && ((K % kBK) || ((group % kBK) && group != 32))) return SASQ_ERR_SHAPE;
     if ((M * N + 255) / 256 > 0x7FFFFFFF) return SASQ_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(wq) || !aligned16(y) || (f_out && !aligned16(f_out)) ||
         (xq_out && (reinterpret_cast<uintptr_t>(xq_out) & 7u))) return SASQ_ERR_ALIGN;

@@ -36,7 +36,7 @@ void gemm_k64_kernel(const int8_t* __restrict__ xq, const uint8_t* __restrict__ 
     gemm_k64_body<DT, WMODE, BM, BN, ROWS>(xq, wq, s_ptr, s_w, bias, y, acc_out, M, N, K, tm, tn, lds);
 }
 
-template <int DT, int WMODE, int BM, int BN>
+template <int DT, int WMODE, int BM, int BN, int GMODE>
 __global__ __launch_bounds__(kGemmThreads)
 __attribute__((amdgpu_waves_per_eu(Tile<BM, BN>::kWavesPerSimd, Tile<BM, BN>::kWavesPerSimd)))
 void gemm_k64_grouped_kernel(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq,
@@ -47,7 +47,7 @@ void gemm_k64_grouped_kernel(const int8_t* __restrict__ xq, const uint8_t* __res
     __shared__ __attribute__((aligned(1024))) char lds[lds_bytes_k64<BM, BN>()];
     int tm, tn;
     if (!tile_of_block((int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
-    gemm_k64_body<DT, WMODE, BM, BN, false, true>(xq, wq, s_g, s_w, bias, y, f_out, M, N, K, tm, tn, lds, group_tiles);
+    gemm_k64_body<DT, WMODE, BM, BN, false, GMODE>(xq, wq, s_g, s_w, bias, y, f_out, M, N, K, tm, tn, lds, group_tiles);
 }
 
 // Several projections in one launch, 256x256 tiles: each projection owns a run of workgroup ids
@@ -112,15 +112,19 @@ static void launch_grouped_one(const GemmK64Args& a, int group_tiles, hipStream_
 {
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-    gemm_k64_grouped_kernel<DT, WMODE, BM, BN><<<grid, kGemmThreads, 0, st>>>(
-        a.xq, a.wq, a.s, a.s_w, a.bias, a.y, a.acc_out, (int)a.M, (int)a.N, (int)a.K, tiles_m, tiles_n, group_tiles);
+    if (group_tiles == 0)     // groups of 32 channels: two per K tile
+        gemm_k64_grouped_kernel<DT, WMODE, BM, BN, 2><<<grid, kGemmThreads, 0, st>>>(
+            a.xq, a.wq, a.s, a.s_w, a.bias, a.y, a.acc_out, (int)a.M, (int)a.N, (int)a.K, tiles_m, tiles_n, 0);
+    else
+        gemm_k64_grouped_kernel<DT, WMODE, BM, BN, 1><<<grid, kGemmThreads, 0, st>>>(
+            a.xq, a.wq, a.s, a.s_w, a.bias, a.y, a.acc_out, (int)a.M, (int)a.N, (int)a.K, tiles_m, tiles_n, group_tiles);
 }
 
 template <int DT, int WMODE>
 static void launch_grouped_w(const GemmK64Args& a, int tile, int group_tiles, hipStream_t st)
 {
-    if (tile == 1) launch_grouped_one<DT, WMODE, 128, 256>(a, group_tiles, st);
-    else           launch_grouped_one<DT, WMODE, 128, 128>(a, group_tiles, st);
+    if (tile == 1 && group_tiles != 0) launch_grouped_one<DT, WMODE, 128, 256>(a, group_tiles, st);
+    else                               launch_grouped_one<DT, WMODE, 128, 128>(a, group_tiles, st);
 }
 
 template <int DT>

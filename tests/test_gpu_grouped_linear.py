@@ -79,6 +79,22 @@ def test_grouped_linear_mfma(shape, group, dtype, fmt, blocked, tile):
         assert np.array_equal(y2, y)
 
 
+@pytest.mark.parametrize("blocked", [False, True])
+@pytest.mark.parametrize("dtype,fmt", [("f16", "int8"), ("bf16", "int4"), ("bf16", "int8")])
+@pytest.mark.parametrize("shape", [(33, 47, 128), (256, 256, 64), (300, 520, 384), (257, 255, 1024), (130, 700, 320)])
+def test_grouped_linear_groups_of_32(shape, dtype, fmt, blocked):
+    """Groups of 32 channels, two per 64-byte K tile: the matrix-unit path multiplies every K tile twice, one half
+    of the channels at a time.  Row-major int4 weights stay on the scalar kernel and are compared all the same."""
+    xb, wq, s_w, bias, s_g = problem(53, shape, 32, dtype, fmt)
+    ref = oracle.static_linear_grouped(xb, s_g, wq, s_w, bias, 32, 8, fmt, dtype)
+    y, f, xq = run_grouped(xb, s_g, wq, s_w, bias, 32, fmt, dtype, blocked)
+    assert np.array_equal(xq, ref["xq"]), "activation codes"
+    assert np.array_equal(f.view(np.uint32), ref["f"].view(np.uint32)) or np.array_equal(f, ref["f"]), "fp32 group sums"
+    assert_same_values(y, ref["y"], dtype, "Y")
+    y2, _, _ = run_grouped(xb, s_g, wq, s_w, bias, 32, fmt, dtype, blocked, want_debug=False)
+    assert np.array_equal(y2, y)
+
+
 @pytest.mark.parametrize("dtype,fmt", [("f16", "int8"), ("bf16", "int4"), ("f16", "int4")])
 @pytest.mark.parametrize("shape,group", [((3, 5, 8), 1), ((19, 23, 70), 7), ((19, 23, 70), 70), ((33, 47, 128), 1),
                                          ((33, 47, 128), 16), ((64, 256, 256), 32), ((1, 1, 2), 2)])
@@ -103,7 +119,7 @@ def test_grouped_linear_rejects():
         B._ptr(ws), ws.numel(), None)
     assert call(3, 0) == 2          # group does not divide K
     assert call(0, 0) == 2
-    assert call(32, 2) == 2         # pre-arranged weights need whole K tiles per group
+    assert call(16, 2) == 2         # pre-arranged weights need whole K tiles per group, or groups of 32
     assert call(64, 7) == 4
 
 
