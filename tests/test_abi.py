@@ -78,6 +78,19 @@ def test_host_side_validation(lib):
     assert bwd(good, None, good, good, good, i64(4), i64(4), 8, 0, good, ctypes.c_size_t(1 << 20), None) == 1
     assert bwd(good, good, good, good, good, i64(4), i64(4), 8, 0, None, ctypes.c_size_t(0), None) == 5
     assert bwd(good, good, good, good, good, i64(4), i64(4), 8, 0, good, ctypes.c_size_t(8), None) == 5
+    bst = lib.sasq_fakequant_bwd_static                    # the variant that allocates nothing: same checks, no workspace
+    assert bst(good, None, good, good, good, i64(4), i64(4), 8, 0, None) == 1
+    assert bst(good, good, good, good, None, i64(4), i64(4), 8, 0, None) == 1
+    assert bst(good, good, good, good, good, i64(0), i64(4), 8, 0, None) == 2
+    assert bst(good, good, good, good, good, i64(1 << 21), i64(1 << 20), 8, 0, None) == 2     # above the stated maximum
+    assert bst(good, good, good, good, good, i64(4), i64(4), 9, 0, None) == 4
+    assert bst(good, odd, good, good, good, i64(4), i64(4), 8, 0, None) == 3
+    assert bst(good, good, good, odd, good, i64(4), i64(4), 8, 0, None) == 3
+    tune = lib.sasq_set_tuning
+    assert tune(-1, 0) == 4 and tune(5, 0) == 4            # no such knob
+    assert tune(0, 3) == 4 and tune(1, 4) == 4 and tune(2, 3) == 4 and tune(3, 4) == 4 and tune(4, 3) == 4
+    assert tune(1, -1) == 4
+    assert all(tune(k, 0) == 0 for k in range(5))          # 0 = the library's own choice
     lin = lib.sasq_static_linear
     big = ctypes.c_size_t(1 << 40)
     args = lambda **kw: [kw.get("x", good), good, kw.get("wq", good), good, None, good, None, None,
@@ -101,7 +114,8 @@ def test_host_side_validation(lib):
     assert lg(*gargs(x=None)) == 1
     assert lg(*gargs(group=0)) == 2
     assert lg(*gargs(group=48)) == 2
-    assert lg(*gargs(group=32, wf=2)) == 2
+    assert lg(*gargs(group=16, wf=2)) == 2     # pre-arranged weights: whole K tiles per group, or groups of 32
+    assert lg(*gargs(group=32, wf=2, K=96)) == 2
     assert lg(*gargs(wf=9)) == 4
     assert lg(*gargs(bits=1)) == 4
     assert lg(*gargs(ws=None)) == 5

@@ -104,12 +104,17 @@ LIN_BATCHES = [
     [(33, 47, 128)],
     [(300, 520, 384), (300, 260, 1024), (300, 520, 64)],
     [(257, 255, 1024), (40, 300, 64), (512, 768, 512), (64, 256, 256), (1, 1, 128), (260, 70, 192), (130, 700, 512), (256, 256, 128)],
+    # more than 256 tiles of 256x256 with a short last round: its tiles are handed out as 128-row halves.  The
+    # first M leaves 204 rows in the last row of tiles (a full upper half, a ragged lower one), the second 100
+    # rows (the lower halves have nothing to do)
+    [(250, 200, 128), (4300, 4090, 64)],
+    [(4196, 4096, 64)],
 ]
 
 
 @pytest.mark.parametrize("blocked", [False, True])
 @pytest.mark.parametrize("dtype,fmt", [("f16", "int8"), ("bf16", "int4")])
-@pytest.mark.parametrize("batch", LIN_BATCHES, ids=["one", "three", "eight"])
+@pytest.mark.parametrize("batch", LIN_BATCHES, ids=["one", "three", "eight", "split-tail", "split-tail-short"])
 def test_linear_batch_matches_oracle(batch, dtype, fmt, blocked):
     wf = WF[(fmt, blocked)]
     items, refs = [], []
