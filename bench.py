@@ -40,14 +40,15 @@ from paper_2512_14481_amd import workloads as wl       # noqa: E402
 
 INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8, published
 F16_MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense fp16 / bf16, published
-# what a register-only v_mfma_i32_32x32x32_i8 loop sustains on this part with GEMM-like operand codes (the part is
-# power-limited under MFMA load; profiles/mfma_peak_and_clock.txt) -- context for `frac`, not the roofline's peak
-INT8_MFMA_SUSTAINED_TOPS = 3700.0    # 3613-3750 across boxes (python bench.py --mfma-peak)
+# what a register-only v_mfma_i32_16x16x64_i8 loop (the default GEMM's instruction) sustains on this part with GEMM-like
+# operand codes (the part is power-limited under MFMA load; profiles/mfma_peak_and_clock.txt) -- context for `frac`, not
+# the roofline's peak
+INT8_MFMA_SUSTAINED_TOPS = 4400.0    # 4150-4580 across launches and boxes (python bench.py --mfma-peak)
 # HBM-side bytes per static linear call (both kernels) on config 3: RECORDED constants, not read in
 # this run: rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a plain 1 GiB copy), from
 # the counter passes summarised in profiles/bench_c3_mlp7b_counters.txt.
-C3_LINEAR_TRAFFIC_BYTES = 450654 * 1024          # one call per projection, average
-C3_LINEAR_BATCH_TRAFFIC_BYTES = 1364068 * 1024   # the batched call (all three projections)
+C3_LINEAR_TRAFFIC_BYTES = 450324 * 1024          # one call per projection, average
+C3_LINEAR_BATCH_TRAFFIC_BYTES = 1387602 * 1024   # the batched call (all three projections)
 TRAFFIC_SOURCE = "recorded constant from profiles/bench_c3_mlp7b_counters.txt (rocprofv3 FETCH_SIZE/WRITE_SIZE, copy-calibrated), not measured in this run"
 HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published
 LR = 2e-4
