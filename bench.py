@@ -222,8 +222,9 @@ def cpu_baseline(cfg, rows: int):
     import oracle
     from threadpoolctl import threadpool_limits
     cores = oracle.threads()
+    rows = min(rows, cfg.M)
     t_all, ops_all = _oracle_step(cfg, rows)
-    rows1 = max(16, rows // max(cores, 1))
+    rows1 = min(cfg.M, max(16, rows // max(cores, 1)))
     with threadpool_limits(limits=1, user_api="openmp"):
         one = oracle.threads()
         t_one, ops_one = _oracle_step(cfg, rows1)
