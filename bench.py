@@ -257,7 +257,8 @@ def mfma_peak():
     out = {"metric": "register-only MFMA loop, sustained", "unit": "TOP/s (TFLOP/s for f16)", "iters_per_launch": iters,
            "launches": launches, "patterns": {}}
     for kind, name, ops in ((0, "i8 32x32x32 zeros", 65536.0), (1, "i8 32x32x32 random bits", 65536.0),
-                            (2, "i8 32x32x32 GEMM-like codes", 65536.0), (4, "i8 16x16x64 GEMM-like codes", 131072.0),
+                            (2, "i8 32x32x32 GEMM-like codes", 65536.0), (5, "i8 16x16x64 zeros", 131072.0),
+                            (4, "i8 16x16x64 GEMM-like codes", 131072.0),
                             (3, "f16 32x32x16 small random values", 32768.0)):
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(launches + 1)]
         torch.cuda.synchronize()

@@ -61,6 +61,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
 // The same 128x128 block per wave as 8 x 8 tiles of v_mfma_i32_16x16x64_i8, GEMM-like codes; the weight-like operand is
 // the MFMA's first source as in the library's GEMM.
+template <bool ZERO>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void mfma_probe_i8_k64_kernel(int* sink, int iters)
 {
     i32x4 acc[8][8];
@@ -75,8 +76,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 av |= (s2 == 0 ? 0xFFu : (s2 == 3 ? 1u : 0u)) << (8 * e);
                 bv |= ((((g >> (6 * e)) & 63u) - 32u) & 0xFFu) << (8 * e);
             }
-            a[u][j] = (int)av;
-            b[u][j] = (int)bv;
+            a[u][j] = ZERO ? 0 : (int)av;                      // ZERO: the issue rate without data-dependent power
+            b[u][j] = ZERO ? 0 : (int)bv;
         }
     for (int i = 0; i < iters; ++i) {
 #pragma unroll
@@ -117,7 +118,7 @@ using namespace sasq_bench;
 
 // kind 0: v_mfma_i32_32x32x32_i8 on zero operands, 1: on random bits, 2: on GEMM-like codes (activation bytes in
 // {-1, 0, 0, 1}, weight bytes in [-32, 31]); 3: v_mfma_f32_32x32x16_f16 on small random values; 4: v_mfma_i32_16x16x64_i8
-// on the codes of kind 2.  256 workgroups of 4 waves, `iters` x 16 MFMAs of 32x32 (64 of 16x16) per wave; sink: 65536 ints.
+// on the codes of kind 2, 5: the same on zero operands.  256 workgroups of 4 waves, `iters` x 16 MFMAs of 32x32 (64 of 16x16) per wave; sink: 65536 ints.
 // Returns 0, or 1 for a bad argument, 2 for a launch error.
 extern "C" int sasq_bench_mfma_probe(int kind, int iters, int* sink, void* stream)
 {
@@ -129,7 +130,8 @@ extern "C" int sasq_bench_mfma_probe(int kind, int iters, int* sink, void* strea
         case 1: mfma_probe_i8_kernel<1><<<256, 256, 0, st>>>(sink, iters); break;
         case 2: mfma_probe_i8_kernel<2><<<256, 256, 0, st>>>(sink, iters); break;
         case 3: mfma_probe_f16_kernel<<<256, 256, 0, st>>>(sink, iters); break;
-        case 4: mfma_probe_i8_k64_kernel<<<256, 256, 0, st>>>(sink, iters); break;
+        case 4: mfma_probe_i8_k64_kernel<false><<<256, 256, 0, st>>>(sink, iters); break;
+        case 5: mfma_probe_i8_k64_kernel<true><<<256, 256, 0, st>>>(sink, iters); break;
         default: return 1;
     }
     return hipGetLastError() == hipSuccess ? 0 : 2;

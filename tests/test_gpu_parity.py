@@ -496,6 +496,10 @@ def test_mfma_probe_runs_and_validates():
     assert probe(0, 3, ptr, stream) == 0                   # zero operands: every accumulator stays zero
     torch.cuda.synchronize()
     assert int(sink.abs().max()) == 0
+    sink.fill_(7)
+    assert probe(5, 3, ptr, stream) == 0                   # the 16x16x64 form on zero operands
+    torch.cuda.synchronize()
+    assert int(sink.abs().max()) == 0
     for kind in (1, 2, 3, 4):
         assert probe(kind, 2, ptr, stream) == 0
     torch.cuda.synchronize()
