@@ -235,6 +235,52 @@ def cpu_baseline(cfg, rows: int):
                               "sample": f"first {rows1} tokens, same step; {t_one:.1f} s"}}
 
 
+def tile_timestamps(cfg, layer, run_step, settle: int):
+    """Where the cycles of a tile of the batched GEMM go, in the benchmark's steady state: `settle` steps on the
+    instrumented library, then one step whose GEMM workgroups stamp s_memtime / s_memrealtime at body start, after the
+    pipeline fill, after the K loop, after the stages have drained and after the epilogue."""
+    lib = B._lib()
+    lib.sasq_ts_set_buffer.argtypes = [ctypes.c_void_p]
+    lib.sasq_ts_set_buffer.restype = ctypes.c_int
+    if not layer.lin_batched:
+        sys.exit("bench.py: --tile-timestamps stamps the batched GEMM; this configuration does not use it")
+    for _ in range(settle):
+        run_step()
+    torch.cuda.synchronize()
+    max_wgs = 1 << 16
+    buf = torch.zeros(max_wgs * 16, dtype=torch.int64, device="cuda")
+    if lib.sasq_ts_set_buffer(buf.data_ptr()) != 0:
+        sys.exit("bench.py: could not set the timestamp buffer")
+    run_step()
+    torch.cuda.synchronize()
+    lib.sasq_ts_set_buffer(None)
+    t = buf.cpu().numpy().reshape(max_wgs, 16)
+    t = t[t[:, 0] != 0]
+    cyc, wall = t[:, [0, 2, 4, 6, 8]].astype(np.float64), t[:, [1, 3, 5, 7, 9]].astype(np.float64)
+    K, half = t[:, 14], t[:, 15]
+    span_us = (wall[:, 4].max() - wall[:, 0].min()) / 100.0
+    total_us = (wall[:, 4] - wall[:, 0]) / 100.0
+    out = {"metric": "cycles per tile of the batched int8 GEMM (instrumented build), medians over the tiles of one call",
+           "config": cfg.name, "workgroups": int(len(t)), "kernel_span_us": round(span_us, 1),
+           "sum_of_tile_times_over_256_us": round(float(total_us.sum()) / 256.0, 1),
+           "shader_clock_ghz": round(float(np.median((cyc[:, 4] - cyc[:, 0]) / np.maximum(total_us, 1e-9)) / 1e3), 3), "tiles": []}
+    for k in sorted(set(K.tolist())):
+        for h in (0, 1, 2):
+            m = (K == k) & (half == h)
+            if not m.any():
+                continue
+            kt = int(k) // 64
+            d = np.diff(cyc[m], axis=1)                # fill, K loop, drain, epilogue
+            med = np.median(d, axis=0)
+            out["tiles"].append({"K": int(k), "shape": "256x256" if h == 0 else "128x256 (split last round)", "count": int(m.sum()),
+                                 "fill": int(med[0]), "k_loop": int(med[1]), "per_k_tile": round(float(med[1]) / kt, 1),
+                                 "per_k_tile_p10_p90": [round(float(np.percentile(d[:, 1], q)) / kt, 1) for q in (10, 90)],
+                                 "mfma_issue_per_k_tile": 1024 if h == 0 else 512,
+                                 "drain": int(med[2]), "epilogue": int(med[3]), "total": int(np.median(cyc[m][:, 4] - cyc[m][:, 0])),
+                                 "total_us": round(float(np.median(total_us[m])), 1)})
+    print(json.dumps(out))
+
+
 def load_probe():
     """The benchmark's register-only MFMA loop (paper_2512_14481_amd/bench_csrc, built by the package's build step
     into libsasq_bench.so): tooling of this script, not an entry point of the SASQ library."""
@@ -293,6 +339,10 @@ def main():
     ap.add_argument("--mfma-peak", action="store_true",
                     help="instead of the workload: time the library's register-only MFMA loop under sustained load "
                          "(80 back-to-back launches per operand pattern) and print what the matrix units sustain")
+    ap.add_argument("--tile-timestamps", action="store_true",
+                    help="instead of the timings: run the workload on the instrumented build of the library (libsasq_ts.so: "
+                         "cycle and wall-clock stamps at five points of every tile of the batched GEMM), settle for W + K steps, "
+                         "stamp one step and print where a tile's cycles go")
     ap.add_argument("--tune", action="append", default=[], metavar="KNOB=VALUE",
                     help="force a kernel variant through sasq_set_tuning for the whole run (for profiles that compare variants): "
                          "path=twopass|fused, tile=256|128x256|128, mfma=32x32x32|16x16x64; path and tile act on single calls, "
@@ -310,6 +360,12 @@ def main():
         torch.cuda.set_device(0)
         mfma_peak()
         return
+
+    if a.tile_timestamps:
+        ts_lib = os.path.join(ROOT, "paper_2512_14481_amd", "libsasq_ts.so")
+        if not os.path.exists(ts_lib):
+            sys.exit(f"bench.py: {ts_lib} is missing: build it with `python -m paper_2512_14481_amd.build`")
+        B.LIB_PATH = ts_lib                            # before the binding loads anything: same entry points, stamped GEMM
 
     knobs = {"path": (B.SASQ_TUNE_LINEAR_PATH, {"twopass": 1, "fused": 2}),
              "tile": (B.SASQ_TUNE_LINEAR_TILE, {"256": 1, "128x256": 2, "128": 3}),
@@ -334,6 +390,10 @@ def main():
     layer = Layer(projs, rot)
     run_step = (lambda ev=None: step_unbatched(layer, ws_small, ev)) if a.unbatched else (lambda ev=None: step(layer, ev))
     torch.cuda.synchronize()
+
+    if a.tile_timestamps:
+        tile_timestamps(cfg, layer, run_step, a.warmup + a.steps)
+        return
 
     if a.calib:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)

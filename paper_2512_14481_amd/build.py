@@ -12,6 +12,8 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsasq.so")
 BENCH_CSRC = os.path.join(PKG, "bench_csrc")
 BENCH_LIB = os.path.join(PKG, "libsasq_bench.so")    # benchmark tooling (register-only MFMA probe), not part of the C ABI
+TS_LIB = os.path.join(PKG, "libsasq_ts.so")          # benchmark tooling: the library with per-tile timestamps in the batched GEMM
+TS_SOURCE = "static_linear_k64.hip"                  # the one source the instrumented build compiles differently
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -64,11 +66,29 @@ def build(verbose: bool = True, incremental: bool = False) -> str:
             subprocess.run(cmd, check=True)
             return obj
 
+        def compile_ts(src: str) -> str:
+            obj = os.path.join(tmp, os.path.basename(src) + ".ts.o")
+            if incremental and os.path.exists(obj) and all(os.path.getmtime(d) <= os.path.getmtime(obj) for d in [src] + headers):
+                return obj
+            cmd = [HIPCC] + compile_flags + ["-DSASQ_GEMM_TIMESTAMPS", "-c", src, "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            subprocess.run(cmd, check=True)
+            return obj
+
         srcs = sources()
-        workers = max(1, min(len(srcs), int(os.environ.get("MAX_JOBS", "0")) or os.cpu_count() or 1))
+        workers = max(1, min(len(srcs) + 1, int(os.environ.get("MAX_JOBS", "0")) or os.cpu_count() or 1))
         with concurrent.futures.ThreadPoolExecutor(max_workers=workers) as pool:
+            ts_future = pool.submit(compile_ts, os.path.join(CSRC, TS_SOURCE))
             objs = list(pool.map(compile_one, srcs))
+            ts_obj = ts_future.result()
         link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+        if verbose:
+            print(" ".join(link), flush=True)
+        subprocess.run(link, check=True)
+        # the same library with the instrumented GEMM object in place of the plain one
+        ts_objs = [ts_obj if os.path.basename(o) == TS_SOURCE + ".o" else o for o in objs]
+        link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", TS_LIB] + ts_objs
         if verbose:
             print(" ".join(link), flush=True)
         subprocess.run(link, check=True)

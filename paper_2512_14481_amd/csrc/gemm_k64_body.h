@@ -45,6 +45,13 @@ __device__ __forceinline__ void lds_load16(uint32_t lds_addr, const void* base, 
                  :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
 }   // row-major int8 / pre-arranged int8 (values shared with static_linear.hip)
 
+// Measurement hook: a translation unit that wants cycle and wall-clock stamps at five points of every tile (body start,
+// pipeline filled, K loop done, stages drained, epilogue done) defines SASQ_TILE_TS(k) before including this file (the
+// benchmark's instrumented build of static_linear_k64.hip does); everywhere else it expands to nothing.
+#ifndef SASQ_TILE_TS
+#define SASQ_TILE_TS(k)
+#endif
+
 // GROUPED (Sec. 3, Eq. 3): one activation factor per group of `group_tiles` K tiles; s_ptr then
 // points at the factors.  The int32 accumulators cover one group at a time (a group's first K tile
 // multiplies into a zero accumulator operand) and are folded into fp32 sums at its end,
@@ -262,6 +269,7 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
             }
         }
     };
+    SASQ_TILE_TS(0);
     // fill: the first four tiles requested, tile 0 landed for everyone, its fragments read
     const int nfill = min(KT, 4);
     for (int t = 0; t < nfill; ++t)
@@ -275,6 +283,7 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     asm volatile("" ::: "memory");
 #pragma unroll
     for (int k = 0; k < NFR; ++k) read_frag(0, 0, k);
+    SASQ_TILE_TS(1);
     // An even number of steady iterations (they always have a tile i+4 to request), then the tail,
     // written out so that every copy of the loop body knows its fragment set at compile time.
     const int steady = KT >= 6 ? ((KT - 4) & ~1) : 0;
@@ -314,8 +323,10 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
             }
         }
     }
+    SASQ_TILE_TS(2);
     // the last fragment reads (none pending) and loads (none in flight) are complete; LDS is reused
     __builtin_amdgcn_s_waitcnt(kWaitLgkm0 & waitcnt_vm(0));
+    SASQ_TILE_TS(3);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 
@@ -479,6 +490,7 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
                                                                   : FLT ? __float_as_int((float)acc[g][b][e]) : ((int)acc[g][b][e] >> kAccShift);
             }
     }
+    SASQ_TILE_TS(4);
 }
 
 }  // namespace sasq

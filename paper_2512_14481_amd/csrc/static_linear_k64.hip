@@ -17,6 +17,21 @@
 #include "sasq_device.h"
 #include "gemm_tile.h"
 #include "gemm_k64.h"
+
+// Instrumented build (the benchmark's libsasq_ts.so, `bench.py --tile-timestamps`; never the product library): thread 0
+// of every workgroup of the batched kernel writes s_memtime (shader cycles) and s_memrealtime (100 MHz) at five points
+// of its tile into a caller-provided buffer of 16 uint64 per workgroup: [2k], [2k+1] = the stamps of point k; [14] = K,
+// [15] = 0 for a whole tile, 1 / 2 for the upper / lower half of a split one.
+#ifdef SASQ_GEMM_TIMESTAMPS
+namespace sasq { __device__ unsigned long long* g_tile_ts = nullptr; }
+#define SASQ_TILE_TS(k)                                                                                   \
+    do {                                                                                                  \
+        if (sasq::g_tile_ts && threadIdx.x == 0) {                                                        \
+            sasq::g_tile_ts[(size_t)blockIdx.x * 16 + 2 * (k)] = __builtin_amdgcn_s_memtime();            \
+            sasq::g_tile_ts[(size_t)blockIdx.x * 16 + 2 * (k) + 1] = __builtin_amdgcn_s_memrealtime();    \
+        }                                                                                                 \
+    } while (0)
+#endif
 #include "gemm_k64_body.h"
 #include <type_traits>
 
@@ -72,6 +87,12 @@ void gemm_k64_batch_kernel(const LinBatch b)
     const LinItem& it = b.it[k];
     int tm, tn;
     if (!tile_of_block(bid - b.first_block[k], it.tiles_m, it.tiles_n, tm, tn)) return;
+#ifdef SASQ_GEMM_TIMESTAMPS
+    if (g_tile_ts && threadIdx.x == 0) {
+        g_tile_ts[(size_t)blockIdx.x * 16 + 14] = (unsigned long long)it.K;
+        g_tile_ts[(size_t)blockIdx.x * 16 + 15] = (unsigned long long)(half + 1);
+    }
+#endif
     if (half < 0) {
         gemm_k64_body<DT, WMODE, 256, 256, false>(it.xq, it.wq, it.s, it.s_w, it.bias, it.y, nullptr, it.M, it.N, it.K, tm, tn, lds);
     } else {
@@ -171,3 +192,12 @@ void launch_gemm_k64_batch(LinBatch& b, int grid, sasq_dtype dt, int wmode, bool
 }
 
 }  // namespace sasq
+
+#ifdef SASQ_GEMM_TIMESTAMPS
+// Where the batched GEMM's workgroups write their stamps from now on (device memory, 128 bytes per workgroup of the
+// launches to come; nullptr: nowhere).  Only the instrumented build exports this.
+extern "C" int sasq_ts_set_buffer(void* device_buffer)
+{
+    return hipMemcpyToSymbol(HIP_SYMBOL(sasq::g_tile_ts), &device_buffer, sizeof(device_buffer)) == hipSuccess ? 0 : 1;
+}
+#endif

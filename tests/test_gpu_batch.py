@@ -332,3 +332,46 @@ def test_batch_operators_sharing_one_input(dtype, shape, force_sharing):
             assert np.array_equal(wl.storage_bits_to_f32(to_bits(dxd[i]), dtype), wl.storage_bits_to_f32(ref["dx"], dtype)), i
         tol = 1e-4 * abs(ref["ds64"]) + 1e-7 * ref["sum_abs"] + 1e-30
         assert abs(float(ds1[i]) - ref["ds64"]) <= tol, (i, ds1[i], ref["ds64"])
+
+
+def test_instrumented_build_computes_the_same_and_stamps_in_order():
+    """The benchmark's instrumented build of the library (per-tile timestamps in the batched GEMM, bench.py
+    --tile-timestamps) against the product library on one batch: same Y bit for bit; every workgroup that ran a tile
+    left five non-decreasing cycle stamps and its K."""
+    import ctypes
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(B.__file__)), "libsasq_ts.so")
+    assert os.path.exists(path), "libsasq_ts.so missing: python -m paper_2512_14481_amd.build"
+    ts = ctypes.CDLL(path)
+    ts.sasq_ts_set_buffer.argtypes = [ctypes.c_void_p]
+    wf = WF[("int8", True)]
+    batch = [(300, 520, 384), (257, 255, 1024)]
+    items = []
+    for j, (M, N, K) in enumerate(batch):
+        xb = wl.random_bits(97, f"tsx{j}", (M, K), "f16", gain=2.0)
+        wq, s_w = oracle.quantize_weight(wl.random_f32(97, f"tsw{j}", (N, K), 0.02), "int8")
+        s = np.float32(oracle.absmax_scale(xb, 8, "f16") / 3)
+        items.append((to_dev(xb, "f16"), dev_scalar(s), device_weights(wq, "int8", True), torch.from_numpy(s_w).cuda(), None,
+                      torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")))
+    ws = B.new_workspace(B.sasq_static_linear_batch_workspace(items, wf))
+    B.sasq_static_linear_batch(items, wf, ws)
+    torch.cuda.synchronize()
+    want = [it[5].clone() for it in items]
+    for it in items:
+        it[5].fill_(float("nan"))
+    arr, dt = B._lin_items(items, wf)
+    stamps = torch.zeros(64 * 16, dtype=torch.int64, device="cuda")
+    assert ts.sasq_ts_set_buffer(stamps.data_ptr()) == 0
+    rc = ts.sasq_static_linear_batch(arr, len(items), 8, wf, dt, ctypes.c_void_p(ws.data_ptr()),
+                                     ctypes.c_size_t(ws.numel() * ws.element_size()), None)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert ts.sasq_ts_set_buffer(None) == 0
+    for j, it in enumerate(items):
+        assert torch.equal(it[5].view(torch.int16), want[j].view(torch.int16)), j
+    t = stamps.cpu().numpy().reshape(64, 16)
+    ran = t[t[:, 0] != 0]
+    assert len(ran) == 6 + 2                               # 2 x 3 tiles of the first item, 2 x 1 of the second
+    assert (np.diff(ran[:, [0, 2, 4, 6, 8]], axis=1) >= 0).all()
+    assert sorted(set(ran[:, 14].tolist())) == [384, 1024]
+
