@@ -123,7 +123,7 @@ def test_grouped_linear_rejects():
     assert call(64, 7) == 4
 
 
-@pytest.mark.parametrize("proj_name,group", [("gate", 128), ("down", 256)])
+@pytest.mark.parametrize("proj_name,group", [("gate", 128), ("down", 256), ("up", 32)])
 def test_grouped_linear_config3_sampled(proj_name, group):
     """Config-3 shapes in the configuration the benchmark times (pre-arranged int8 weights, no debug
     outputs); rows and columns sampled for the oracle, including tile edges."""
