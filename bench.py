@@ -470,6 +470,35 @@ def main():
                              "fakequant_frac": round(pp.fq_bytes / (tf_med * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
     ms_per_step = asked["ms_per_step"]
 
+    # the single-tensor operators on their own: nothing but the forward and backward launches of one tensor, over
+    # enough distinct copies (about 1.5 GB) that every launch reads cold memory; one entry per tensor size of the config
+    single = {}
+    for pp in projs:
+        n = pp.M * pp.K
+        if str(n) in single:
+            continue
+        sets = max(2, int(1.5e9 // (n * 8)))
+        xs = [pp.xf[0].clone() for _ in range(sets)]
+        dys = [pp.dy[0].clone() for _ in range(sets)]
+        ys = [torch.empty_like(pp.xf[0]) for _ in range(sets)]
+        dxs = [torch.empty_like(pp.xf[0]) for _ in range(sets)]
+        def pair(i):
+            B.sasq_fakequant_fwd(xs[i % sets], pp.s, ys[i % sets], None, 8)
+            B.sasq_fakequant_bwd(xs[(i + sets // 2) % sets], dys[i % sets], pp.s, dxs[i % sets], pp.ds, ws_small, 8)
+        for i in range(sets):
+            pair(i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 6 * sets
+        e0.record()
+        for i in range(reps):
+            pair(i)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        single[str(n)] = {"shape": [pp.M, pp.K], "fwd_bwd_us": round(us, 2), "gbps": round(10 * n / us / 1e3, 1),
+                          "frac": round(10 * n / us / 1e3 / HBM_PEAK_GBPS, 4), "copies": sets}
+        del xs, dys, ys, dxs
+
     # per-channel fake-quant (the granularity of the paper's main runs), measured after the timed
     # region on the same tensors: one scale per column, ds a column reduction
     pc = None
@@ -663,6 +692,10 @@ def main():
     fq.update(fakequant_of(asked))
     fq["bytes_counted"] = int(layer.fq_bytes)
     fq["bytes_moved"] = int(layer.fq_bytes if a.unbatched else layer.fq_bytes_moved)
+    fq["single_tensor_alone"] = single
+    fq["single_tensor_alone_note"] = ("sasq_fakequant_fwd + sasq_fakequant_bwd of ONE tensor per launch pair, back to back over `copies` "
+                                      "distinct sets of buffers (cold), nothing else running; per_projection times the same pair inside "
+                                      "the unbatched step, between GEMMs")
     fq["protocol"] = (f"cold: {rot} copies of x, dy, x', dx per direction used in turn; whatever a launch reads was last touched "
                       "more than 1 GB of traffic earlier" if rot > 1 else "warm: one copy of every tensor")
     fq["note"] = ("achieved/frac count 10 B/element per operator (fwd 2+2, bwd 2+2+2); operators in front of projections that "
