@@ -43,7 +43,7 @@ __device__ __forceinline__ void lds_load16(uint32_t lds_addr, const void* base, 
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(lds_addr), "v"(lane_off), "s"(base) : "memory");
-}   // row-major int8 / pre-arranged int8 (values shared with static_linear.hip)
+}
 
 // Measurement hook: a translation unit that wants cycle and wall-clock stamps at five points of every tile (body start,
 // pipeline filled, K loop done, stages drained, epilogue done) defines SASQ_TILE_TS(k) before including this file (the
