@@ -145,6 +145,15 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
             fw[set][idx - MF] = *reinterpret_cast<const i32x4*>(stage_ptr(st, 1) + wbase + (idx - MF) * 16 * kBK + foff);
         }
     };
+    auto wfrag_piece = [&](const WFrag& f, int j) -> int {   // output dword j of the unpacked operand
+        if constexpr (I4) {
+            const uint32_t p = f[j >> 1];
+            return (int)(((j & 1) ? p : (p << 4)) & 0xF0F0F0F0u);
+        } else {
+            return f[j];
+        }
+    };
+    i32x4 wv_ahead = {0, 0, 0, 0}, wv_next = {0, 0, 0, 0};   // packed int4: the weight operand of the row to come
     auto wfrag = [&](const WFrag& f) -> i32x4 {         // the MFMA's weight operand: as read, or unpacked here
         if constexpr (I4) {
             const uint32_t p0 = f[0], p1 = f[1];
@@ -210,7 +219,13 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
         }
 #pragma unroll
         for (int g = 0; g < NF; ++g) {
-            const i32x4 wv = wfrag(fw[CUR][g]);
+            // Packed int4: the operand of this row was unpacked while the previous row multiplied (wv_ahead), and the next
+            // row's -- at the end of the tile, row 0 of the next tile -- is unpacked one output dword behind each of this
+            // row's first four MFMAs: done at the top of a row, the six VALU operations and their latency stand in front of
+            // the row's first MFMA (195 of 1405 cycles per K tile on the 13B layer).
+            const i32x4 wv = I4 ? wv_ahead : wfrag(fw[CUR][g]);
+            const bool ahead_in_tile = g + 1 < NF;
+            const WFrag& fnext = ahead_in_tile ? fw[CUR][g + 1 < NF ? g + 1 : 0] : fw[1 - CUR][0];
 #pragma unroll
             for (int b = 0; b < MF; ++b) {
                 // K tile 0 multiplies into a zero accumulator operand instead of clearing the accumulators
@@ -230,8 +245,12 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
                     const int u = t - kFragStep * NFR;
                     if (u % kLoadStep == 0 && u / kLoadStep < kLoads) dma(i + 4, u / kLoadStep);
                 }
+                if constexpr (I4) {
+                    if (b < 4 && (ahead_in_tile || more)) wv_next[b] = wfrag_piece(fnext, b);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
+            if constexpr (I4) wv_ahead = wv_next;
         }
         if constexpr (GROUPED == 2) {
             // channels 0..31 of this K tile are in acc: fold them, then the same tile with channels 32..63
@@ -283,6 +302,7 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     asm volatile("" ::: "memory");
 #pragma unroll
     for (int k = 0; k < NFR; ++k) read_frag(0, 0, k);
+    if constexpr (I4) wv_ahead = wfrag(fw[0][0]);
     SASQ_TILE_TS(1);
     // An even number of steady iterations (they always have a tile i+4 to request), then the tail,
     // written out so that every copy of the loop body knows its fragment set at compile time.
