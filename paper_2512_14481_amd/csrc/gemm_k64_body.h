@@ -126,11 +126,18 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     }
     constexpr int kWTileStep = (WMODE == KW_I8B || I4) ? 1024 : kBK;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_ptr_t)&lds[0] + (uint32_t)wave * 1024u;
-    auto dma = [&](int Tk, int j) {                  // loads 0..XS-1: activations, XS..: weights
-        const uint32_t st_off = (uint32_t)(Tk & 3) * T::kStageBytes;
-        if (j < XS) lds_load16(lds_base + j * 4096, st_off, xpanel + (int64_t)Tk * kXTileStep, xoff[j]);
-        else        lds_load16(lds_base + T::kXBytes + (j - XS) * 4096, st_off, wpanel + (int64_t)Tk * kWTileStep, woff[j - XS < WSL ? j - XS : 0]);
+    auto dma_at = [&](const int8_t* xtile, const int8_t* wtile, int j, int st) {   // loads 0..XS-1: activations, XS..: weights
+        const uint32_t st_off = (uint32_t)st * T::kStageBytes;
+        if (j < XS) lds_load16(lds_base + j * 4096, st_off, xtile, xoff[j]);
+        else        lds_load16(lds_base + T::kXBytes + (j - XS) * 4096, st_off, wtile, woff[j - XS < WSL ? j - XS : 0]);
     };
+    auto dma = [&](int Tk, int j, int st) {          // K tile Tk into stage st = Tk & 3
+        dma_at(xpanel + (int64_t)Tk * kXTileStep, wpanel + (int64_t)Tk * kWTileStep, j, st);
+    };
+    // The steady loop keeps the operands' addresses at its current group of four K tiles here: a load of
+    // tile i + 4 then adds a constant to them.
+    const int8_t* xrun = xpanel;
+    const int8_t* wrun = wpanel;
 
     // ---- LDS -> MFMA fragments: lane l reads chunk l/16 of row l%16 of a 16-row tile ----
     const int frow = lane & 15, fq = lane >> 4;
@@ -203,8 +210,9 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
                     fsum[GROUPED ? g : 0][GROUPED ? b : 0][e] =
                         __builtin_fmaf((float)((int)acc[g][b][e] >> kAccShift), sg, fsum[GROUPED ? g : 0][GROUPED ? b : 0][e]);
     };
-    auto iteration = [&](int i, auto cur_tag, auto first_tag, auto tail_tag) {
+    auto iteration = [&](int i, auto cur_tag, auto stage_tag, auto first_tag, auto tail_tag) {
         constexpr int CUR = decltype(cur_tag)::value;
+        constexpr int STG = decltype(stage_tag)::value;        // i & 3 where the copy of the body knows it, else -1
         constexpr bool FIRST = decltype(first_tag)::value;
         constexpr bool TAIL = decltype(tail_tag)::value;
         if (!TAIL) {
@@ -217,7 +225,7 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
         }
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        const int stn = (i + 1) & 3;
+        const int stn = STG >= 0 ? (STG + 1) & 3 : (i + 1) & 3;
         const bool more = !TAIL || i + 1 < KT;                 // a next tile to read fragments of
         i32x4 xhalf[GROUPED == 2 ? MF : 1];                    // GROUPED 2: the fragments with one half of the channels zeroed
         if constexpr (GROUPED == 2) {
@@ -250,7 +258,10 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
                     if (t % kFragStep == 0 && more) read_frag(1 - CUR, stn, t / kFragStep);
                 } else if (!TAIL || i + 4 < KT) {
                     const int u = t - kFragStep * NFR;
-                    if (u % kLoadStep == 0 && u / kLoadStep < kLoads) dma(i + 4, u / kLoadStep);
+                    if (u % kLoadStep == 0 && u / kLoadStep < kLoads) {
+                        if constexpr (STG >= 0) dma_at(xrun + (STG + 4) * kXTileStep, wrun + (STG + 4) * kWTileStep, u / kLoadStep, STG);
+                        else                    dma(i + 4, u / kLoadStep, i & 3);
+                    }
                 }
                 if constexpr (I4) {
                     if (b < 4 && (ahead_in_tile || more)) wv_next[b] = wfrag_piece(fnext, b);
@@ -276,18 +287,23 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     };
     using C0 = std::integral_constant<int, 0>;
     using C1 = std::integral_constant<int, 1>;
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    using S2 = std::integral_constant<int, 2>;
+    using S3 = std::integral_constant<int, 3>;
+    using SR = std::integral_constant<int, -1>;               // stage known only at run time
     using Yes = std::true_type;
     using No = std::false_type;
     // one K tile; with grouped factors also the group bookkeeping (all of it uniform)
     int in_group = 0, group_idx = 0;
-    auto step = [&](int i, auto cur_tag, auto first_tag, auto tail_tag) {
+    auto step = [&](int i, auto cur_tag, auto stage_tag, auto first_tag, auto tail_tag) {
         if constexpr (!GROUPED) {
-            iteration(i, cur_tag, first_tag, tail_tag);
+            iteration(i, cur_tag, stage_tag, first_tag, tail_tag);
         } else if constexpr (GROUPED == 2) {
-            iteration(i, cur_tag, Yes{}, tail_tag);                // both folds of the tile happen inside
+            iteration(i, cur_tag, stage_tag, Yes{}, tail_tag);     // both folds of the tile happen inside
         } else {
-            if (in_group == 0) iteration(i, cur_tag, Yes{}, tail_tag);
-            else               iteration(i, cur_tag, No{}, tail_tag);
+            if (in_group == 0) iteration(i, cur_tag, stage_tag, Yes{}, tail_tag);
+            else               iteration(i, cur_tag, stage_tag, No{}, tail_tag);
             if (++in_group == group_tiles) {
                 fold(group_idx);
                 in_group = 0;
@@ -300,7 +316,7 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     const int nfill = min(KT, 4);
     for (int t = 0; t < nfill; ++t)
 #pragma unroll
-        for (int j = 0; j < kLoads; ++j) dma(t, j);
+        for (int j = 0; j < kLoads; ++j) dma(t, j, t);
     if (nfill == 4)      __builtin_amdgcn_s_waitcnt(waitcnt_vm(3 * kLoads));
     else if (nfill == 3) __builtin_amdgcn_s_waitcnt(waitcnt_vm(2 * kLoads));
     else if (nfill == 2) __builtin_amdgcn_s_waitcnt(waitcnt_vm(kLoads));
@@ -311,16 +327,37 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     for (int k = 0; k < NFR; ++k) read_frag(0, 0, k);
     if constexpr (I4) wv_ahead = wfrag(fw[0][0]);
     SASQ_TILE_TS(1);
-    // An even number of steady iterations (they always have a tile i+4 to request), then the tail,
-    // written out so that every copy of the loop body knows its fragment set at compile time.
-    const int steady = KT >= 6 ? ((KT - 4) & ~1) : 0;
-    if (steady > 0) {
-        step(0, C0{}, Yes{}, No{});
-        step(1, C1{}, No{}, No{});
+    // A multiple of four steady iterations (they always have a tile i+4 to request), then the tail.
+    // The steady loop is written out four iterations at a time: every copy of the body then knows
+    // its fragment set and its LDS stages at compile time, and the addresses of its fragment reads
+    // and loads are constants instead of a chain of scalar arithmetic in front of the first read.
+    // (Whole-tile groups keep two iterations with run-time stages: their body exists once per accumulator
+    // mode already, and four copies of each push the register allocator into scratch memory.)
+    constexpr bool kBy4 = GROUPED != 1;
+    const int steady = !kBy4 ? (KT >= 6 ? ((KT - 4) & ~1) : 0) : KT >= 8 ? ((KT - 4) & ~3) : 0;
+    if constexpr (!kBy4) {
+        if (steady > 0) {
+            step(0, C0{}, SR{}, Yes{}, No{});
+            step(1, C1{}, SR{}, No{}, No{});
 #pragma unroll 1
-        for (int it = 2; it < steady; it += 2) {
-            step(it, C0{}, No{}, No{});
-            step(it + 1, C1{}, No{}, No{});
+            for (int it = 2; it < steady; it += 2) {
+                step(it, C0{}, SR{}, No{}, No{});
+                step(it + 1, C1{}, SR{}, No{}, No{});
+            }
+        }
+    } else if (steady > 0) {
+        step(0, C0{}, S0{}, Yes{}, No{});
+        step(1, C1{}, S1{}, No{}, No{});
+        step(2, C0{}, S2{}, No{}, No{});
+        step(3, C1{}, S3{}, No{}, No{});
+#pragma unroll 1
+        for (int it = 4; it < steady; it += 4) {
+            xrun += 4 * kXTileStep;
+            wrun += 4 * kWTileStep;
+            step(it, C0{}, S0{}, No{}, No{});
+            step(it + 1, C1{}, S1{}, No{}, No{});
+            step(it + 2, C0{}, S2{}, No{}, No{});
+            step(it + 3, C1{}, S3{}, No{}, No{});
         }
     } else if (!GROUPED) {
 #pragma unroll
@@ -339,14 +376,22 @@ void gemm_k64_body(const int8_t* __restrict__ xq, const uint8_t* __restrict__ wq
     if (cols_inside)
         lds_load16(lds_base - (uint32_t)wave * 1024u + T::kLds + (uint32_t)wave * kFacBytes, s_w + wn0,
                    (uint32_t)(lane & (BN / 8 - 1)) * 16u);   // lanes past BN/8 fetch the same factors again: no lane reads past the block
-    step(steady, C0{}, No{}, Yes{});                            // KT - steady is 1 .. 5
-    if (steady + 1 < KT) {
-        step(steady + 1, C1{}, No{}, Yes{});
-        if (steady + 2 < KT) {
-            step(steady + 2, C0{}, No{}, Yes{});
-            if (steady + 3 < KT) {
-                step(steady + 3, C1{}, No{}, Yes{});
-                if (steady + 4 < KT) step(steady + 4, C0{}, No{}, Yes{});
+    if constexpr (kBy4) {
+#pragma unroll 1
+        for (int i = steady; i < KT; i += 2) {                  // KT - steady is 1 .. 7, steady is even
+            step(i, C0{}, SR{}, No{}, Yes{});
+            if (i + 1 < KT) step(i + 1, C1{}, SR{}, No{}, Yes{});
+        }
+    } else {
+        step(steady, C0{}, SR{}, No{}, Yes{});                  // KT - steady is 1 .. 5
+        if (steady + 1 < KT) {
+            step(steady + 1, C1{}, SR{}, No{}, Yes{});
+            if (steady + 2 < KT) {
+                step(steady + 2, C0{}, SR{}, No{}, Yes{});
+                if (steady + 3 < KT) {
+                    step(steady + 3, C1{}, SR{}, No{}, Yes{});
+                    if (steady + 4 < KT) step(steady + 4, C0{}, SR{}, No{}, Yes{});
+                }
             }
         }
     }
