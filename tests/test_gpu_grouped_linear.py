@@ -81,7 +81,8 @@ def test_grouped_linear_mfma(shape, group, dtype, fmt, blocked, tile):
 
 @pytest.mark.parametrize("blocked", [False, True])
 @pytest.mark.parametrize("dtype,fmt", [("f16", "int8"), ("bf16", "int4"), ("bf16", "int8")])
-@pytest.mark.parametrize("shape", [(33, 47, 128), (256, 256, 64), (300, 520, 384), (257, 255, 1024), (130, 700, 320)])
+@pytest.mark.parametrize("shape", [(33, 47, 128), (256, 256, 64), (300, 520, 384), (257, 255, 1024), (130, 700, 320),
+                                   (140, 150, 576), (140, 150, 704), (70, 260, 960)])   # K loop remainders of 5, 7, 7 tiles
 def test_grouped_linear_groups_of_32(shape, dtype, fmt, blocked):
     """Groups of 32 channels, two per 64-byte K tile: the matrix-unit path multiplies every K tile twice, one half
     of the channels at a time.  Row-major int4 weights stay on the scalar kernel and are compared all the same."""

@@ -371,6 +371,25 @@ def test_static_linear_blocked_weights(shape, dtype, fmt, tile):
         assert np.array_equal(acc3, ref["acc"]) and np.array_equal(y3, y), "32x32x32 kernel"
 
 
+@pytest.mark.parametrize("tile", ["256", "128x256", "128"])
+@pytest.mark.parametrize("k_tiles", [5, 7, 9, 10, 11, 13, 14, 15, 17, 22])
+def test_static_linear_every_k_loop_remainder(k_tiles, tile):
+    """The GEMM's K loop has a steady part of whole trips and a remainder of one to seven 64-channel
+    tiles: every remainder, with and without a steady part, on row-major and pre-arranged weights of
+    both widths (the other shapes in this file all leave a remainder of four)."""
+    M, N, K = 150, 275, 64 * k_tiles
+    for dtype, fmt, blocked in (("f16", "int8", True), ("bf16", "int8", False), ("bf16", "int4", True), ("f16", "int4", False)):
+        xb = wl.random_bits(16, f"kx{k_tiles}{dtype}", (M, K), dtype, gain=2.0)
+        w = wl.random_f32(16, f"kw{k_tiles}", (N, K), 0.02)
+        wq, s_w = oracle.quantize_weight(w, fmt)
+        s = np.float32(oracle.absmax_scale(xb, 8, dtype) / 3)
+        ref = oracle.static_linear(xb, s, wq, s_w, None, 8, fmt, dtype)
+        y, acc, xq = run_linear(xb, s, wq, s_w, None, fmt, dtype, tile=tile, blocked=blocked)
+        assert np.array_equal(xq, ref["xq"]), "activation codes"
+        assert np.array_equal(acc, ref["acc"]), "int32 accumulators"
+        assert_same_values(y, ref["y"], dtype, "Y")
+
+
 @pytest.mark.parametrize("a_bits", [4, 6, 2])
 @pytest.mark.parametrize("path,blocked", [("twopass", False), ("fused", False), (None, True)])
 def test_static_linear_low_bit_activations(a_bits, path, blocked):
