@@ -47,8 +47,8 @@ INT8_MFMA_SUSTAINED_TOPS = 4400.0    # 4150-4580 across launches and boxes (pyth
 # HBM-side bytes per static linear call (both kernels) on config 3: RECORDED constants, not read in
 # this run: rocprofv3 FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (factors from a plain 1 GiB copy), from
 # the counter passes summarised in profiles/bench_c3_mlp7b_counters.txt.
-C3_LINEAR_TRAFFIC_BYTES = 450260 * 1024          # one call per projection, average
-C3_LINEAR_BATCH_TRAFFIC_BYTES = 1388136 * 1024   # the batched call (all three projections)
+C3_LINEAR_TRAFFIC_BYTES = 449967 * 1024          # one call per projection, average
+C3_LINEAR_BATCH_TRAFFIC_BYTES = 1421507 * 1024   # the batched call (all three projections)
 TRAFFIC_SOURCE = "recorded constant from profiles/bench_c3_mlp7b_counters.txt (rocprofv3 FETCH_SIZE/WRITE_SIZE, copy-calibrated), not measured in this run"
 HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published
 LR = 2e-4
