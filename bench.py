@@ -255,6 +255,7 @@ def tile_timestamps(cfg, layer, run_step, settle: int):
     torch.cuda.synchronize()
     lib.sasq_ts_set_buffer(None)
     t = buf.cpu().numpy().reshape(max_wgs, 16)
+    wg_id = np.nonzero(t[:, 0] != 0)[0]
     t = t[t[:, 0] != 0]
     cyc, wall = t[:, [0, 2, 4, 6, 8]].astype(np.float64), t[:, [1, 3, 5, 7, 9]].astype(np.float64)
     K, half = t[:, 14], t[:, 15]
@@ -264,6 +265,23 @@ def tile_timestamps(cfg, layer, run_step, settle: int):
            "config": cfg.name, "workgroups": int(len(t)), "kernel_span_us": round(span_us, 1),
            "sum_of_tile_times_over_256_us": round(float(total_us.sum()) / 256.0, 1),
            "shader_clock_ghz": round(float(np.median((cyc[:, 4] - cyc[:, 0]) / np.maximum(total_us, 1e-9)) / 1e3), 3), "tiles": []}
+    # Between two tiles on one CU: workgroup ids go to the eight XCDs in turn and an XCD holds 32 workgroups of this
+    # kernel at a time, so within an XCD the (32 + j)-th workgroup to start took the place of the j-th to end.
+    gaps = []
+    for x in range(8):
+        m = wg_id % 8 == x
+        starts, ends = np.sort(wall[m, 0]), np.sort(wall[m, 4])
+        if len(starts) > 32:
+            gaps.append((starts[32:] - ends[:len(starts) - 32]) / 100.0)
+    if gaps:
+        g = np.concatenate(gaps)
+        out["between_tiles_us"] = {"median": round(float(np.median(g)), 2), "p10": round(float(np.percentile(g, 10)), 2),
+                                   "p90": round(float(np.percentile(g, 90)), 2), "count": int(len(g)),
+                                   "note": "end of a workgroup's last stamp to the first stamp of the workgroup that took its place "
+                                           "(matched by order within each XCD; the realtime counter ticks every 10 ns)"}
+    last = np.sort(wall[:, 4])[-256:] if len(wall) >= 256 else wall[:, 4]
+    out["idle_at_the_end_us"] = round(float((wall[:, 4].max() - last).mean() / 100.0), 1)   # mean over the CUs' last tiles
+    out["xcd_done_before_the_end_us"] = [round(float((wall[:, 4].max() - wall[wg_id % 8 == x, 4].max()) / 100.0), 1) for x in range(8)]
     for k in sorted(set(K.tolist())):
         for h in (0, 1, 2):
             m = (K == k) & (half == h)
