@@ -28,6 +28,9 @@
  *   - Workspaces come from sasq_workspace_init(): a workspace is caller-owned device memory
  *     that must have been passed ONCE to sasq_workspace_init before its first use, may be reused
  *     by any number of later calls, and must not be used by two calls that can overlap in time.
+ *   - Graph capture: an entry point only launches kernels on the caller's stream (no allocation,
+ *     no copy, no memset, no synchronisation), so calls may be recorded into a HIP graph and
+ *     replayed; items arrays and other host arguments are read before the call returns.
  *
  * Numerical contract (the paper gives real-number formulas; these make them bit-level)
  *   - round(x/s) is round-half-to-even of the exact product x * inv_s, inv_s = fl32(1/s).

@@ -77,3 +77,83 @@ def test_scale_training_step_stage_by_stage(dtype, fmt, shape):
                              np.zeros(1, np.float32), np.zeros(1, np.float32), 1, 1e-3)
     assert np.allclose(s_new.cpu().numpy(), upd[0], rtol=2e-6, atol=0)     # fp32 kernel, fp64-evaluated oracle
     assert float(s_new.item()) != float(s)
+
+
+def test_batched_step_replays_from_a_hip_graph():
+    """The library allocates nothing, copies nothing and clears nothing on its own, so the whole batched pass
+    (fake-quant forward and backward of every input, SGD on the scales, static linears) can be captured into a
+    HIP graph.  Three replays, with eager library calls and synchronisations between them, must leave exactly
+    what three eager passes leave: outputs, ds and the trained scales, bit for bit (the scales change with
+    every pass, so a replay that reused stale state would show)."""
+    dtype, tdt = "f16", TDT["f16"]
+    shapes = [(300, 384, 256), (300, 256, 256), (200, 520, 192)]       # (M, N, K); the first two share their input
+    xb = [wl.random_bits(95, "gx0", (300, 256), dtype, gain=2.0), None, wl.random_bits(95, "gx2", (200, 192), dtype, gain=2.0)]
+    xb[1] = xb[0]
+    x_d = [to_dev(xb[0], dtype), None, to_dev(xb[2], dtype)]
+    x_d[1] = x_d[0]
+    dy_d = [to_dev(wl.random_bits(95, f"gdy{i}", (sh[0], sh[2]), dtype, gain=0.01), dtype) for i, sh in enumerate(shapes)]
+    s0 = [np.float32(oracle.absmax_scale(xb[i], 8, dtype) * (0.5 + 0.1 * i)) for i in range(3)]
+    wq_d, sw_d = [], []
+    for i, (M, N, K) in enumerate(shapes):
+        wq, s_w = oracle.quantize_weight(wl.random_f32(95, f"gw{i}", (N, K), 0.02), "int8")
+        wq_d.append(torch.from_numpy(wq).cuda()); sw_d.append(torch.from_numpy(s_w).cuda())
+    s_all = torch.zeros(3, dtype=torch.float32, device="cuda")
+    ds_all = torch.zeros(3, dtype=torch.float32, device="cuda")
+    xhat = [torch.empty_like(x) for x in x_d]
+    dx = [torch.empty_like(x) for x in x_d]
+    y = [torch.empty((M, N), dtype=tdt, device="cuda") for (M, N, K) in shapes]
+    fwd_items = [(x_d[i], s_all[i:i + 1], xhat[i]) for i in range(3)]
+    bwd_items = [(x_d[i], dy_d[i], s_all[i:i + 1], dx[i], ds_all[i:i + 1]) for i in range(3)]
+    lin_items = [(x_d[i], s_all[i:i + 1], wq_d[i], sw_d[i], None, y[i]) for i in range(3)]
+    ws_bwd = B.new_workspace(B.sasq_fakequant_bwd_batch_workspace(3))
+    ws_lin = B.new_workspace(B.sasq_static_linear_batch_workspace(lin_items, B.SASQ_W_INT8))
+
+    def one_pass():
+        B.sasq_fakequant_fwd_batch(fwd_items, 8)
+        B.sasq_fakequant_bwd_batch(bwd_items, ws_bwd, 8)
+        B.sasq_scale_sgd_vec(s_all, ds_all, 2e-4)
+        B.sasq_static_linear_batch(lin_items, B.SASQ_W_INT8, ws_lin)
+
+    def reset():
+        s_all.copy_(torch.tensor([float(v) for v in s0]))
+        for t in xhat + dx + y:
+            t.fill_(float("nan"))
+        ds_all.fill_(float("nan"))
+        torch.cuda.synchronize()
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [to_bits(t).copy() for t in xhat + dx + y] + [s_all.cpu().numpy().copy(), ds_all.cpu().numpy().copy()]
+
+    reset()
+    eager = []
+    for _ in range(3):
+        one_pass()
+        eager.append(snapshot())
+    assert not np.array_equal(eager[0][-2], eager[1][-2]), "the scales move from pass to pass"
+
+    reset()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        one_pass()                                  # warm-up on the capture stream (PyTorch's capture protocol)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            one_pass()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+
+    scratch = torch.empty_like(x_d[2])
+    ws1 = B.new_workspace(B.sasq_fakequant_bwd_workspace(200, 192))
+    ds1 = torch.zeros(1, dtype=torch.float32, device="cuda")
+    reset()
+    for k in range(3):
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(got, eager[k]):
+            assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), f"replay {k + 1} differs from eager pass {k + 1}"
+        # the program's own eager work between replays
+        B.sasq_fakequant_fwd(x_d[2], s_all[2:3], scratch, None, 8)
+        B.sasq_fakequant_bwd(x_d[2], dy_d[2], s_all[2:3], scratch, ds1, ws1, 8)
+        torch.cuda.synchronize()
